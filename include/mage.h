@@ -1,0 +1,116 @@
+/*
+ * mage.h -- C ABI of the MI355X (gfx950) implementation of the MAGE hot path
+ * ([MASK]-Guided Sparse Attention for block-diffusion LLM decoding, arxiv 2602.14209).
+ *
+ * Notation (the paper's): B block size, Hq query heads, Hkv KV heads, G = Hq/Hkv query
+ * heads per KV group, d head dimension, L cached prefix length (the paper's N), k budget,
+ * T denoising steps per block.  Query head g belongs to KV head g / G (contiguous groups).
+ *
+ * Conventions that hold for every entry point
+ *   - Every data pointer is a DEVICE pointer (HBM), row-major and contiguous, 16-byte
+ *     aligned.  `shape` is a HOST pointer.  `hip_stream` is a hipStream_t passed as void*
+ *     (NULL = the default stream).
+ *   - The caller owns every buffer, including the workspace; the library never allocates,
+ *     never frees and never synchronises: it validates its arguments on the host, enqueues
+ *     kernels on `hip_stream` and returns.  Results are complete when the stream reaches the
+ *     point after the call.  Two calls that share a workspace must be ordered (same stream,
+ *     or an event between them).
+ *   - Return value: MAGE_OK or a negative mage_status.  Argument errors are detected before
+ *     anything is launched; in that case no buffer is touched.
+ *   - Element type of q / k_cache / v_cache / k_blk / v_blk is shape->dtype: MAGE_F32
+ *     (float) or MAGE_BF16 (bfloat16 bit patterns, uint16).  Arithmetic accumulates in fp32;
+ *     `out`, `lse_out`, `alpha_out` are fp32; indices are int32.
+ *   - T is not an argument: the caller invokes mage_sparse_attn once per denoising step
+ *     2..T with the index set that mage_select produced at step 1 (Alg. 1, Phase 2).
+ *   - Supported: d in {64, 128}; Hq % Hkv == 0; 1 <= k <= L <= 2^30; B*G <= 256 for
+ *     mage_select with MAGE_BF16.
+ */
+#ifndef MAGE_H
+#define MAGE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { MAGE_F32 = 0, MAGE_BF16 = 1 } mage_dtype;
+
+typedef enum {
+    MAGE_OK = 0,
+    MAGE_ERR_NULL = -1,        /* a required pointer is NULL */
+    MAGE_ERR_SHAPE = -2,       /* B, Hq, Hkv, d, L or k <= 0; Hq % Hkv != 0; k > L */
+    MAGE_ERR_UNSUPPORTED = -3, /* d not in {64,128}; unknown dtype; L > 2^30; B*G too large */
+    MAGE_ERR_WORKSPACE = -4,   /* workspace NULL or smaller than mage_workspace_bytes() */
+    MAGE_ERR_HIP = -5,         /* a kernel launch reported an error */
+    MAGE_ERR_ALIGN = -6        /* a data pointer is not 16-byte aligned */
+} mage_status;
+
+/* Problem geometry of one layer and one block (Alg. 1 "Require: cache C, B, k, T"). */
+typedef struct {
+    int B;       /* block size: queries per block */
+    int Hq;      /* query heads */
+    int Hkv;     /* KV heads */
+    int d;       /* head dimension */
+    int64_t L;   /* cached prefix length */
+    int k;       /* selection budget per KV head (ignored by mage_exact_attn, which only needs k >= 1) */
+    int dtype;   /* mage_dtype of q / K / V */
+} mage_shape;
+
+/* Library version (major*10000 + minor*100 + patch).  Host only. */
+int mage_version(void);
+
+/* Static, never-freed description of a status code.  Host only. */
+const char *mage_status_string(int status);
+
+/* Bytes of device workspace that any of the three calls below needs for `shape`
+ * (the maximum over them).  Host only, pure.  Returns 0 if `shape` is invalid. */
+size_t mage_workspace_bytes(const mage_shape *shape);
+
+/*
+ * Step-1 selection (Alg. 1, select stream; Sec. 4 Phase 1, Eq. 5; Eq. 2 per-block form).
+ *   A[g,q,j]   = softmax over the L prefix positions j of  q1[q,g,:].k_cache[j,g/G,:] / sqrt(d)
+ *   alpha[h,j] = 1/(G*B) * sum_{g in group(h)} sum_q A[g,q,j]
+ *   S[h]       = the k positions j with the largest alpha[h,j]; equal values: smaller j first
+ * In:  q1 [B,Hq,d] (the All-[MASK] block's queries), k_cache [L,Hkv,d].
+ * Out: idx_out [Hkv,k] int32, each row ascending in j;
+ *      alpha_out [Hkv,L] fp32, nullable (the averaged probabilities that were ranked).
+ * The ranking is taken on the fp32 alpha the kernels computed.
+ */
+int mage_select(const mage_shape *shape, const void *q1, const void *k_cache,
+                int32_t *idx_out, float *alpha_out,
+                void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Exact attention of the block over the whole cache plus the block itself (Alg. 1 main
+ * stream "Attn(Q,K,V,C)"; also the Exact baseline of Sec. 5):
+ *   out[q,g,:] = softmax_j( [q.K_cache^T ; q.K_blk^T] / sqrt(d) ) . [V_cache ; V_blk]
+ * one softmax over L + B keys of KV head g/G, in-block part bidirectional (no mask).
+ * In:  q [B,Hq,d]; k_cache, v_cache [L,Hkv,d]; k_blk, v_blk [B,Hkv,d] (both NULL = no
+ *      in-block keys).
+ * Out: out [B,Hq,d] fp32; lse_out [B,Hq] fp32, nullable (natural-log sum-exp of the logits).
+ */
+int mage_exact_attn(const mage_shape *shape, const void *q, const void *k_cache, const void *v_cache,
+                    const void *k_blk, const void *v_blk,
+                    float *out, float *lse_out,
+                    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Sparse attention of one denoising step (Alg. 1 Phase 2 "SparseAttn(Q_h,K_h,V_h,C[S])";
+ * Sec. 4 Phase 2): as mage_exact_attn, with the cache restricted, per KV head h, to the k
+ * positions idx[h,:]; one softmax over k + B keys.
+ * In:  idx [Hkv,k] int32, every entry in [0,L) (a precondition: not checked on the device;
+ *      an out-of-range entry reads out of bounds).  Order within a row is free; duplicates
+ *      are attended as many times as they appear.
+ * Out: out [B,Hq,d] fp32; lse_out [B,Hq] fp32, nullable.
+ */
+int mage_sparse_attn(const mage_shape *shape, const void *q, const void *k_cache, const void *v_cache,
+                     const int32_t *idx, const void *k_blk, const void *v_blk,
+                     float *out, float *lse_out,
+                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MAGE_H */

@@ -1,0 +1,135 @@
+"""Thin ctypes binding of libmage.so (argument marshalling only).
+
+Every step of the MAGE hot path runs inside the HIP library; PyTorch is used for
+device memory and streams.  The functions carry the names of the C entry points
+declared in ``include/mage.h`` and take torch CUDA(HIP) tensors in place of raw
+device pointers.  There is no CPU fallback: if the library is missing, importing
+or calling this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch  # noqa: F401  (must be imported first: libmage.so binds to the HIP runtime torch loaded)
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmage.so")
+
+MAGE_F32 = 0
+MAGE_BF16 = 1
+MAGE_OK = 0
+
+EXPORTS = ("mage_version", "mage_status_string", "mage_workspace_bytes",
+           "mage_select", "mage_exact_attn", "mage_sparse_attn")
+
+
+class mage_shape(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int), ("Hq", ctypes.c_int), ("Hkv", ctypes.c_int), ("d", ctypes.c_int),
+                ("L", ctypes.c_int64), ("k", ctypes.c_int), ("dtype", ctypes.c_int)]
+
+
+class MageError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libmage.so (built in-tree by ``paper_2602_14209_amd.build``); raises if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} not found: build it with `python -m paper_2602_14209_amd.build` "
+                "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, sz = ctypes.c_void_p, ctypes.c_size_t
+        shp = ctypes.POINTER(mage_shape)
+        L.mage_version.restype = ctypes.c_int
+        L.mage_status_string.restype = ctypes.c_char_p
+        L.mage_status_string.argtypes = [ctypes.c_int]
+        L.mage_workspace_bytes.restype = sz
+        L.mage_workspace_bytes.argtypes = [shp]
+        L.mage_select.restype = ctypes.c_int
+        L.mage_select.argtypes = [shp, vp, vp, vp, vp, vp, sz, vp]
+        L.mage_exact_attn.restype = ctypes.c_int
+        L.mage_exact_attn.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.mage_sparse_attn.restype = ctypes.c_int
+        L.mage_sparse_attn.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().mage_status_string(int(status)).decode()
+
+
+def make_shape(B: int, Hq: int, Hkv: int, d: int, L: int, k: int, dtype) -> mage_shape:
+    if isinstance(dtype, str):
+        dt = {"f32": MAGE_F32, "bf16": MAGE_BF16}[dtype]
+    elif isinstance(dtype, torch.dtype):
+        dt = {torch.float32: MAGE_F32, torch.bfloat16: MAGE_BF16}[dtype]
+    else:
+        dt = int(dtype)
+    return mage_shape(B, Hq, Hkv, d, L, k, dt)
+
+
+def mage_workspace_bytes(shape: mage_shape) -> int:
+    return int(lib().mage_workspace_bytes(ctypes.byref(shape)))
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("device tensor expected")
+    if not t.is_contiguous():
+        raise ValueError("contiguous tensor expected")
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+def _wsize(ws: Optional[torch.Tensor]) -> int:
+    return 0 if ws is None else ws.numel() * ws.element_size()
+
+
+def mage_select(shape: mage_shape, q1, k_cache, idx_out, alpha_out, workspace, stream=None) -> int:
+    """Step-1 selection; see include/mage.h.  Returns the status code (0 = ok)."""
+    return lib().mage_select(ctypes.byref(shape), _ptr(q1), _ptr(k_cache), _ptr(idx_out), _ptr(alpha_out),
+                             _ptr(workspace), _wsize(workspace), _stream(stream))
+
+
+def mage_exact_attn(shape: mage_shape, q, k_cache, v_cache, k_blk, v_blk, out, lse_out, workspace, stream=None) -> int:
+    """Exact attention over cache + block; see include/mage.h."""
+    return lib().mage_exact_attn(ctypes.byref(shape), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_blk), _ptr(v_blk),
+                                 _ptr(out), _ptr(lse_out), _ptr(workspace), _wsize(workspace), _stream(stream))
+
+
+def mage_sparse_attn(shape: mage_shape, q, k_cache, v_cache, idx, k_blk, v_blk, out, lse_out, workspace,
+                     stream=None) -> int:
+    """Sparse attention of one denoising step; see include/mage.h."""
+    return lib().mage_sparse_attn(ctypes.byref(shape), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(idx), _ptr(k_blk),
+                                  _ptr(v_blk), _ptr(out), _ptr(lse_out), _ptr(workspace), _wsize(workspace),
+                                  _stream(stream))
+
+
+def check(status: int, where: str = "mage") -> None:
+    if status != MAGE_OK:
+        raise MageError(status, where)
+
+
+def alloc_workspace(shape: mage_shape, device="cuda") -> torch.Tensor:
+    n = mage_workspace_bytes(shape)
+    if n == 0:
+        raise ValueError("invalid shape")
+    return torch.empty(n, dtype=torch.uint8, device=device)

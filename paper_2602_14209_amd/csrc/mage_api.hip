@@ -1,0 +1,202 @@
+// C ABI of the MAGE hot path (declared in include/mage.h): host-side validation, launch plans,
+// workspace carving and kernel dispatch.  Nothing here allocates or synchronises.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "plan.hpp"
+
+namespace mage {
+hipError_t bf16_attn(const KernelArgs &a, int d, int waves, int row_groups, bool gather, hipStream_t stream);
+hipError_t bf16_stats(const KernelArgs &a, int d, int waves, int row_groups, hipStream_t stream);
+hipError_t bf16_colsum(const KernelArgs &a, int d, int waves, hipStream_t stream);
+hipError_t f32_attn(const KernelArgs &a, int d, int row_groups, bool gather, hipStream_t stream);
+hipError_t f32_stats(const KernelArgs &a, int d, int row_groups, hipStream_t stream);
+hipError_t f32_colsum(const KernelArgs &a, int d, hipStream_t stream);
+hipError_t launch_combine(const KernelArgs &a, int d, hipStream_t stream);
+hipError_t launch_lse(const KernelArgs &a, float *lse2_out, hipStream_t stream);
+hipError_t launch_topk(const float *alpha, int Hkv, long long L, int k, int32_t *idx_out, hipStream_t stream);
+}  // namespace mage
+
+using namespace mage;
+
+namespace {
+
+constexpr int64_t kMaxL = (int64_t)1 << 30;
+
+int check_shape(const mage_shape *s, bool need_k)
+{
+    if (!s) return MAGE_ERR_NULL;
+    if (s->B <= 0 || s->Hq <= 0 || s->Hkv <= 0 || s->d <= 0 || s->L <= 0) return MAGE_ERR_SHAPE;
+    if (s->Hq % s->Hkv != 0) return MAGE_ERR_SHAPE;
+    if (need_k && (s->k <= 0 || (int64_t)s->k > s->L)) return MAGE_ERR_SHAPE;
+    if (s->d != 64 && s->d != 128) return MAGE_ERR_UNSUPPORTED;
+    if (s->dtype != MAGE_F32 && s->dtype != MAGE_BF16) return MAGE_ERR_UNSUPPORTED;
+    if (s->L > kMaxL) return MAGE_ERR_UNSUPPORTED;
+    if ((int64_t)(s->Hq / s->Hkv) * s->B > (1 << 20)) return MAGE_ERR_UNSUPPORTED;
+    return MAGE_OK;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+KernelArgs base_args(const mage_shape &s, const SplitPlan &p)
+{
+    KernelArgs a{};
+    a.B = s.B;
+    a.Hq = s.Hq;
+    a.Hkv = s.Hkv;
+    a.G = s.Hq / s.Hkv;
+    a.R = p.R;
+    a.rpad = p.rpad;
+    a.L = s.L;
+    a.kps = p.kps;
+    a.n_split = p.n_split;
+    a.blk_split = p.blk_split;
+    a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)s.d));
+    a.inv_rows = (float)(1.0 / (double)p.R);
+    return a;
+}
+
+void carve_partials(const mage_shape &s, const SplitPlan &p, void *workspace, KernelArgs &a)
+{
+    const size_t rows = (size_t)s.Hkv * p.n_split * p.rpad;
+    char *w = static_cast<char *>(workspace);
+    a.part_o = reinterpret_cast<float *>(w);
+    w += align_up(rows * s.d * sizeof(float), 256);
+    a.part_m = reinterpret_cast<float *>(w);
+    w += align_up(rows * sizeof(float), 256);
+    a.part_l = reinterpret_cast<float *>(w);
+}
+
+int run_attention(const mage_shape *shape, const SplitPlan &p, bool gather,
+                  const void *q, const void *k_cache, const void *v_cache, const int32_t *idx,
+                  const void *k_blk, const void *v_blk, float *out, float *lse_out,
+                  void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!q || !k_cache || !v_cache || !out || (gather && !idx)) return MAGE_ERR_NULL;
+    if ((k_blk == nullptr) != (v_blk == nullptr)) return MAGE_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(k_blk) || !aligned16(v_blk) ||
+        !aligned16(out) || !aligned16(workspace))
+        return MAGE_ERR_ALIGN;
+    if (p.n_split > 1 && (!workspace || workspace_bytes < partial_bytes(*shape, p))) return MAGE_ERR_WORKSPACE;
+
+    KernelArgs a = base_args(*shape, p);
+    a.q = q;
+    a.kc = k_cache;
+    a.vc = v_cache;
+    // with no in-block keys the block pointers are never dereferenced; keep them valid anyway
+    a.kblk = k_blk ? k_blk : k_cache;
+    a.vblk = v_blk ? v_blk : v_cache;
+    a.n_blk = k_blk ? shape->B : 0;
+    a.idx = idx;
+    a.nc = gather ? (long long)shape->k : (long long)shape->L;
+    a.out = out;
+    a.lse_out = lse_out;
+    if (p.n_split > 1) carve_partials(*shape, p, workspace, a);
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = shape->dtype == MAGE_BF16 ? bf16_attn(a, shape->d, p.waves, p.row_groups, gather, stream)
+                                             : f32_attn(a, shape->d, p.row_groups, gather, stream);
+    if (e != hipSuccess) return MAGE_ERR_HIP;
+    if (p.n_split > 1) {
+        e = launch_combine(a, shape->d, stream);
+        if (e != hipSuccess) return MAGE_ERR_HIP;
+    }
+    return MAGE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int mage_version(void) { return 100; }
+
+const char *mage_status_string(int status)
+{
+    switch (status) {
+    case MAGE_OK: return "ok";
+    case MAGE_ERR_NULL: return "a required pointer is NULL";
+    case MAGE_ERR_SHAPE: return "invalid shape (non-positive size, Hq % Hkv != 0, or k > L)";
+    case MAGE_ERR_UNSUPPORTED: return "unsupported configuration (d not in {64,128}, unknown dtype, L > 2^30, or B*G too large)";
+    case MAGE_ERR_WORKSPACE: return "workspace missing or smaller than mage_workspace_bytes()";
+    case MAGE_ERR_HIP: return "HIP reported a launch error";
+    case MAGE_ERR_ALIGN: return "a data pointer is not 16-byte aligned";
+    default: return "unknown status";
+    }
+}
+
+size_t mage_workspace_bytes(const mage_shape *shape)
+{
+    if (check_shape(shape, true) != MAGE_OK) return 0;
+    const SplitPlan dense = plan_dense(*shape), sparse = plan_sparse(*shape);
+    size_t need = partial_bytes(*shape, dense);
+    const size_t b = partial_bytes(*shape, sparse);
+    if (b > need) need = b;
+    const size_t c = select_layout(*shape, dense).bytes;
+    if (c > need) need = c;
+    return need;
+}
+
+int mage_select(const mage_shape *shape, const void *q1, const void *k_cache,
+                int32_t *idx_out, float *alpha_out,
+                void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    int rc = check_shape(shape, true);
+    if (rc != MAGE_OK) return rc;
+    if (!q1 || !k_cache || !idx_out) return MAGE_ERR_NULL;
+    const SplitPlan p = plan_dense(*shape);
+    if (shape->dtype == MAGE_BF16 && p.row_groups != 1) return MAGE_ERR_UNSUPPORTED;
+    if (!aligned16(q1) || !aligned16(k_cache) || !aligned16(workspace) || !aligned16(alpha_out)) return MAGE_ERR_ALIGN;
+    const SelectLayout lay = select_layout(*shape, p);
+    if (!workspace || workspace_bytes < lay.bytes) return MAGE_ERR_WORKSPACE;
+
+    char *w = static_cast<char *>(workspace);
+    KernelArgs a = base_args(*shape, p);
+    a.q = q1;
+    a.kc = k_cache;
+    a.vc = k_cache;
+    a.kblk = k_cache;
+    a.vblk = k_cache;
+    a.n_blk = 0;
+    a.blk_split = -1;
+    a.nc = shape->L;
+    a.part_m = reinterpret_cast<float *>(w + lay.part_m);
+    a.part_l = reinterpret_cast<float *>(w + lay.part_l);
+    float *lse2 = reinterpret_cast<float *>(w + lay.lse2);
+    a.lse2 = lse2;
+    a.alpha = alpha_out ? alpha_out : reinterpret_cast<float *>(w + lay.alpha);
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const bool bf = shape->dtype == MAGE_BF16;
+    hipError_t e = bf ? bf16_stats(a, shape->d, p.waves, p.row_groups, stream) : f32_stats(a, shape->d, p.row_groups, stream);
+    if (e != hipSuccess) return MAGE_ERR_HIP;
+    e = launch_lse(a, lse2, stream);
+    if (e != hipSuccess) return MAGE_ERR_HIP;
+    e = bf ? bf16_colsum(a, shape->d, p.waves, stream) : f32_colsum(a, shape->d, stream);
+    if (e != hipSuccess) return MAGE_ERR_HIP;
+    e = launch_topk(a.alpha, shape->Hkv, shape->L, shape->k, idx_out, stream);
+    if (e != hipSuccess) return MAGE_ERR_HIP;
+    return MAGE_OK;
+}
+
+int mage_exact_attn(const mage_shape *shape, const void *q, const void *k_cache, const void *v_cache,
+                    const void *k_blk, const void *v_blk, float *out, float *lse_out,
+                    void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    const int rc = check_shape(shape, false);
+    if (rc != MAGE_OK) return rc;
+    return run_attention(shape, plan_dense(*shape), false, q, k_cache, v_cache, nullptr, k_blk, v_blk, out, lse_out,
+                         workspace, workspace_bytes, hip_stream);
+}
+
+int mage_sparse_attn(const mage_shape *shape, const void *q, const void *k_cache, const void *v_cache,
+                     const int32_t *idx, const void *k_blk, const void *v_blk, float *out, float *lse_out,
+                     void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    const int rc = check_shape(shape, true);
+    if (rc != MAGE_OK) return rc;
+    return run_attention(shape, plan_sparse(*shape), true, q, k_cache, v_cache, idx, k_blk, v_blk, out, lse_out,
+                         workspace, workspace_bytes, hip_stream);
+}
+
+}  // extern "C"

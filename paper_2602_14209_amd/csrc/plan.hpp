@@ -1,0 +1,129 @@
+// Host-side launch plans and workspace layout for the MAGE kernels (gfx950).
+//
+// A plan is a pure function of the problem geometry, so mage_workspace_bytes() and the
+// launchers always agree.  Partial results of split attention live in the caller's workspace:
+//   part_o [Hkv][n_split][rpad][d] fp32  unnormalised weighted value sums
+//   part_m [Hkv][n_split][rpad]    fp32  running maximum of the log2-scaled logits
+//   part_l [Hkv][n_split][rpad]    fp32  sum of exp2(logit2 - part_m)
+#pragma once
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/mage.h"
+
+namespace mage {
+
+constexpr int kBf16Tile = 64;   // keys per LDS tile, MFMA path
+constexpr int kF32Tile = 32;    // keys per LDS tile, fp32 vector path
+constexpr int kF32Rows = 64;    // query rows per workgroup, fp32 vector path
+constexpr int kTargetWorkgroups = 512;   // 2 per CU on 256 CUs
+
+struct SplitPlan {
+    int R;            // query rows sharing one KV head: G*B
+    int rows_per_wg;  // rows one workgroup covers
+    int row_groups;   // workgroups along the row axis
+    int rpad;         // row_groups * rows_per_wg
+    int waves;        // wavefronts per workgroup
+    int tile;         // keys per tile
+    int kps;          // cache keys per split (multiple of tile)
+    int n_split;      // splits along the key axis, including a block-only split if any
+    int blk_split;    // split that also attends the in-block keys
+};
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+inline void plan_rows(const mage_shape &s, SplitPlan &p)
+{
+    p.R = (s.Hq / s.Hkv) * s.B;
+    if (s.dtype == MAGE_BF16) {
+        p.waves = p.R > 128 ? 8 : 4;
+        p.rows_per_wg = p.waves * 32;
+        p.tile = kBf16Tile;
+    } else {
+        p.waves = 4;
+        p.rows_per_wg = kF32Rows;
+        p.tile = kF32Tile;
+    }
+    p.row_groups = ceil_div(p.R, p.rows_per_wg);
+    p.rpad = p.row_groups * p.rows_per_wg;
+}
+
+// Dense pass over all L cache keys (exact attention; both passes of selection).
+inline SplitPlan plan_dense(const mage_shape &s)
+{
+    SplitPlan p{};
+    plan_rows(s, p);
+    const int64_t tiles = (s.L + p.tile - 1) / p.tile;
+    const int64_t target = kTargetWorkgroups / ((int64_t)s.Hkv * p.row_groups) > 0
+                               ? kTargetWorkgroups / ((int64_t)s.Hkv * p.row_groups) : 1;
+    int64_t tps = (tiles + target - 1) / target;     // tiles per split
+    const int64_t min_tps = s.dtype == MAGE_BF16 ? 4 : 8;
+    if (tps < min_tps) tps = min_tps;
+    p.n_split = (int)((tiles + tps - 1) / tps);
+    p.kps = (int)(tps * p.tile);
+    p.blk_split = p.n_split - 1;
+    return p;
+}
+
+// Sparse step: k gathered cache keys, in-block keys in a split of their own when k is large
+// enough for the gather splits to be full tiles.
+inline SplitPlan plan_sparse(const mage_shape &s)
+{
+    SplitPlan p{};
+    plan_rows(s, p);
+    const int64_t tiles = ((int64_t)s.k + p.tile - 1) / p.tile;
+    const int64_t max_splits = 8;
+    const int64_t tps = (tiles + max_splits - 1) / max_splits;
+    const int n_cache = (int)((tiles + tps - 1) / tps);
+    p.kps = (int)(tps * p.tile);
+    if (s.k >= p.tile) {
+        p.n_split = n_cache + 1;
+        p.blk_split = n_cache;
+    } else {
+        p.n_split = n_cache;
+        p.blk_split = n_cache - 1;
+    }
+    return p;
+}
+
+inline size_t partial_bytes(const mage_shape &s, const SplitPlan &p)
+{
+    const size_t rows = (size_t)s.Hkv * p.n_split * p.rpad;
+    return align_up(rows * s.d * sizeof(float), 256) + 2 * align_up(rows * sizeof(float), 256);
+}
+
+struct SelectLayout {
+    size_t part_m, part_l, lse2, alpha, bytes;
+};
+
+inline SelectLayout select_layout(const mage_shape &s, const SplitPlan &p)
+{
+    SelectLayout l{};
+    const size_t rows = (size_t)s.Hkv * p.n_split * p.rpad;
+    size_t off = 0;
+    l.part_m = off; off += align_up(rows * sizeof(float), 256);
+    l.part_l = off; off += align_up(rows * sizeof(float), 256);
+    l.lse2 = off;   off += align_up((size_t)s.Hkv * p.rpad * sizeof(float), 256);
+    l.alpha = off;  off += align_up((size_t)s.Hkv * (size_t)s.L * sizeof(float), 256);
+    l.bytes = off;
+    return l;
+}
+
+// Arguments shared by the attention / statistics / column-sum kernels of both element types.
+struct KernelArgs {
+    const void *q, *kc, *vc, *kblk, *vblk;
+    const int32_t *idx;      // gather indices [Hkv][nc] or nullptr
+    float *out, *lse_out;    // final outputs (used directly when n_split == 1)
+    float *part_o, *part_m, *part_l;
+    const float *lse2;       // column-sum pass: per-row log2-domain log-sum-exp [Hkv][rpad]
+    float *alpha;            // column-sum pass: [Hkv][L]
+    int B, Hq, Hkv, G, R, rpad;
+    long long L;             // rows in the cache
+    long long nc;            // cache keys attended: L (dense) or k (gather)
+    int kps, n_split, blk_split, n_blk;
+    float scale_log2;        // log2(e) / sqrt(d)
+    float inv_rows;          // 1 / (G*B)
+};
+
+}  // namespace mage

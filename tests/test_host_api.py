@@ -1,0 +1,80 @@
+"""Host-side checks that need no GPU: the C-ABI library loads, exports every declared symbol,
+validates its arguments before launching anything, and sizes its workspace consistently."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2602_14209_amd import binding as mb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "mage.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mage_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = mb.lib()
+    names = _declared_symbols()
+    assert set(names) == set(mb.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+    assert lib.mage_version() >= 100
+
+
+def test_status_strings():
+    for code in range(0, -7, -1):
+        s = mb.status_string(code)
+        assert s and s != "unknown status"
+    assert mb.status_string(-99) == "unknown status"
+
+
+def test_workspace_bytes():
+    s = mb.make_shape(32, 32, 8, 128, 131072, 512, "bf16")
+    n = mb.mage_workspace_bytes(s)
+    assert n >= 8 * 131072 * 4          # holds alpha[Hkv,L]
+    assert n < 1 << 30
+    assert mb.mage_workspace_bytes(mb.make_shape(32, 32, 8, 128, 131072, 0, "bf16")) == 0
+    assert mb.mage_workspace_bytes(mb.make_shape(32, 30, 8, 128, 131072, 512, "bf16")) == 0
+    assert mb.mage_workspace_bytes(mb.make_shape(4, 4, 1, 64, 2048, 64, "f32")) > 0
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(B=0), -2), (dict(Hq=0), -2), (dict(Hkv=0), -2), (dict(L=0), -2), (dict(k=0), -2),
+    (dict(Hq=30), -2),              # Hq % Hkv != 0
+    (dict(k=5000, L=4096), -2),     # k > L
+    (dict(d=96), -3), (dict(dtype=7), -3), (dict(L=(1 << 30) + 1), -3),
+])
+def test_argument_validation_happens_before_any_launch(kw, code):
+    base = dict(B=32, Hq=32, Hkv=8, d=128, L=4096, k=512, dtype=1)
+    base.update(kw)
+    s = mb.make_shape(**base)
+    fake = ctypes.c_void_p(0x1000)      # never dereferenced: validation fails first
+    L = mb.lib()
+    assert L.mage_select(ctypes.byref(s), fake, fake, fake, None, fake, 1 << 40, None) == code
+    assert L.mage_sparse_attn(ctypes.byref(s), fake, fake, fake, fake, fake, fake, fake, None, fake, 1 << 40, None) == code
+    if "k" not in kw:
+        assert L.mage_exact_attn(ctypes.byref(s), fake, fake, fake, fake, fake, fake, None, fake, 1 << 40, None) == code
+
+
+def test_null_alignment_and_workspace_errors():
+    s = mb.make_shape(32, 32, 8, 128, 4096, 512, "bf16")
+    L = mb.lib()
+    fake = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1004)
+    big = 1 << 40
+    assert L.mage_select(None, fake, fake, fake, None, fake, big, None) == -1
+    assert L.mage_select(ctypes.byref(s), None, fake, fake, None, fake, big, None) == -1
+    assert L.mage_select(ctypes.byref(s), fake, fake, None, None, fake, big, None) == -1
+    assert L.mage_select(ctypes.byref(s), odd, fake, fake, None, fake, big, None) == -6
+    assert L.mage_select(ctypes.byref(s), fake, fake, fake, None, fake, 16, None) == -4
+    assert L.mage_select(ctypes.byref(s), fake, fake, fake, None, None, 0, None) == -4
+    assert L.mage_exact_attn(ctypes.byref(s), fake, fake, fake, fake, None, fake, None, fake, big, None) == -1
+    assert L.mage_exact_attn(ctypes.byref(s), fake, fake, odd, fake, fake, fake, None, fake, big, None) == -6
+    assert L.mage_exact_attn(ctypes.byref(s), fake, fake, fake, fake, fake, fake, None, fake, 16, None) == -4
+    assert L.mage_sparse_attn(ctypes.byref(s), fake, fake, fake, None, fake, fake, fake, None, fake, big, None) == -1
+    assert L.mage_sparse_attn(ctypes.byref(s), fake, fake, fake, fake, fake, fake, fake, None, fake, 16, None) == -4
