@@ -1,0 +1,226 @@
+#!/usr/bin/env python3
+"""Benchmark of the MAGE hot path on one MI355X.
+
+One "step" = decoding one block of B tokens through `--layers` layers with T denoising steps at the
+headline workload (config c4: bf16, Hq=32, Hkv=8, d=128, L=131072, B=32, k=512, T=16):
+  phase 1 (step 1)    per layer: mage_exact_attn on the main stream, mage_select on a side stream,
+                      one join at the end of the phase (Alg. 1);
+  phase 2 (steps 2..T) per layer and step: mage_sparse_attn with the layer's index set.
+Every layer has its own K/V cache (distinct buffers, dependent chain), so a layer's gathered rows are
+not cache-resident when it is revisited.  The whole step is captured once in a HIP graph and replayed.
+
+Prints ONE JSON line; `value` is the sparse-step attention time per layer-block (phase 2 time divided
+by layers*(T-1)), inputs resident in HBM.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c4")
+    ap.add_argument("--k", type=int, default=512)
+    ap.add_argument("--layers", type=int, default=28)
+    ap.add_argument("--T", type=int, default=0, help="denoising steps per block (0 = the workload's)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=2602)
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the path needs no exchange between GPUs; "
+              "see DESIGN.md for how it would shard). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    from paper_2602_14209_amd import binding as mb
+    from paper_2602_14209_amd.workloads import CONFIGS, algorithmic_bytes, make_layer_device
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    mb.lib()      # fail loudly if the HIP library is missing
+    w = CONFIGS[args.workload]
+    k = args.k
+    T = args.T or w.T
+    NL = args.layers
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    shape = mb.make_shape(w.B, w.Hq, w.Hkv, w.d, w.L, k, w.dtype)
+
+    layers = [make_layer_device(w, args.seed + 1000 * 4 + l, dev, steps=T) for l in range(NL)]
+    ws_main = mb.alloc_workspace(shape)
+    ws_side = mb.alloc_workspace(shape)
+    idx = [torch.zeros((w.Hkv, k), dtype=torch.int32, device=dev) for _ in range(NL)]
+    out = torch.empty((w.B, w.Hq, w.d), dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+
+    main_s = torch.cuda.Stream(device=dev)
+    side_s = torch.cuda.Stream(device=dev)
+
+    def exact(l, stream):
+        x = layers[l]
+        mb.check(mb.mage_exact_attn(shape, x["q"][0], x["k_cache"], x["v_cache"], x["k_blk"][0], x["v_blk"][0],
+                                    out, None, ws_main, stream), "mage_exact_attn")
+
+    def select(l, stream, ws):
+        x = layers[l]
+        mb.check(mb.mage_select(shape, x["q"][0], x["k_cache"], idx[l], None, ws, stream), "mage_select")
+
+    def sparse(l, t, stream):
+        x = layers[l]
+        mb.check(mb.mage_sparse_attn(shape, x["q"][t], x["k_cache"], x["v_cache"], idx[l], x["k_blk"][t],
+                                     x["v_blk"][t], out, None, ws_main, stream), "mage_sparse_attn")
+
+    def phase1(overlap=True):
+        if overlap:
+            side_s.wait_stream(main_s)
+        for l in range(NL):
+            if overlap:
+                select(l, side_s, ws_side)
+            exact(l, main_s)
+            if not overlap:
+                select(l, main_s, ws_main)
+        if overlap:
+            main_s.wait_stream(side_s)
+
+    def phase2():
+        for t in range(1, T):
+            for l in range(NL):
+                sparse(l, t, main_s)
+
+    def capture(fn):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=main_s):
+            fn()
+        return g
+
+    # index sets must exist before the sparse chain is first replayed
+    with torch.cuda.stream(main_s):
+        phase1(overlap=False)
+    torch.cuda.synchronize()
+
+    graphs = {
+        "step": capture(lambda: (phase1(True), phase2())),
+        "phase1": capture(lambda: phase1(True)),
+        "exact_only": capture(lambda: [exact(l, main_s) for l in range(NL)]),
+        "select_only": capture(lambda: [select(l, main_s, ws_main) for l in range(NL)]),
+        "phase2": capture(phase2),
+    }
+
+    def time_graph(g, reps, warm):
+        for _ in range(warm):
+            g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record(torch.cuda.current_stream())
+        for _ in range(reps):
+            g.replay()
+        e1.record(torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3
+        return e0.elapsed_time(e1) / reps, wall / reps
+
+    K, W = args.steps, args.warmup
+    ms_step, wall_step = time_graph(graphs["step"], K, W)
+    ms = {n: time_graph(g, K, 1)[0] for n, g in graphs.items() if n != "step"}
+
+    n_sparse = NL * (T - 1)
+    sparse_us = ms["phase2"] * 1e3 / n_sparse
+    exact_us = ms["exact_only"] * 1e3 / NL
+    select_us = ms["select_only"] * 1e3 / NL
+    phase1_us = ms["phase1"] * 1e3 / NL
+    ab = algorithmic_bytes(w, k)
+
+    def roof(name, us, nbytes, kernel):
+        gbs = nbytes / (us * 1e-6) / 1e9
+        return {"kernel": kernel, "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "bytes_per_launch": nbytes,
+                "us_per_launch": round(us, 3)}
+
+    rooflines = {
+        "mage_sparse_attn": roof("sparse", sparse_us, ab["sparse_attn"], "attn_bf16_kernel<gather> + combine_kernel"),
+        "mage_exact_attn": roof("exact", exact_us, ab["exact_attn"], "attn_bf16_kernel<dense> + combine_kernel"),
+        "mage_select": roof("select", select_us, ab["select"], "attn_bf16_kernel<stats> + colsum_bf16_kernel + topk_kernel"),
+    }
+
+    result = {
+        "metric": "sparse_step_attn_us_per_layer_block",
+        "value": round(sparse_us, 3),
+        "unit": "us",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": round(ms_step, 4),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: L={w.L} Hq={w.Hq} Hkv={w.Hkv} d={w.d} B={w.B} k={k} T={T}",
+                   "layers": NL, "k": k, "T": T, "launch": "HIP graph replay, dependent chain over distinct layer buffers"},
+        "sparse_step_hbm_gbs": rooflines["mage_sparse_attn"]["achieved"],
+        "select_us": round(select_us, 2),
+        "select_exposed_us": round(phase1_us - exact_us, 2),
+        "exact_attn_us": round(exact_us, 2),
+        "phase1_us_per_layer": round(phase1_us, 2),
+        "block_ms": {"mage": round(ms_step, 4), "exact_baseline_est": round(exact_us * NL * T / 1e3, 4)},
+        "wall_ms_per_step": round(wall_step, 4),
+        "roofline": rooflines["mage_sparse_attn"],
+        "rooflines": rooflines,
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, k, args.seed)
+    print(json.dumps(result), flush=True)
+
+
+def cpu_baseline(w, k, seed):
+    """The CPU oracle, as it stands, on the same workload shape: a full sparse step of one layer-block
+    (the metric's unit) plus, as context, selection and exact attention on a 1/Hkv sample (one KV head)."""
+    import numpy as np
+
+    import oracle
+    from paper_2602_14209_amd.workloads import make_layer
+
+    oracle.build()
+    x = make_layer(w, seed, steps=2)
+    rng = np.random.default_rng(seed)
+    idx = np.stack([np.sort(rng.choice(w.L, k, replace=False)) for _ in range(w.Hkv)]).astype(np.int32)
+    reps = 5
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        oracle.sparse_attn(x["q"][1], x["k_cache"], x["v_cache"], idx, x["k_blk"][1], x["v_blk"][1])
+    sparse_us = (time.perf_counter() - t0) / reps * 1e6
+    G = w.G
+    q1h = np.ascontiguousarray(x["q"][0][:, :G])
+    kh = np.ascontiguousarray(x["k_cache"][:, :1])
+    vh = np.ascontiguousarray(x["v_cache"][:, :1])
+    t0 = time.perf_counter()
+    oracle.select(q1h, kh, k)
+    select_us = (time.perf_counter() - t0) * 1e6 * w.Hkv
+    t0 = time.perf_counter()
+    oracle.exact_attn(q1h, kh, vh, np.ascontiguousarray(x["k_blk"][0][:, :1]), np.ascontiguousarray(x["v_blk"][0][:, :1]))
+    exact_us = (time.perf_counter() - t0) * 1e6 * w.Hkv
+    return {"value": round(sparse_us, 1), "unit": "us", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"sparse step: full layer-block, mean of {reps} runs; select/exact: KV head 0 only, scaled x{w.Hkv}",
+            "select_us": round(select_us, 1), "exact_attn_us": round(exact_us, 1)}
+
+
+if __name__ == "__main__":
+    main()

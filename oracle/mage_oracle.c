@@ -197,14 +197,16 @@ int mage_oracle_select(int B, int Hq, int Hkv, int d, int64_t L, int k,
  *                 idx[kv(g), :] (Alg. 1 Phase 2 "SparseAttn(Q_h,K_h,V_h,C[S])",
  *                 Sec. 4 Phase 2).
  * In both cases one softmax runs over the cache keys kept plus the nb in-block
- * keys (nb = B when k_blk != NULL, else 0), all logits scaled 1/sqrt(d), no mask.
- * q [B,Hq,d]; kc,vc [L,Hkv,d]; idx [Hkv,k]; k_blk,v_blk [B,Hkv,d];
+ * keys (nb = 0 when k_blk == NULL), all logits scaled 1/sqrt(d), no mask.  nb equals B in
+ * the method; it is a separate argument so that a test can evaluate a sample of the B
+ * query rows against the full block.
+ * q [B,Hq,d]; kc,vc [L,Hkv,d]; idx [Hkv,k]; k_blk,v_blk [nb,Hkv,d];
  * out [B,Hq,d] fp32; lse [B,Hq] fp32 (nullable; natural-log sum-exp of the logits).
  */
 int mage_oracle_attn(int B, int Hq, int Hkv, int d, int64_t L,
                      const float *q, const float *kc, const float *vc,
                      const int32_t *idx, int k,
-                     const float *k_blk, const float *v_blk,
+                     const float *k_blk, const float *v_blk, int nb_in,
                      float *out, float *lse)
 {
     if (B <= 0 || Hq <= 0 || Hkv <= 0 || d <= 0 || L <= 0 || Hq % Hkv != 0 || !q || !kc || !vc || !out)
@@ -219,7 +221,9 @@ int mage_oracle_attn(int B, int Hq, int Hkv, int d, int64_t L,
                 return -1;
     const int G = Hq / Hkv;
     const int64_t nc = idx ? (int64_t)k : L;
-    const int nb = k_blk ? B : 0;
+    const int nb = k_blk ? nb_in : 0;
+    if (nb < 0)
+        return -1;
     const int64_t n = nc + nb;
     int fail = 0;
 #pragma omp parallel for schedule(dynamic, 1)

@@ -50,7 +50,7 @@ def _load():
         lib.mage_oracle_attn.restype = ctypes.c_int
         lib.mage_oracle_attn.argtypes = [
             ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int64,
-            _f32p, _f32p, _f32p, _i32p, ctypes.c_int, _f32p, _f32p, _f32p, _f32p]
+            _f32p, _f32p, _f32p, _i32p, ctypes.c_int, _f32p, _f32p, ctypes.c_int, _f32p, _f32p]
         _lib = lib
     return _lib
 
@@ -130,12 +130,16 @@ def _attn(q, k_cache, v_cache, idx, k_blk, v_blk):
         if idx.ndim != 2 or idx.shape[0] != Hkv:
             raise ValueError("idx must be [Hkv,k]")
         k = idx.shape[1]
+    nb = 0
     if k_blk is not None:
-        k_blk, v_blk = _f32(k_blk, (B, Hkv, d)), _f32(v_blk, (B, Hkv, d))
+        k_blk, v_blk = _f32(k_blk), _f32(v_blk)
+        nb = k_blk.shape[0]
+        if k_blk.shape != (nb, Hkv, d) or v_blk.shape != k_blk.shape:
+            raise ValueError("k_blk / v_blk must be [nb,Hkv,d]")
     out = np.empty((B, Hq, d), np.float32)
     lse = np.empty((B, Hq), np.float32)
     rc = _load().mage_oracle_attn(B, Hq, Hkv, d, L, _ptr(q, _f32p), _ptr(k_cache, _f32p), _ptr(v_cache, _f32p),
-                                  _ptr(idx, _i32p), k, _ptr(k_blk, _f32p), _ptr(v_blk, _f32p),
+                                  _ptr(idx, _i32p), k, _ptr(k_blk, _f32p), _ptr(v_blk, _f32p), nb,
                                   _ptr(out, _f32p), _ptr(lse, _f32p))
     if rc:
         raise RuntimeError("mage_oracle_attn failed")

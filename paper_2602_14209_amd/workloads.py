@@ -134,3 +134,66 @@ def device_bits(a: np.ndarray, dtype: str) -> np.ndarray:
             raise ValueError("array is not bf16-representable")
         return bits
     raise ValueError(f"unknown dtype {dtype}")
+
+
+def make_layer_device(w: Workload, seed: int, device="cuda", steps: int | None = None):
+    """The recipe of :func:`make_layer`, drawn on the device with torch's seeded generator (used by
+    the benchmark, where 28 layers of 128K-token caches would take minutes to draw on the host).
+    Returns torch tensors of the workload's dtype with the same names and shapes."""
+    import torch
+
+    T = w.T if steps is None else int(steps)
+    g = torch.Generator(device=device)
+    g.manual_seed(int(seed))
+    dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+
+    def randn(*shape):
+        return torch.randn(*shape, generator=g, device=device, dtype=torch.float32)
+
+    q_mask = randn(w.Hq, w.d)
+    q1 = q_mask[None] + 0.1 * randn(w.B, w.Hq, w.d)
+    q = torch.empty((T, w.B, w.Hq, w.d), device=device, dtype=torch.float32)
+    q[0] = q1
+    for t in range(1, T):
+        q[t] = q1 + 0.3 * randn(w.B, w.Hq, w.d)
+    k_blk = randn(T, w.B, w.Hkv, w.d)
+    v_blk = randn(T, w.B, w.Hkv, w.d)
+    k_cache = torch.empty((w.L, w.Hkv, w.d), device=device, dtype=dt)
+    v_cache = torch.empty((w.L, w.Hkv, w.d), device=device, dtype=dt)
+    n_heavy = int(round(w.heavy_frac * w.L))
+    chunk = 16384
+    heavy_mask = torch.zeros((w.L, w.Hkv), device=device, dtype=torch.bool)
+    for h in range(w.Hkv):
+        if n_heavy:
+            pos = torch.randperm(w.L, generator=g, device=device)[:n_heavy]
+            heavy_mask[pos, h] = True
+    dirs = None
+    if w.drift != 0.0:
+        qbar = q_mask.view(w.Hkv, w.G, w.d).double().mean(dim=1)
+        nrm = qbar.norm(dim=1, keepdim=True)
+        dirs = ((w.drift * (w.d ** 0.5) / nrm) * (qbar / nrm)).float()          # gamma_h * u_h, [Hkv,d]
+    for j0 in range(0, w.L, chunk):
+        j1 = min(w.L, j0 + chunk)
+        kk = randn(j1 - j0, w.Hkv, w.d)
+        kk = torch.where(heavy_mask[j0:j1, :, None], kk * w.heavy_scale, kk)
+        if dirs is not None:
+            ramp = (torch.arange(j0, j1, device=device, dtype=torch.float64) / w.L).float()
+            kk = kk + ramp[:, None, None] * dirs[None]
+        k_cache[j0:j1] = kk.to(dt)
+        v_cache[j0:j1] = randn(j1 - j0, w.Hkv, w.d).to(dt)
+    return {"q": q.to(dt), "k_blk": k_blk.to(dt), "v_blk": v_blk.to(dt), "k_cache": k_cache, "v_cache": v_cache}
+
+
+def algorithmic_bytes(w: Workload, k: int) -> Dict[str, int]:
+    """Bytes each entry point must move per call (one layer, one block), the figure the roofline
+    fractions are computed from: inputs read once, outputs written once, nothing else."""
+    esz = 2 if w.dtype == "bf16" else 4
+    q = w.B * w.Hq * w.d * esz
+    out = w.B * w.Hq * w.d * 4
+    blk = 2 * w.B * w.Hkv * w.d * esz
+    cache_k = w.L * w.Hkv * w.d * esz
+    return {
+        "sparse_attn": 2 * w.Hkv * k * w.d * esz + 4 * w.Hkv * k + q + blk + out,
+        "exact_attn": 2 * cache_k + q + blk + out,
+        "select": 2 * cache_k + 2 * q + 2 * 4 * w.Hkv * w.L + 4 * w.Hkv * k,   # K twice; alpha written + read
+    }

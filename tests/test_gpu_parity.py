@@ -142,3 +142,36 @@ def test_select_ties_and_uniform_on_gpu(oracle_mod):
     idx, alpha = p.select()
     from gpu_util import check_index_sets
     check_index_sets(idx, ref["idx"], ref["alpha32"], L)
+
+
+def test_c4_full_size_headline_shape(oracle_mod):
+    """The benchmark's shape and launch configuration (L=131072, Hq=32, Hkv=8, k=512): selection
+    checked in full, exact attention on sampled block positions, one sparse step in full."""
+    from gpu_util import Problem, check_alpha, check_index_sets, check_out
+    w = CONFIGS["c4"]
+    x = make_layer(w, 1004, steps=2)
+    k = 512
+    print(f"[parity] c4 full size L={w.L} k={k}", flush=True)
+    p = Problem(x["q"][0], x["k_cache"], x["v_cache"], x["k_blk"][0], x["v_blk"][0], k, w.dtype)
+    idx, alpha = p.select()
+    o, l = p.exact()
+    print("[parity] c4 GPU done, running the oracle", flush=True)
+    ref = oracle_mod.select(x["q"][0], x["k_cache"], k)
+    check_alpha(alpha, ref["alpha32"])
+    check_index_sets(idx, ref["idx"], ref["alpha32"], w.L)
+    rows = [0, 13, 31]
+    o_ref, l_ref = oracle_mod.exact_attn(x["q"][0][rows], x["k_cache"], x["v_cache"], x["k_blk"][0], x["v_blk"][0])
+    check_out(o[rows], o_ref, l[rows], l_ref, w.dtype)
+    for kk in w.ks:
+        if kk == k:
+            pk, ref_k = p, ref["idx"]
+        else:
+            pk = Problem(x["q"][0], x["k_cache"], x["v_cache"], x["k_blk"][1], x["v_blk"][1], kk, w.dtype)
+            ref_k = np.stack([oracle_mod.topk(ref["alpha32"][h], kk) for h in range(w.Hkv)])
+            idx_k, _ = pk.select(with_alpha=False)
+            check_index_sets(idx_k, ref_k, ref["alpha32"], w.L)
+        pk.set_q(x["q"][1])
+        pk.set_blk(x["k_blk"][1], x["v_blk"][1])
+        o_ref, l_ref = oracle_mod.sparse_attn(x["q"][1], x["k_cache"], x["v_cache"], ref_k, x["k_blk"][1], x["v_blk"][1])
+        o, l = pk.sparse(ref_k)
+        check_out(o, o_ref, l, l_ref, w.dtype)
