@@ -12,13 +12,18 @@
 //                 its final log-sum-exp and averages over the G*B rows (Eq. 5) -> alpha[h,j].
 //
 // Tiling: one workgroup = NW wavefronts; wavefront w owns 32 query rows (one 32x32 MFMA tile
-// along M); all wavefronts share each 64-key K / V tile, staged once in LDS from coalesced
-// 16-byte global loads and register-prefetched one tile ahead.
+// along M); all wavefronts share each 64-key K / V tile.
 //
-// Scores are produced transposed (S^T = K Q^T, v_mfma_f32_32x32x16_bf16 with the K tile as
-// the A operand): a lane then holds 32 scores of ONE query row, so the online softmax is
-// in-lane work, and the exponentiated scores are already laid out as the B operand of
-// O^T = V^T P^T.  V is transposed on its way into LDS (pairs of keys per 32-bit write).
+// Data movement: tiles go HBM -> LDS directly (global_load_lds, 16 bytes per lane, no VGPR
+// staging), double-buffered, one workgroup barrier per tile.  Rows stay row-major in LDS with an
+// XOR swizzle of their 16-byte chunks, so that
+//   - the K fragment of a lane (one key row, 8 channels) is one conflict-free ds_read_b128;
+//   - the V fragment (8 keys at one channel) is two transposing reads (ds_read_b64_tr_b16), which
+//     deliver V^T straight from the row-major tile.
+//
+// Scores are produced transposed (S^T = K Q^T, v_mfma_f32_32x32x16_bf16 with the K tile as the A
+// operand): a lane then holds 32 scores of ONE query row, so the online softmax is in-lane work,
+// and the exponentiated scores are already laid out as the B operand of O^T = V^T P^T.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -28,75 +33,89 @@ namespace mage {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x8_t __attribute__((ext_vector_type(8)));
 typedef unsigned short u16;
 
 enum { MODE_ATTN = 0, MODE_STATS = 1 };
 
-constexpr int KPAD = 8;                      // bf16 elements of padding per K row in LDS
-constexpr int VT_STRIDE = kBf16Tile + 8;     // bf16 elements per V^T row in LDS
+#define MAGE_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
+#define MAGE_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
 __device__ __forceinline__ bf16x8_t as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8_t, v); }
 
-// position of key kappa inside a V^T row: bits 2 and 3 of the key index swapped, so that the 8
-// keys one lane feeds to one P.V MFMA are contiguous (see the score register layout below)
-__device__ __forceinline__ int vt_pos(int kappa) { return (kappa & ~0xC) | ((kappa >> 1) & 4) | ((kappa << 1) & 8); }
+// XOR swizzle of the 16-byte chunk index of tile row r.  16 consecutive rows (one ds_read_b128
+// phase of the K fragment) and 4 consecutive rows (one half of a transposing V read) both land on
+// distinct LDS banks.
+template <int D>
+__device__ __forceinline__ int swz(int r)
+{
+    return D == 128 ? (((r & 3) << 2) | ((r >> 2) & 3)) : ((((r >> 1) & 1) << 2) | ((r >> 2) & 3));
+}
 
-template <int D, int NT, bool WITH_V>
-struct TileStager {
-    static constexpr int CH = D / 8;                         // 16-byte chunks per row
-    static constexpr int ITEMS = (kBf16Tile / 2) * CH;       // (key pair, chunk) work items per tile
-    static constexpr int IPT = (ITEMS + NT - 1) / NT;        // items per thread
-    uint4 kreg[IPT][2];
-    uint4 vreg[WITH_V ? IPT : 1][2];
-
-    // Issue the global loads of one tile.  `row_of(key)` returns the source row (already clamped
-    // to a valid key) and `kbase`/`vbase` point at element (row 0, this KV head, 0).
-    template <class RowOf>
-    __device__ __forceinline__ void fetch(const u16 *kbase, const u16 *vbase, long long row_stride, RowOf row_of)
-    {
-#pragma unroll
-        for (int i = 0; i < IPT; ++i) {
-            const int id = threadIdx.x + i * NT;
-            if (ITEMS % NT == 0 || id < ITEMS) {
-                const int c = id % CH, p = id / CH;
-#pragma unroll
-                for (int e = 0; e < 2; ++e) {
-                    const long long off = row_of(2 * p + e) * row_stride + c * 8;
-                    kreg[i][e] = *reinterpret_cast<const uint4 *>(kbase + off);
-                    if (WITH_V) vreg[i][e] = *reinterpret_cast<const uint4 *>(vbase + off);
-                }
-            }
-        }
-    }
-
-    // registers -> LDS: K row-major [key][D+KPAD]; V transposed [physical d row][key position]
-    // with physical row = (d % 8) * CH + d / 8 (16 consecutive lanes hit 16 consecutive rows on
-    // both the write and the read side, which keeps the 144-byte row stride conflict-free).
-    __device__ __forceinline__ void commit(u16 *ks, u16 *vt)
-    {
-#pragma unroll
-        for (int i = 0; i < IPT; ++i) {
-            const int id = threadIdx.x + i * NT;
-            if (ITEMS % NT == 0 || id < ITEMS) {
-                const int c = id % CH, p = id / CH;
-                *reinterpret_cast<uint4 *>(ks + (2 * p) * (D + KPAD) + c * 8) = kreg[i][0];
-                *reinterpret_cast<uint4 *>(ks + (2 * p + 1) * (D + KPAD) + c * 8) = kreg[i][1];
-                if (WITH_V) {
-                    const int pos = vt_pos(2 * p);
-                    const uint32_t a[4] = {vreg[i][0].x, vreg[i][0].y, vreg[i][0].z, vreg[i][0].w};
-                    const uint32_t b[4] = {vreg[i][1].x, vreg[i][1].y, vreg[i][1].z, vreg[i][1].w};
-#pragma unroll
-                    for (int w = 0; w < 4; ++w) {
-                        const uint32_t even = (a[w] & 0xffffu) | (b[w] << 16);        // d = c*8 + 2w
-                        const uint32_t odd = (a[w] >> 16) | (b[w] & 0xffff0000u);    // d = c*8 + 2w + 1
-                        *reinterpret_cast<uint32_t *>(vt + ((2 * w) * CH + c) * VT_STRIDE + pos) = even;
-                        *reinterpret_cast<uint32_t *>(vt + ((2 * w + 1) * CH + c) * VT_STRIDE + pos) = odd;
-                    }
-                }
-            }
-        }
-    }
+template <int D>
+struct TileGeom {
+    static constexpr int ROW_BYTES = D * 2;
+    static constexpr int CH = D / 8;                               // 16-byte chunks per row
+    static constexpr int MAT_BYTES = kBf16Tile * ROW_BYTES;        // one 64-key K (or V) tile
+    static constexpr int RPI = 1024 / ROW_BYTES;                   // rows covered by one wavefront-wide load
+    static constexpr int LOADS = kBf16Tile / RPI;                  // wavefront-wide loads per matrix per tile
 };
+
+// Issue this wavefront's share of the direct HBM->LDS loads of one tile.  `row_of(r)` gives the
+// source row of tile row r (already clamped to a valid key); `kbase`/`vbase` point at element
+// (row 0, this KV head, channel 0); `buf` is the LDS tile buffer (K matrix, then V matrix).
+template <int D, int NW, bool WITH_V, class RowOf>
+__device__ __forceinline__ void issue_tile(const u16 *kbase, const u16 *vbase, long long row_stride,
+                                           unsigned char *buf, RowOf row_of)
+{
+    using G = TileGeom<D>;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int n = 0; n < G::LOADS / NW; ++n) {
+        const int unit = n * NW + wave;                            // which 1 KB of the matrix
+        const int r = unit * G::RPI + lane / G::CH;
+        const int chunk = (lane % G::CH) ^ swz<D>(r);
+        const long long off = row_of(r) * row_stride + chunk * 8;
+        __builtin_amdgcn_global_load_lds(MAGE_GLOBAL_PTR(kbase + off), MAGE_LDS_PTR(buf + unit * 1024), 16, 0, 0);
+        if (WITH_V)
+            __builtin_amdgcn_global_load_lds(MAGE_GLOBAL_PTR(vbase + off), MAGE_LDS_PTR(buf + G::MAT_BYTES + unit * 1024), 16, 0, 0);
+    }
+}
+
+// wait for this wavefront's outstanding HBM->LDS loads, then meet the rest of the workgroup
+__device__ __forceinline__ void tile_barrier()
+{
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+}
+
+// K fragment: key row `rk` of the tile, channels [16*ks + 8*lg, +8)
+template <int D>
+__device__ __forceinline__ bf16x8_t read_k_frag(const unsigned char *kbuf, int rk, int ks, int lg)
+{
+    const int chunk = (2 * ks + lg) ^ swz<D>(rk);
+    return as_bf16x8(*reinterpret_cast<const uint4 *>(kbuf + rk * TileGeom<D>::ROW_BYTES + chunk * 16));
+}
+
+// V^T fragment for O^T tile dt: lane holds channel dt*32 + (lane & 31) of the 8 keys
+// key0 + {0,1,2,3, 8,9,10,11}.  Within each 16-lane block, lane i' addresses 4 channels
+// (4*(i' & 3) ..) of key (i' >> 2); the transposing read hands lane i the 4 keys at channel i.
+template <int D>
+__device__ __forceinline__ bf16x8_t read_vt_frag(const unsigned char *vbuf, int key0, int dt, int lane)
+{
+    const int blk = lane >> 4, ip = lane & 15;
+    const int j = ip >> 2, q = ip & 3;
+    const int d = dt * 32 + 16 * (blk & 1) + 4 * q;
+    const int key_a = key0 + j, key_b = key0 + 8 + j;
+    const unsigned char *pa = vbuf + key_a * TileGeom<D>::ROW_BYTES + (((d >> 3) ^ swz<D>(key_a)) * 16) + 8 * (q & 1);
+    const unsigned char *pb = vbuf + key_b * TileGeom<D>::ROW_BYTES + (((d >> 3) ^ swz<D>(key_b)) * 16) + 8 * (q & 1);
+    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t *)(pa));
+    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t *)(pb));
+    const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8_t, both);
+}
 
 // Query fragment of this lane: row (l % 32) of the wavefront's M tile, 8 consecutive channels
 // per MFMA k-step.  Row r of a KV head's row space is (g_local = r / B, q = r % B).
@@ -134,15 +153,19 @@ __device__ __forceinline__ SplitRange split_range(const KernelArgs &a, int s)
 }
 
 template <int D, int NW, int MODE, bool GATHER>
-__global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const KernelArgs a)
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) void attn_bf16_kernel(const KernelArgs a)
 {
-    constexpr int NT = NW * 64;
+    using G = TileGeom<D>;
     constexpr bool WITH_V = (MODE == MODE_ATTN);
     constexpr int KS = D / 16;     // MFMA k-steps over the head dimension
     constexpr int DT = D / 32;     // 32-row tiles of O^T
+    constexpr int BUF_BYTES = G::MAT_BYTES * (WITH_V ? 2 : 1);
+    constexpr int OST = D + 4;     // floats per staged output row
+    constexpr int STAGE_BYTES = WITH_V ? 2 * 32 * OST * 4 : 0;
+    static_assert(2 * BUF_BYTES >= STAGE_BYTES, "output staging must fit in the tile buffers");
 
-    __shared__ __attribute__((aligned(16))) u16 ks_lds[kBf16Tile * (D + KPAD)];
-    __shared__ __attribute__((aligned(16))) u16 vt_lds[WITH_V ? D * VT_STRIDE : 8];
+    // two tile buffers; after the key loop the same memory stages the output transposition
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[2 * BUF_BYTES];
 
     const int h = blockIdx.x, split = blockIdx.y, rg = blockIdx.z;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -154,17 +177,6 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const KernelArgs a)
     const SplitRange sr = split_range(a, split);
     const int ntiles = sr.cache_tiles + sr.blk_tiles;
 
-    bf16x8_t qf[KS];
-    load_q_frag<D>(a, h, row, qf);
-
-    f32x16_t o[WITH_V ? DT : 1];
-#pragma unroll
-    for (int i = 0; i < (WITH_V ? DT : 1); ++i)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) o[i][v] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
-
-    TileStager<D, NT, WITH_V> st;
     const long long cache_stride = (long long)a.Hkv * D;
     const u16 *kc = static_cast<const u16 *>(a.kc) + (long long)h * D;
     const u16 *vc = static_cast<const u16 *>(a.vc) + (long long)h * D;
@@ -180,26 +192,39 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const KernelArgs a)
         const int left = a.n_blk - (t - sr.cache_tiles) * kBf16Tile;
         return left < kBf16Tile ? left : kBf16Tile;
     };
-    auto fetch_tile = [&](int t) {
+    auto issue = [&](int t) {
         const int valid = tile_valid(t);
+        unsigned char *buf = smem + (t & 1) * BUF_BYTES;
         if (t < sr.cache_tiles) {
             const long long base = sr.c0 + (long long)t * kBf16Tile;
-            st.fetch(kc, vc, cache_stride, [&](int key) -> long long {
-                const long long pos = base + (key < valid ? key : valid - 1);
+            issue_tile<D, NW, WITH_V>(kc, vc, cache_stride, buf, [&](int r) -> long long {
+                const long long pos = base + (r < valid ? r : valid - 1);
                 return GATHER ? (long long)idx[pos] : pos;
             });
         } else {
             const int base = (t - sr.cache_tiles) * kBf16Tile;
-            st.fetch(kb, vb, cache_stride, [&](int key) -> long long { return base + (key < valid ? key : valid - 1); });
+            issue_tile<D, NW, WITH_V>(kb, vb, cache_stride, buf, [&](int r) -> long long { return base + (r < valid ? r : valid - 1); });
         }
     };
 
-    if (ntiles > 0) fetch_tile(0);
+    if (ntiles > 0) issue(0);          // first: the longest dependent chain (index -> row)
+
+    bf16x8_t qf[KS];
+    load_q_frag<D>(a, h, row, qf);
+
+    f32x16_t o[WITH_V ? DT : 1];
+#pragma unroll
+    for (int i = 0; i < (WITH_V ? DT : 1); ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[i][v] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;     // running max (log2 domain) and this lane's share of the normaliser
+
     for (int t = 0; t < ntiles; ++t) {
-        st.commit(ks_lds, vt_lds);
-        __syncthreads();
-        if (t + 1 < ntiles) fetch_tile(t + 1);
+        tile_barrier();                        // tile t landed; everyone is done with tile t-1
+        if (t + 1 < ntiles) issue(t + 1);
         const int valid = tile_valid(t);
+        const unsigned char *kbuf = smem + (t & 1) * BUF_BYTES;
+        const unsigned char *vbuf = kbuf + G::MAT_BYTES;
 
         if (wave_active) {
             // S^T tile: sc[kt][v] = score of query row l32 against key kt*32 + 8*(v/4) + 4*lg + v%4
@@ -208,44 +233,45 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const KernelArgs a)
             for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) sc[kt][v] = 0.f;
-                const u16 *krow = ks_lds + (kt * 32 + l32) * (D + KPAD) + 8 * lg;
+                bf16x8_t kf[KS];
 #pragma unroll
-                for (int s = 0; s < KS; ++s) {
-                    const bf16x8_t kf = as_bf16x8(*reinterpret_cast<const uint4 *>(krow + s * 16));
-                    sc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sc[kt], 0, 0, 0);
-                }
+                for (int s = 0; s < KS; ++s) kf[s] = read_k_frag<D>(kbuf, kt * 32 + l32, s, lg);
+#pragma unroll
+                for (int s = 0; s < KS; ++s) sc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[s], sc[kt], 0, 0, 0);
             }
-            float mx = -INFINITY;
+            if (valid < kBf16Tile) {
 #pragma unroll
-            for (int kt = 0; kt < 2; ++kt)
+                for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int key = kt * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
-                    float s2 = sc[kt][v] * a.scale_log2;
-                    if (valid < kBf16Tile && key >= valid) s2 = -INFINITY;
-                    sc[kt][v] = s2;
-                    mx = fmaxf(mx, s2);
-                }
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
+                    for (int v = 0; v < 16; ++v)
+                        if (kt * 32 + 8 * (v >> 2) + 4 * lg + (v & 3) >= valid) sc[kt][v] = -INFINITY;
+            }
+            float mx = fmaxf(sc[0][0], sc[1][0]);
+#pragma unroll
+            for (int v = 1; v < 16; ++v) mx = fmaxf(mx, fmaxf(sc[0][v], sc[1][v]));
+            mx = fmaxf(mx, __shfl_xor(mx, 32)) * a.scale_log2;
             const float m_new = fmaxf(m_run, mx);
             const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
+            const bool grew = m_new > m_run;
             m_run = m_new;
             float psum = 0.f;
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const float p = __builtin_amdgcn_exp2f(sc[kt][v] - m_new);
+                    const float p = __builtin_amdgcn_exp2f(fmaf(sc[kt][v], a.scale_log2, -m_new));
                     sc[kt][v] = p;
                     psum += p;
                 }
             l_run = l_run * corr + psum;
 
             if (WITH_V) {
+                if (__any(grew)) {             // rescale only when some row's maximum moved
 #pragma unroll
-                for (int dt = 0; dt < DT; ++dt)
+                    for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) o[dt][v] *= corr;
+                        for (int v = 0; v < 16; ++v) o[dt][v] *= corr;
+                }
 #pragma unroll
                 for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
@@ -253,23 +279,20 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const KernelArgs a)
                         bf16x8_t pf;
 #pragma unroll
                         for (int e = 0; e < 8; ++e) pf[e] = (__bf16)sc[kt][8 * m2 + e];
+                        bf16x8_t vf[DT];
 #pragma unroll
-                        for (int dt = 0; dt < DT; ++dt) {
-                            const u16 *vrow = vt_lds + (dt * 32 + l32) * VT_STRIDE + kt * 32 + m2 * 16 + lg * 8;
-                            const bf16x8_t vf = as_bf16x8(*reinterpret_cast<const uint4 *>(vrow));
-                            o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[dt], 0, 0, 0);
-                        }
+                        for (int dt = 0; dt < DT; ++dt) vf[dt] = read_vt_frag<D>(vbuf, kt * 32 + m2 * 16 + 4 * lg, dt, lane);
+#pragma unroll
+                        for (int dt = 0; dt < DT; ++dt) o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt], pf, o[dt], 0, 0, 0);
                     }
             }
         }
-        __syncthreads();
     }
 
-    if (!wave_active) return;
     const float l_tot = l_run + __shfl_xor(l_run, 32);
 
     if (MODE == MODE_STATS) {
-        if (row < a.R && lg == 0) {
+        if (wave_active && row < a.R && lg == 0) {
             const long long pi = ((long long)h * a.n_split + split) * a.rpad + row;
             a.part_m[pi] = m_run;
             a.part_l[pi] = l_tot;
@@ -277,37 +300,53 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const KernelArgs a)
         return;
     }
 
-    if (row >= a.R) return;
-    // O^T register (dt, v) holds channel d = 8*c + e of query row `row`, where the physical
-    // V^T row is pr = dt*32 + 8*(v/4) + 4*lg + v%4, c = pr % CH, e = pr / CH.
-    constexpr int CH = D / 8;
-    if (a.n_split == 1) {
-        const int gl = row / a.B, qi = row - gl * a.B;
-        float *dst = a.out + ((long long)qi * a.Hq + (long long)h * a.G + gl) * D;
-        const float inv = 1.f / l_tot;
+    // Epilogue.  O^T register (dt, v) holds channel d = dt*32 + 8*(v/4) + 4*lg + v%4 of query row
+    // `row`.  Two wavefronts at a time transpose their 32 x D block through LDS and write whole
+    // rows (16 bytes per lane, consecutive lanes on consecutive addresses).
+    constexpr int LPR = D / 4;          // lanes per output row
+    constexpr int RPS = 64 / LPR;       // rows per store instruction
+    const bool direct = a.n_split == 1;
+    const float inv = direct ? 1.f / l_tot : 1.f;
+    float *stage = reinterpret_cast<float *>(smem) + (wave & 1) * 32 * OST;
+    __syncthreads();                    // every wavefront is done reading the last tile
+    for (int round = 0; round < NW / 2; ++round) {
+        if ((wave >> 1) == round && wave_active) {
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
+            for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int pr = dt * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
-                dst[8 * (pr % CH) + pr / CH] = o[dt][v] * inv;
+                for (int v4 = 0; v4 < 4; ++v4) {
+                    f32x4_t val = {o[dt][4 * v4] * inv, o[dt][4 * v4 + 1] * inv, o[dt][4 * v4 + 2] * inv, o[dt][4 * v4 + 3] * inv};
+                    *reinterpret_cast<f32x4_t *>(stage + l32 * OST + dt * 32 + 8 * v4 + 4 * lg) = val;
+                }
+#pragma unroll
+            for (int it = 0; it < 32 / RPS; ++it) {
+                const int rr = it * RPS + lane / LPR, col = (lane % LPR) * 4;
+                const f32x4_t val = *reinterpret_cast<const f32x4_t *>(stage + rr * OST + col);
+                const int orow = row0 + rr;
+                if (orow < a.R) {
+                    float *dst;
+                    if (direct) {
+                        const int gl = orow / a.B, qi = orow - gl * a.B;
+                        dst = a.out + ((long long)qi * a.Hq + (long long)h * a.G + gl) * D;
+                    } else {
+                        dst = a.part_o + (((long long)h * a.n_split + split) * a.rpad + orow) * D;
+                    }
+                    *reinterpret_cast<f32x4_t *>(dst + col) = val;
+                }
             }
-        if (a.lse_out && lg == 0)
-            a.lse_out[(long long)qi * a.Hq + (long long)h * a.G + gl] = (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
+        }
+        __syncthreads();
+    }
+    if (!wave_active || row >= a.R || lg != 0) return;
+    if (direct) {
+        if (a.lse_out) {
+            const int gl = row / a.B, qi = row - gl * a.B;
+            a.lse_out[(long long)qi * a.Hq + (long long)h * a.G + gl] = (m_run + log2f(l_tot)) * 0.6931471805599453f;
+        }
     } else {
         const long long pi = ((long long)h * a.n_split + split) * a.rpad + row;
-        float *dst = a.part_o + pi * D;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int pr = dt * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
-                dst[8 * (pr % CH) + pr / CH] = o[dt][v];
-            }
-        if (lg == 0) {
-            a.part_m[pi] = m_run;
-            a.part_l[pi] = l_tot;
-        }
+        a.part_m[pi] = m_run;
+        a.part_l[pi] = l_tot;
     }
 }
 
@@ -316,10 +355,11 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const KernelArgs a)
 template <int D, int NW>
 __global__ __launch_bounds__(NW * 64) void colsum_bf16_kernel(const KernelArgs a)
 {
-    constexpr int NT = NW * 64;
+    using G = TileGeom<D>;
     constexpr int KS = D / 16;
-    __shared__ __attribute__((aligned(16))) u16 ks_lds[kBf16Tile * (D + KPAD)];
-    __shared__ float red[NW][kBf16Tile];
+    constexpr int BUF_BYTES = G::MAT_BYTES;
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[2 * BUF_BYTES];
+    __shared__ float red[2][NW][kBf16Tile];
 
     const int h = blockIdx.x, split = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -329,6 +369,20 @@ __global__ __launch_bounds__(NW * 64) void colsum_bf16_kernel(const KernelArgs a
 
     const SplitRange sr = split_range(a, split);
     const int ntiles = sr.cache_tiles;
+    const long long cache_stride = (long long)a.Hkv * D;
+    const u16 *kc = static_cast<const u16 *>(a.kc) + (long long)h * D;
+
+    auto tile_valid = [&](int t) -> int {
+        const long long left = sr.c1 - (sr.c0 + (long long)t * kBf16Tile);
+        return left < kBf16Tile ? (int)left : kBf16Tile;
+    };
+    auto issue = [&](int t) {
+        const int valid = tile_valid(t);
+        const long long base = sr.c0 + (long long)t * kBf16Tile;
+        issue_tile<D, NW, false>(kc, kc, cache_stride, smem + (t & 1) * BUF_BYTES,
+                                 [&](int r) -> long long { return base + (r < valid ? r : valid - 1); });
+    };
+    if (ntiles > 0) issue(0);
 
     bf16x8_t qf[KS];
     load_q_frag<D>(a, h, row0 + l32, qf);
@@ -341,27 +395,23 @@ __global__ __launch_bounds__(NW * 64) void colsum_bf16_kernel(const KernelArgs a
         lse2[v] = r < a.R ? a.lse2[(long long)h * a.rpad + r] : INFINITY;   // exp2(-inf) = 0 for padding rows
     }
 
-    TileStager<D, NT, false> st;
-    const long long cache_stride = (long long)a.Hkv * D;
-    const u16 *kc = static_cast<const u16 *>(a.kc) + (long long)h * D;
-
-    auto tile_valid = [&](int t) -> int {
-        const long long left = sr.c1 - (sr.c0 + (long long)t * kBf16Tile);
-        return left < kBf16Tile ? (int)left : kBf16Tile;
-    };
-    auto fetch_tile = [&](int t) {
+    // The cross-wavefront sum of tile t is finished after the barrier of tile t+1 (the `red`
+    // buffer alternates), so the loop needs one barrier per tile.
+    auto finish = [&](int t) {
         const int valid = tile_valid(t);
-        const long long base = sr.c0 + (long long)t * kBf16Tile;
-        st.fetch(kc, kc, cache_stride, [&](int key) -> long long { return base + (key < valid ? key : valid - 1); });
+        if (threadIdx.x < kBf16Tile && (int)threadIdx.x < valid) {
+            float acc = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) acc += red[t & 1][w][threadIdx.x];
+            a.alpha[(long long)h * a.L + sr.c0 + (long long)t * kBf16Tile + threadIdx.x] = acc * a.inv_rows;
+        }
     };
 
-    if (ntiles > 0) fetch_tile(0);
     for (int t = 0; t < ntiles; ++t) {
-        st.commit(ks_lds, nullptr);
-        __syncthreads();
-        if (t + 1 < ntiles) fetch_tile(t + 1);
-        const int valid = tile_valid(t);
-
+        tile_barrier();
+        if (t + 1 < ntiles) issue(t + 1);
+        if (t > 0) finish(t - 1);
+        const unsigned char *kbuf = smem + (t & 1) * BUF_BYTES;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt) {
             float col = 0.f;
@@ -369,25 +419,21 @@ __global__ __launch_bounds__(NW * 64) void colsum_bf16_kernel(const KernelArgs a
                 f32x16_t sc;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) sc[v] = 0.f;
-                const u16 *krow = ks_lds + (kt * 32 + l32) * (D + KPAD) + 8 * lg;
+                bf16x8_t kf[KS];
 #pragma unroll
-                for (int s = 0; s < KS; ++s) {
-                    const bf16x8_t kf = as_bf16x8(*reinterpret_cast<const uint4 *>(krow + s * 16));
-                    sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[s], kf, sc, 0, 0, 0);
-                }
+                for (int s = 0; s < KS; ++s) kf[s] = read_k_frag<D>(kbuf, kt * 32 + l32, s, lg);
+#pragma unroll
+                for (int s = 0; s < KS; ++s) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[s], kf[s], sc, 0, 0, 0);
 #pragma unroll
                 for (int v = 0; v < 16; ++v) col += __builtin_amdgcn_exp2f(fmaf(sc[v], a.scale_log2, -lse2[v]));
                 col += __shfl_xor(col, 32);
             }
-            if (lg == 0) red[wave][kt * 32 + l32] = col;
+            if (lg == 0) red[t & 1][wave][kt * 32 + l32] = col;
         }
+    }
+    if (ntiles > 0) {
         __syncthreads();
-        if (threadIdx.x < kBf16Tile && (int)threadIdx.x < valid) {
-            float acc = 0.f;
-#pragma unroll
-            for (int w = 0; w < NW; ++w) acc += red[w][threadIdx.x];
-            a.alpha[(long long)h * a.L + sr.c0 + (long long)t * kBf16Tile + threadIdx.x] = acc * a.inv_rows;
-        }
+        finish(ntiles - 1);
     }
 }
 

@@ -24,9 +24,11 @@ __global__ __launch_bounds__(256) void combine_kernel(const KernelArgs a)
     if (row >= a.R) return;
 
     float M = -INFINITY;
+#pragma unroll 8
     for (int s = 0; s < a.n_split; ++s) M = fmaxf(M, a.part_m[((long long)h * a.n_split + s) * a.rpad + row]);
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     float lt = 0.f;
+#pragma unroll 8
     for (int s = 0; s < a.n_split; ++s) {
         const long long pi = ((long long)h * a.n_split + s) * a.rpad + row;
         const float w = exp2f(a.part_m[pi] - M);
@@ -44,20 +46,26 @@ __global__ __launch_bounds__(256) void combine_kernel(const KernelArgs a)
     if (a.lse_out && c4 == 0) a.lse_out[orow] = (M + log2f(lt)) * 0.6931471805599453f;
 }
 
-// lse2[h][row] = M + log2( sum_s l_s * 2^(m_s - M) ), accumulated in fp64 (a few dozen terms).
+// lse2[h][row] = M + log2( sum_s l_s * 2^(m_s - M) ): one wavefront per row, lane s takes splits
+// s, s+64, ...; the sum is accumulated in fp64 in a fixed order.
 __global__ __launch_bounds__(256) void lse_kernel(const KernelArgs a, float *lse2_out)
 {
     const int h = blockIdx.y;
-    const int row = blockIdx.x * 256 + threadIdx.x;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
     if (row >= a.R) return;
     float M = -INFINITY;
-    for (int s = 0; s < a.n_split; ++s) M = fmaxf(M, a.part_m[((long long)h * a.n_split + s) * a.rpad + row]);
+    for (int s = lane; s < a.n_split; s += 64) M = fmaxf(M, a.part_m[((long long)h * a.n_split + s) * a.rpad + row]);
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) M = fmaxf(M, __shfl_xor(M, d));
     double lt = 0.0;
-    for (int s = 0; s < a.n_split; ++s) {
+    for (int s = lane; s < a.n_split; s += 64) {
         const long long pi = ((long long)h * a.n_split + s) * a.rpad + row;
         lt += (double)a.part_l[pi] * (double)exp2f(a.part_m[pi] - M);
     }
-    lse2_out[(long long)h * a.rpad + row] = M + (float)log2(lt);
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) lt += __shfl_xor(lt, d);
+    if (lane == 0) lse2_out[(long long)h * a.rpad + row] = M + (float)log2(lt);
 }
 
 // ------------------------------------------------------------------------------ top-k
@@ -105,9 +113,19 @@ __device__ __forceinline__ void radix_step(const uint32_t *u, long long L, int s
     const uint32_t hi_mask = (shift + bits >= 32) ? 0u : (0xffffffffu << (shift + bits));
     for (int b = threadIdx.x; b < nb; b += TK_THREADS) hist[b] = 0;
     __syncthreads();
-    for (long long j = threadIdx.x; j < L; j += TK_THREADS) {
-        const uint32_t x = u[j];
-        if ((x & hi_mask) == prefix) atomicAdd(&hist[(x >> shift) & (nb - 1)], 1u);
+    constexpr int UNR = 8;      // independent loads in flight per thread
+    for (long long j0 = threadIdx.x; j0 < L; j0 += (long long)TK_THREADS * UNR) {
+        uint32_t x[UNR];
+#pragma unroll
+        for (int i = 0; i < UNR; ++i) {
+            const long long j = j0 + (long long)i * TK_THREADS;
+            x[i] = j < L ? u[j] : 0xffffffffu;
+        }
+#pragma unroll
+        for (int i = 0; i < UNR; ++i) {
+            const long long j = j0 + (long long)i * TK_THREADS;
+            if (j < L && (x[i] & hi_mask) == prefix) atomicAdd(&hist[(x[i] >> shift) & (nb - 1)], 1u);
+        }
     }
     __syncthreads();
     // thread t owns bins [t*per, (t+1)*per) counted from the TOP digit downwards
@@ -205,7 +223,7 @@ hipError_t launch_combine(const KernelArgs &a, int d, hipStream_t stream)
 
 hipError_t launch_lse(const KernelArgs &a, float *lse2_out, hipStream_t stream)
 {
-    dim3 grid((a.R + 255) / 256, a.Hkv), block(256);
+    dim3 grid((a.R + 3) / 4, a.Hkv), block(256);
     hipLaunchKernelGGL(lse_kernel, grid, block, 0, stream, a, lse2_out);
     return hipGetLastError();
 }
