@@ -28,6 +28,7 @@
 #include <stdint.h>
 
 #include "plan.hpp"
+#include "probe.hpp"
 
 namespace mage {
 
@@ -174,6 +175,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     const int row = row0 + l32;
     const bool wave_active = row0 < a.R;
 
+    MAGE_PROBE_AT(0);
     const SplitRange sr = split_range(a, split);
     const int ntiles = sr.cache_tiles + sr.blk_tiles;
 
@@ -221,6 +223,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 
     for (int t = 0; t < ntiles; ++t) {
         tile_barrier();                        // tile t landed; everyone is done with tile t-1
+        if (t == 0) MAGE_PROBE_AT(1);
         if (t + 1 < ntiles) issue(t + 1);
         const int valid = tile_valid(t);
         const unsigned char *kbuf = smem + (t & 1) * BUF_BYTES;
@@ -290,6 +293,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     }
 
     const float l_tot = l_run + __shfl_xor(l_run, 32);
+    MAGE_PROBE_AT(2);
 
     if (MODE == MODE_STATS) {
         if (wave_active && row < a.R && lg == 0) {
@@ -337,6 +341,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
         }
         __syncthreads();
     }
+    MAGE_PROBE_AT(3);
     if (!wave_active || row >= a.R || lg != 0) return;
     if (direct) {
         if (a.lse_out) {

@@ -10,6 +10,7 @@ namespace mage {
 hipError_t bf16_attn(const KernelArgs &a, int d, int waves, int row_groups, bool gather, hipStream_t stream);
 hipError_t bf16_stats(const KernelArgs &a, int d, int waves, int row_groups, hipStream_t stream);
 hipError_t bf16_colsum(const KernelArgs &a, int d, int waves, hipStream_t stream);
+hipError_t bf16_sparse(const KernelArgs &a, int d, hipStream_t stream);
 hipError_t f32_attn(const KernelArgs &a, int d, int row_groups, bool gather, hipStream_t stream);
 hipError_t f32_stats(const KernelArgs &a, int d, int row_groups, hipStream_t stream);
 hipError_t f32_colsum(const KernelArgs &a, int d, hipStream_t stream);
@@ -195,8 +196,32 @@ int mage_sparse_attn(const mage_shape *shape, const void *q, const void *k_cache
 {
     const int rc = check_shape(shape, true);
     if (rc != MAGE_OK) return rc;
-    return run_attention(shape, plan_sparse(*shape), true, q, k_cache, v_cache, idx, k_blk, v_blk, out, lse_out,
-                         workspace, workspace_bytes, hip_stream);
+    if (shape->dtype != MAGE_BF16)
+        return run_attention(shape, plan_sparse(*shape), true, q, k_cache, v_cache, idx, k_blk, v_blk, out, lse_out,
+                             workspace, workspace_bytes, hip_stream);
+
+    // bf16: one kernel, no partials in HBM, no workspace
+    if (!q || !k_cache || !v_cache || !out || !idx) return MAGE_ERR_NULL;
+    if ((k_blk == nullptr) != (v_blk == nullptr)) return MAGE_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(k_blk) || !aligned16(v_blk) ||
+        !aligned16(out))
+        return MAGE_ERR_ALIGN;
+    SplitPlan p{};
+    plan_rows(*shape, p);
+    p.n_split = 1;
+    KernelArgs a = base_args(*shape, p);
+    a.q = q;
+    a.kc = k_cache;
+    a.vc = v_cache;
+    a.kblk = k_blk ? k_blk : k_cache;
+    a.vblk = v_blk ? v_blk : v_cache;
+    a.n_blk = k_blk ? shape->B : 0;
+    a.idx = idx;
+    a.nc = shape->k;
+    a.out = out;
+    a.lse_out = lse_out;
+    if (bf16_sparse(a, shape->d, static_cast<hipStream_t>(hip_stream)) != hipSuccess) return MAGE_ERR_HIP;
+    return MAGE_OK;
 }
 
 }  // extern "C"

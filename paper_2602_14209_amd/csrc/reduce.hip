@@ -1,0 +1,85 @@
+// Small kernels around the attention passes (gfx950):
+//   combine_kernel   merges the split-key partials of an attention call into out / lse
+//   lse_kernel       merges the statistics partials of selection into one log2-domain
+//                    log-sum-exp per query row
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "plan.hpp"
+
+namespace mage {
+
+// One thread per (row, 4 channels).  Split s contributes weight exp2(m_s - M).
+template <int D>
+__global__ __launch_bounds__(256) void combine_kernel(const KernelArgs a)
+{
+    constexpr int TPR = D / 4;                 // threads per row
+    constexpr int ROWS = 256 / TPR;            // rows per workgroup
+    const int h = blockIdx.y;
+    const int row = blockIdx.x * ROWS + threadIdx.x / TPR;
+    const int c4 = threadIdx.x % TPR;
+    if (row >= a.R) return;
+
+    float M = -INFINITY;
+#pragma unroll 8
+    for (int s = 0; s < a.n_split; ++s) M = fmaxf(M, a.part_m[((long long)h * a.n_split + s) * a.rpad + row]);
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    float lt = 0.f;
+#pragma unroll 8
+    for (int s = 0; s < a.n_split; ++s) {
+        const long long pi = ((long long)h * a.n_split + s) * a.rpad + row;
+        const float w = exp2f(a.part_m[pi] - M);
+        lt = fmaf(w, a.part_l[pi], lt);
+        const float4 v = *reinterpret_cast<const float4 *>(a.part_o + pi * D + c4 * 4);
+        acc.x = fmaf(w, v.x, acc.x);
+        acc.y = fmaf(w, v.y, acc.y);
+        acc.z = fmaf(w, v.z, acc.z);
+        acc.w = fmaf(w, v.w, acc.w);
+    }
+    const float inv = 1.f / lt;
+    const int gl = row / a.B, qi = row - gl * a.B;
+    const long long orow = (long long)qi * a.Hq + (long long)h * a.G + gl;
+    *reinterpret_cast<float4 *>(a.out + orow * D + c4 * 4) = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
+    if (a.lse_out && c4 == 0) a.lse_out[orow] = (M + log2f(lt)) * 0.6931471805599453f;
+}
+
+// lse2[h][row] = M + log2( sum_s l_s * 2^(m_s - M) ): one wavefront per row, lane s takes splits
+// s, s+64, ...; the sum is accumulated in fp64 in a fixed order.
+__global__ __launch_bounds__(256) void lse_kernel(const KernelArgs a, float *lse2_out)
+{
+    const int h = blockIdx.y;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (row >= a.R) return;
+    float M = -INFINITY;
+    for (int s = lane; s < a.n_split; s += 64) M = fmaxf(M, a.part_m[((long long)h * a.n_split + s) * a.rpad + row]);
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) M = fmaxf(M, __shfl_xor(M, d));
+    double lt = 0.0;
+    for (int s = lane; s < a.n_split; s += 64) {
+        const long long pi = ((long long)h * a.n_split + s) * a.rpad + row;
+        lt += (double)a.part_l[pi] * (double)exp2f(a.part_m[pi] - M);
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) lt += __shfl_xor(lt, d);
+    if (lane == 0) lse2_out[(long long)h * a.rpad + row] = M + (float)log2(lt);
+}
+
+hipError_t launch_combine(const KernelArgs &a, int d, hipStream_t stream)
+{
+    const int rows_per_wg = 256 / (d / 4);
+    dim3 grid((a.R + rows_per_wg - 1) / rows_per_wg, a.Hkv), block(256);
+    if (d == 128) hipLaunchKernelGGL((combine_kernel<128>), grid, block, 0, stream, a);
+    else if (d == 64) hipLaunchKernelGGL((combine_kernel<64>), grid, block, 0, stream, a);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+hipError_t launch_lse(const KernelArgs &a, float *lse2_out, hipStream_t stream)
+{
+    dim3 grid((a.R + 3) / 4, a.Hkv), block(256);
+    hipLaunchKernelGGL(lse_kernel, grid, block, 0, stream, a, lse2_out);
+    return hipGetLastError();
+}
+
+}  // namespace mage

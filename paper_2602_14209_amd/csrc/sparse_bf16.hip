@@ -1,0 +1,252 @@
+// bf16 sparse-step attention for gfx950 -- Alg. 1 Phase 2 "SparseAttn(Q_h,K_h,V_h,C[S])":
+// softmax over the k selected cache rows of KV head h plus the block's own B keys.
+//
+// The step moves a few MB, so it is bound by dependent-load latency and by how many compute
+// units take part, not by bandwidth.  Layout of the work, chosen for that:
+//   - one workgroup per (KV head, 16 query rows); its 8 wavefronts split the KEYS (tiles of 16
+//     key positions, round-robin), so no partial result ever leaves the compute unit: the eight
+//     partial (max, sum, O) are merged through LDS and every output row is written once;
+//   - every load of a pass is in flight at once: the index entries, then K rows straight into
+//     MFMA operand registers (a lane's fragment is 16 contiguous bytes of one row) and V rows
+//     straight into LDS (global_load_lds), from where transposing reads (ds_read_b64_tr_b16)
+//     deliver V^T fragments;
+//   - workgroups of one KV head sit on the same XCD when Hkv is a multiple of 8 (linear
+//     workgroup id = head + Hkv * row_tile), so a gathered row is fetched from HBM once and
+//     shared through that XCD's L2.
+// Key positions form one sequence: 0..k-1 are cache rows idx[h,p], k..k+B-1 the in-block rows.
+// v_mfma_f32_16x16x32_bf16 throughout; scores are produced transposed (S^T = K Q^T) so that a
+// lane holds scores of one query row and P^T is already the B operand of O^T = V^T P^T.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "plan.hpp"
+#include "probe.hpp"
+
+namespace mage {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x8_t __attribute__((ext_vector_type(8)));
+typedef unsigned short u16;
+
+constexpr int SP_WAVES = 8;
+constexpr int SP_KT = 16;          // key positions per tile
+constexpr int SP_TPW = 5;          // tiles per wavefront per pass (register arrays)
+constexpr int SP_MAXT = SP_WAVES * SP_TPW;   // tiles per pass: all of LDS holds V (640 key positions at d=128)
+
+// chunk swizzle of a 16-row V tile: rows 0..7 (one half of a transposing read) spread over all banks
+__device__ __forceinline__ int sp_swz(int r) { return ((r & 7) << 1) | (r >> 3); }
+
+template <int D>
+__global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2))) void sparse_bf16_kernel(const KernelArgs a)
+{
+    constexpr int KS = D / 32;                  // MFMA k-steps of the score product
+    constexpr int DT = D / 16;                  // 16-channel tiles of O^T
+    constexpr int CH = D / 8;                   // 16-byte chunks per row
+    constexpr int ROW_BYTES = D * 2;
+    constexpr int TILE_BYTES = SP_KT * ROW_BYTES;
+    constexpr int VLOADS = TILE_BYTES / 1024;   // wavefront-wide 1 KB loads per V tile
+    constexpr int RPL = 1024 / ROW_BYTES;       // rows per such load
+
+    // V tiles: slot j*8 + wave belongs to this wavefront alone (distinct compile-time offsets, so
+    // the compiler sees that the direct loads never overlap).  After the key loop the same memory
+    // holds the eight partial results and their (max, sum) pairs.
+    __shared__ __attribute__((aligned(1024))) unsigned char vlds[SP_MAXT * TILE_BYTES];
+    constexpr int PART_BYTES = SP_WAVES * DT * 64 * 16;
+    static_assert(PART_BYTES + 2 * SP_WAVES * 16 * 4 <= SP_MAXT * TILE_BYTES, "merge buffers must fit in the V tiles");
+    float (*ml)[SP_WAVES][16] = reinterpret_cast<float (*)[SP_WAVES][16]>(vlds + PART_BYTES);
+
+    const int h = blockIdx.x, rt = blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l16 = lane & 15, lg4 = lane >> 4;
+    const int row = rt * 16 + l16;
+
+    MAGE_PROBE_AT(0);
+    const int n_keys = (int)a.nc + a.n_blk;
+    const int ntiles = (n_keys + SP_KT - 1) / SP_KT;
+    const int npass = (ntiles + SP_MAXT - 1) / SP_MAXT;
+    const int tpp = (ntiles + npass - 1) / npass;           // tiles per pass, balanced
+
+    const long long stride = (long long)a.Hkv * D;
+    const u16 *kc = static_cast<const u16 *>(a.kc) + (long long)h * D;
+    const u16 *vc = static_cast<const u16 *>(a.vc) + (long long)h * D;
+    const u16 *kb = static_cast<const u16 *>(a.kblk) + (long long)h * D;
+    const u16 *vb = static_cast<const u16 *>(a.vblk) + (long long)h * D;
+    const int32_t *idx = a.idx + (long long)h * a.nc;
+
+    // query fragment: row l16 of this row tile, channels 32*ks + 8*lg4 .. +7
+    bf16x8_t qf[KS];
+    if (row < a.R) {
+        const int gl = row / a.B, qi = row - gl * a.B;
+        const u16 *src = static_cast<const u16 *>(a.q) + ((long long)qi * a.Hq + (long long)h * a.G + gl) * D + 8 * lg4;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qf[ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(src + ks * 32));
+    } else {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qf[ks] = __builtin_bit_cast(bf16x8_t, make_uint4(0, 0, 0, 0));
+    }
+
+    f32x4_t o[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    float m_run = -INFINITY, l_run = 0.f;       // l_run: this lane's share (its 4 keys per tile)
+
+    for (int pass = 0; pass < npass; ++pass) {
+        const int t0 = pass * tpp;
+        const int t1 = t0 + tpp < ntiles ? t0 + tpp : ntiles;
+        const int first = t0 + wave;                        // this wavefront's tiles: first + 8*j
+        if (first >= t1) continue;                          // nothing for this wavefront in this pass
+        const int my_tiles = (t1 - first + SP_WAVES - 1) / SP_WAVES;
+
+        // ---- issue every load of the pass, branch-free (a branch would make the compiler wait
+        // for all outstanding loads at its join).  A tile slot j >= my_tiles repeats the last
+        // real tile's rows into its own (unused) LDS slot; its scores are masked below. ----
+        // enc: source row of key position tile*16 + l16 (cache row >= 0, block row r as -1-r)
+        int tile_of[SP_TPW], enc[SP_TPW];
+#pragma unroll
+        for (int j = 0; j < SP_TPW; ++j) {
+            tile_of[j] = first + SP_WAVES * (j < my_tiles ? j : my_tiles - 1);
+            int p = tile_of[j] * SP_KT + l16;
+            p = p < n_keys ? p : n_keys - 1;                // padding positions re-read the last key (masked below)
+            const int pc = p < (int)a.nc ? p : (int)a.nc - 1;
+            const int ci = idx[pc];
+            enc[j] = p < (int)a.nc ? ci : -1 - (p - (int)a.nc);
+        }
+        bf16x8_t kf[SP_TPW][KS];
+#pragma unroll
+        for (int j = 0; j < SP_TPW; ++j) {
+            const u16 *src = enc[j] >= 0 ? kc + (long long)enc[j] * stride : kb + (long long)(-1 - enc[j]) * stride;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                kf[j][ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(src + ks * 32 + 8 * lg4));
+        }
+#pragma unroll
+        for (int j = 0; j < SP_TPW; ++j) {
+            unsigned char *dst = vlds + (j * SP_WAVES + wave) * TILE_BYTES;
+#pragma unroll
+            for (int n = 0; n < VLOADS; ++n) {
+                const int r = n * RPL + lane / CH;                           // tile row this lane fetches
+                const int e = __shfl(enc[j], r);
+                const u16 *src = e >= 0 ? vc + (long long)e * stride : vb + (long long)(-1 - e) * stride;
+                const int chunk = (lane % CH) ^ (sp_swz(r) & (CH - 1));
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + chunk * 8),
+                                                 (__attribute__((address_space(3))) void *)(dst + n * 1024), 16, 0, 0);
+            }
+        }
+
+        __builtin_amdgcn_sched_barrier(0);     // keep every load ahead of the first MFMA (and its wait)
+        MAGE_PROBE_AT(1);
+        // ---- scores: sc[j][v] = S^T(key 4*lg4 + v of tile j, query row l16) ----
+        f32x4_t sc[SP_TPW];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < SP_TPW; ++j) {
+            sc[j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) sc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[j][ks], qf[ks], sc[j], 0, 0, 0);
+            const int p0 = tile_of[j] * SP_KT + 4 * lg4;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                if (j >= my_tiles || p0 + v >= n_keys) sc[j][v] = -INFINITY;
+                mx = fmaxf(mx, sc[j][v]);
+            }
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32)) * a.scale_log2;
+        const float m_new = fmaxf(m_run, mx);
+        const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
+        m_run = m_new;
+        float psum = 0.f;
+#pragma unroll
+        for (int j = 0; j < SP_TPW; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float p = __builtin_amdgcn_exp2f(fmaf(sc[j][v], a.scale_log2, -m_new));
+                sc[j][v] = p;
+                psum += p;
+            }
+        l_run = l_run * corr + psum;
+        if (pass > 0) {
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) o[dt] *= corr;
+        }
+
+        MAGE_PROBE_AT(2);
+        // ---- O^T += V^T P^T, 32 key positions (two tiles) per MFMA ----
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // this wavefront's V tiles are in LDS
+        MAGE_PROBE_AT(3);
+        const int jj = l16 >> 2, q = l16 & 3;
+        const int vr = 4 * lg4 + jj;                          // tile row this lane addresses in a transposing read
+#pragma unroll
+        for (int s = 0; s < (SP_TPW + 1) / 2; ++s) {
+            if (2 * s < my_tiles) {   // uniform; after the only wait of the pass
+                bf16x8_t pf;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    pf[e] = (__bf16)sc[2 * s][e];
+                    pf[4 + e] = (2 * s + 1 < SP_TPW) ? (__bf16)sc[2 * s + 1 < SP_TPW ? 2 * s + 1 : 0][e] : (__bf16)0.f;
+                }
+                // a missing second tile contributes zeros through P; its slot repeats a real tile
+                const int ja = 2 * s, jb = (2 * s + 1 < SP_TPW) ? 2 * s + 1 : 2 * s;   // constants after unrolling
+                const unsigned char *ta = vlds + (ja * SP_WAVES + wave) * TILE_BYTES + vr * ROW_BYTES + 8 * (q & 1);
+                const unsigned char *tb = vlds + (jb * SP_WAVES + wave) * TILE_BYTES + vr * ROW_BYTES + 8 * (q & 1);
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) {
+                    const int chunk = ((2 * dt + (q >> 1)) ^ sp_swz(vr)) & (CH - 1);
+                    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t *)(ta + chunk * 16));
+                    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t *)(tb + chunk * 16));
+                    const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, both), pf, o[dt], 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    MAGE_PROBE_AT(4);
+    // ---- merge the eight wavefronts through LDS ----
+    float l_w = l_run + __shfl_xor(l_run, 16);
+    l_w += __shfl_xor(l_w, 32);
+    __syncthreads();                                         // every wavefront is done reading V
+    if (lg4 == 0) {
+        ml[0][wave][l16] = m_run;
+        ml[1][wave][l16] = l_w;
+    }
+    f32x4_t *part = reinterpret_cast<f32x4_t *>(vlds);     // [wave][dt][lane]
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) part[(wave * DT + dt) * 64 + lane] = o[dt];
+    __syncthreads();
+
+    float M = ml[0][0][l16];
+#pragma unroll
+    for (int w = 1; w < SP_WAVES; ++w) M = fmaxf(M, ml[0][w][l16]);
+    float wgt[SP_WAVES], lt = 0.f;
+#pragma unroll
+    for (int w = 0; w < SP_WAVES; ++w) {
+        wgt[w] = __builtin_amdgcn_exp2f(ml[0][w][l16] - M);
+        lt = fmaf(wgt[w], ml[1][w][l16], lt);
+    }
+    if (row >= a.R) return;
+    const int gl = row / a.B, qi = row - gl * a.B;
+    const long long orow = (long long)qi * a.Hq + (long long)h * a.G + gl;
+    const float inv = 1.f / lt;
+    for (int dt = wave; dt < DT; dt += SP_WAVES) {
+        f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int w = 0; w < SP_WAVES; ++w) acc += part[(w * DT + dt) * 64 + lane] * wgt[w];
+        *reinterpret_cast<f32x4_t *>(a.out + orow * D + 16 * dt + 4 * lg4) = acc * inv;
+    }
+    MAGE_PROBE_AT(5);
+    if (a.lse_out && wave == 0 && lg4 == 0) a.lse_out[orow] = (M + log2f(lt)) * 0.6931471805599453f;
+}
+
+hipError_t bf16_sparse(const KernelArgs &a, int d, hipStream_t stream)
+{
+    dim3 grid(a.Hkv, (a.R + 15) / 16), block(SP_WAVES * 64);
+    if (d == 128) hipLaunchKernelGGL((sparse_bf16_kernel<128>), grid, block, 0, stream, a);
+    else if (d == 64) hipLaunchKernelGGL((sparse_bf16_kernel<64>), grid, block, 0, stream, a);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+}  // namespace mage

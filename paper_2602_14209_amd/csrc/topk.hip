@@ -1,0 +1,282 @@
+// Exact per-KV-head top-k of alpha[h, 0..L) for gfx950 (Alg. 1 "S <- Top-k(alpha)", Eq. 5):
+// the k positions with the largest fp32 value, equal values to the smaller index, indices
+// emitted in ascending order.  alpha >= 0, so the order of the fp32 bit patterns as unsigned
+// integers is the order of the values.
+//
+// One workgroup of 1024 threads per KV head.  Two routes, chosen per head at run time:
+//   filter route (k small against L, the method's regime): the k-th largest of 8192 strided
+//     group maxima is a lower bound of the k-th largest element, so one more sweep keeps only
+//     the few elements at or above it; those are sorted in LDS by (value desc, index asc), the
+//     first k taken and sorted by index.
+//   radix route (any k, any tie structure; also the overflow exit of the filter route): three
+//     MSB-first radix-select steps over the whole row find the k-th value and the number of
+//     ties to keep, then an ordered sweep emits the set.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mage {
+
+constexpr int TK_THREADS = 1024;
+constexpr int TK_WAVES = TK_THREADS / 64;
+constexpr int TK_BINS = 4096;                        // widest digit: 12 bits
+constexpr int TK_EPT = 16;                           // consecutive elements per thread in the ordered sweep
+constexpr int TK_SLOTS = 8;                          // group maxima per thread = loads in flight per thread
+constexpr int TK_GROUPS = TK_THREADS * TK_SLOTS;     // 8192
+constexpr int TK_CAND = 4096;                        // candidate capacity of the filter route
+constexpr int TK_FILTER_MAX_K = 2048;
+
+// inclusive scan of one value per thread over the workgroup; returns this thread's inclusive
+// prefix and the workgroup total.  `tmp` holds TK_WAVES+1 entries.
+__device__ __forceinline__ uint32_t block_scan_incl(uint32_t v, uint32_t *tmp, uint32_t &total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t x = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t y = __shfl_up(x, d);
+        if (lane >= d) x += y;
+    }
+    __syncthreads();                      // tmp may still be read from a previous call
+    if (lane == 63) tmp[wave] = x;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t run = 0;
+        for (int w = 0; w < TK_WAVES; ++w) {
+            const uint32_t t = tmp[w];
+            tmp[w] = run;
+            run += t;
+        }
+        tmp[TK_WAVES] = run;
+    }
+    __syncthreads();
+    total = tmp[TK_WAVES];
+    return x + tmp[wave];
+}
+
+// One radix step over n elements of u (global or LDS): histogram the `bits`-wide digit at
+// `shift` of every element whose higher bits equal `prefix`, then pick the digit in which the
+// `want`-th largest element falls.  On return prefix has that digit appended and want is the
+// rank inside the digit's bucket.
+__device__ __forceinline__ void radix_step(const uint32_t *u, long long n, int shift, int bits,
+                                           uint32_t &prefix, uint32_t &want,
+                                           uint32_t *hist, uint32_t *tmp, uint32_t *bcast)
+{
+    const int nb = 1 << bits;
+    const uint32_t hi_mask = (shift + bits >= 32) ? 0u : (0xffffffffu << (shift + bits));
+    for (int b = threadIdx.x; b < nb; b += TK_THREADS) hist[b] = 0;
+    __syncthreads();
+    constexpr int UNR = 8;      // independent loads in flight per thread
+    for (long long j0 = threadIdx.x; j0 < n; j0 += (long long)TK_THREADS * UNR) {
+        uint32_t x[UNR];
+#pragma unroll
+        for (int i = 0; i < UNR; ++i) {
+            const long long j = j0 + (long long)i * TK_THREADS;
+            x[i] = j < n ? u[j] : 0xffffffffu;
+        }
+#pragma unroll
+        for (int i = 0; i < UNR; ++i) {
+            const long long j = j0 + (long long)i * TK_THREADS;
+            if (j < n && (x[i] & hi_mask) == prefix) atomicAdd(&hist[(x[i] >> shift) & (nb - 1)], 1u);
+        }
+    }
+    __syncthreads();
+    // thread t owns bins [t*per, (t+1)*per) counted from the TOP digit downwards
+    const int per = (nb + TK_THREADS - 1) / TK_THREADS;
+    uint32_t mine = 0;
+    for (int i = 0; i < per; ++i) {
+        const int b = nb - 1 - (threadIdx.x * per + i);
+        if (b >= 0) mine += hist[b];
+    }
+    uint32_t total;
+    const uint32_t incl = block_scan_incl(mine, tmp, total);
+    const uint32_t excl = incl - mine;
+    if (excl < want && want <= incl) {     // exactly one thread: the bucket lies in its bins
+        uint32_t run = excl;
+        for (int i = 0; i < per; ++i) {
+            const int b = nb - 1 - (threadIdx.x * per + i);
+            if (b < 0) break;
+            const uint32_t c = hist[b];
+            if (run < want && want <= run + c) {
+                bcast[0] = (uint32_t)b;
+                bcast[1] = want - run;
+                break;
+            }
+            run += c;
+        }
+    }
+    __syncthreads();
+    prefix |= bcast[0] << shift;
+    want = bcast[1];
+    __syncthreads();
+}
+
+// ascending bitonic sort of a[0..P) in LDS, P a power of two; every thread of the workgroup calls
+template <class T>
+__device__ __forceinline__ void bitonic_sort(T *a, int P)
+{
+    for (int k2 = 2; k2 <= P; k2 <<= 1)
+        for (int j = k2 >> 1; j > 0; j >>= 1) {
+            __syncthreads();
+            for (int i = threadIdx.x; i < P / 2; i += TK_THREADS) {
+                const int lo = ((i & ~(j - 1)) << 1) | (i & (j - 1)), hi = lo | j;
+                const bool up = (lo & k2) == 0;
+                const T x = a[lo], y = a[hi];
+                if ((x > y) == up) {
+                    a[lo] = y;
+                    a[hi] = x;
+                }
+            }
+        }
+    __syncthreads();
+}
+
+// elements j..j+3 of row u (zero past the end); one 16-byte load when the row allows it
+__device__ __forceinline__ uint4 load4(const uint32_t *u, long long j, long long L, bool vec_ok)
+{
+    if (vec_ok) return j < L ? *reinterpret_cast<const uint4 *>(u + j) : make_uint4(0, 0, 0, 0);
+    uint4 r;
+    r.x = j < L ? u[j] : 0u;
+    r.y = j + 1 < L ? u[j + 1] : 0u;
+    r.z = j + 2 < L ? u[j + 2] : 0u;
+    r.w = j + 3 < L ? u[j + 3] : 0u;
+    return r;
+}
+
+__device__ __forceinline__ int pow2_at_least(int n)
+{
+    int p = 2;
+    while (p < n) p <<= 1;
+    return p;
+}
+
+__global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, long long L, int k, int32_t *idx_out)
+{
+    __shared__ uint32_t hist[TK_BINS];
+    __shared__ uint32_t tmp[TK_WAVES + 1];
+    __shared__ uint32_t tmp2[TK_WAVES + 1];
+    __shared__ uint32_t bcast[2];
+    __shared__ uint32_t n_cand;
+    __shared__ uint32_t gmax[TK_GROUPS];                 // group maxima, later the index sort buffer
+    __shared__ unsigned long long cand[TK_CAND];         // (~value bits) << 32 | index
+
+    const int h = blockIdx.x;
+    const uint32_t *u = reinterpret_cast<const uint32_t *>(alpha) + (long long)h * L;
+    int32_t *out = idx_out + (long long)h * k;
+
+    if (k <= TK_FILTER_MAX_K) {
+        // ---- filter route, sweep 1: strided group maxima (group = slot * 1024 + thread) ----
+        // each thread takes 4 consecutive elements per slot (one 16-byte load when the row is aligned)
+        const bool vec_ok = (L & 3) == 0 && (reinterpret_cast<uintptr_t>(u) & 15) == 0;
+        uint32_t gm[TK_SLOTS];
+#pragma unroll
+        for (int s = 0; s < TK_SLOTS; ++s) gm[s] = 0u;
+        for (long long base0 = 0; base0 < L; base0 += 4ll * TK_GROUPS) {
+            uint4 x[TK_SLOTS];
+#pragma unroll
+            for (int s = 0; s < TK_SLOTS; ++s) x[s] = load4(u, base0 + 4ll * (s * TK_THREADS + threadIdx.x), L, vec_ok);
+#pragma unroll
+            for (int s = 0; s < TK_SLOTS; ++s) {
+                const uint32_t a = x[s].x > x[s].y ? x[s].x : x[s].y, b = x[s].z > x[s].w ? x[s].z : x[s].w;
+                const uint32_t c = a > b ? a : b;
+                gm[s] = c > gm[s] ? c : gm[s];
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < TK_SLOTS; ++s) gmax[s * TK_THREADS + threadIdx.x] = gm[s];
+        if (threadIdx.x == 0) n_cand = 0;
+        __syncthreads();
+        // a lower bound of the k-th largest group maximum (its top 20 bits), hence of the k-th
+        // largest element: at least k elements are >= floor_bits
+        uint32_t floor_bits = 0, rank = (uint32_t)k;
+        radix_step(gmax, TK_GROUPS, 20, 12, floor_bits, rank, hist, tmp, bcast);
+        radix_step(gmax, TK_GROUPS, 12, 8, floor_bits, rank, hist, tmp, bcast);
+
+        // ---- sweep 2: keep the elements at or above the bound ----
+        const int lane = threadIdx.x & 63;
+        for (long long base0 = 0; base0 < L; base0 += 4ll * TK_GROUPS) {      // uniform trip count
+            uint4 x[TK_SLOTS];
+#pragma unroll
+            for (int s = 0; s < TK_SLOTS; ++s) x[s] = load4(u, base0 + 4ll * (s * TK_THREADS + threadIdx.x), L, vec_ok);
+#pragma unroll
+            for (int s = 0; s < TK_SLOTS; ++s) {
+                const long long j = base0 + 4ll * (s * TK_THREADS + threadIdx.x);
+                const uint32_t xs[4] = {x[s].x, x[s].y, x[s].z, x[s].w};
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const bool keep = j + c < L && xs[c] >= floor_bits;
+                    const unsigned long long bal = __ballot(keep);
+                    if (bal) {                           // wavefront-aggregated append
+                        uint32_t base = 0;
+                        if (lane == 0) base = atomicAdd(&n_cand, (uint32_t)__popcll(bal));
+                        base = __shfl(base, 0);
+                        const uint32_t pos = base + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
+                        if (keep && pos < TK_CAND) cand[pos] = ((unsigned long long)(~xs[c]) << 32) | (uint32_t)(j + c);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        const uint32_t nc = n_cand;
+        if (nc <= TK_CAND) {
+            const int P = pow2_at_least((int)nc);
+            for (int i = nc + threadIdx.x; i < P; i += TK_THREADS) cand[i] = ~0ull;
+            bitonic_sort(cand, P);                       // value descending, index ascending
+            int32_t *sidx = reinterpret_cast<int32_t *>(gmax);
+            const int P2 = pow2_at_least(k);
+            for (int i = threadIdx.x; i < P2; i += TK_THREADS) sidx[i] = i < k ? (int32_t)(uint32_t)cand[i] : 0x7fffffff;
+            bitonic_sort(sidx, P2);
+            for (int i = threadIdx.x; i < k; i += TK_THREADS) out[i] = sidx[i];
+            return;
+        }
+        __syncthreads();                                 // too many ties at the bound: radix route
+    }
+
+    // ---- radix route: threshold = bit pattern of the k-th largest value; want = how many
+    // elements equal to it belong to the set (those with the smallest indices) ----
+    uint32_t prefix = 0, want = (uint32_t)k;
+    radix_step(u, L, 20, 12, prefix, want, hist, tmp, bcast);
+    radix_step(u, L, 10, 10, prefix, want, hist, tmp, bcast);
+    radix_step(u, L, 0, 10, prefix, want, hist, tmp, bcast);
+    const uint32_t thr = prefix;
+
+    // ordered sweep: element j goes to slot (#greater before j) + min(#equal before j, want)
+    uint32_t base_gt = 0, base_eq = 0;
+    for (long long c0 = 0; c0 < L; c0 += (long long)TK_THREADS * TK_EPT) {
+        const long long j0 = c0 + (long long)threadIdx.x * TK_EPT;
+        uint32_t x[TK_EPT];
+        uint32_t ngt = 0, neq = 0;
+#pragma unroll
+        for (int i = 0; i < TK_EPT; ++i) {
+            x[i] = (j0 + i < L) ? u[j0 + i] : 0u;
+            const bool in = j0 + i < L;
+            ngt += (in && x[i] > thr) ? 1u : 0u;
+            neq += (in && x[i] == thr) ? 1u : 0u;
+        }
+        uint32_t tot_gt, tot_eq;
+        const uint32_t pre_gt = block_scan_incl(ngt, tmp, tot_gt) - ngt + base_gt;
+        const uint32_t pre_eq = block_scan_incl(neq, tmp2, tot_eq) - neq + base_eq;
+        uint32_t g = pre_gt, e = pre_eq;
+#pragma unroll
+        for (int i = 0; i < TK_EPT; ++i) {
+            if (j0 + i < L) {
+                if (x[i] > thr) {
+                    out[g + (e < want ? e : want)] = (int32_t)(j0 + i);
+                    ++g;
+                } else if (x[i] == thr) {
+                    if (e < want) out[g + e] = (int32_t)(j0 + i);
+                    ++e;
+                }
+            }
+        }
+        base_gt += tot_gt;
+        base_eq += tot_eq;
+    }
+}
+
+hipError_t launch_topk(const float *alpha, int Hkv, long long L, int k, int32_t *idx_out, hipStream_t stream)
+{
+    hipLaunchKernelGGL(topk_kernel, dim3(Hkv), dim3(TK_THREADS), 0, stream, alpha, L, k, idx_out);
+    return hipGetLastError();
+}
+
+}  // namespace mage

@@ -77,4 +77,7 @@ def test_null_alignment_and_workspace_errors():
     assert L.mage_exact_attn(ctypes.byref(s), fake, fake, odd, fake, fake, fake, None, fake, big, None) == -6
     assert L.mage_exact_attn(ctypes.byref(s), fake, fake, fake, fake, fake, fake, None, fake, 16, None) == -4
     assert L.mage_sparse_attn(ctypes.byref(s), fake, fake, fake, None, fake, fake, fake, None, fake, big, None) == -1
-    assert L.mage_sparse_attn(ctypes.byref(s), fake, fake, fake, fake, fake, fake, fake, None, fake, 16, None) == -4
+    # the bf16 sparse step keeps its partials on chip and needs no workspace; the fp32 one does
+    sf = mb.make_shape(32, 32, 8, 128, 4096, 512, "f32")
+    assert L.mage_sparse_attn(ctypes.byref(sf), fake, fake, fake, fake, fake, fake, fake, None, fake, 16, None) == -4
+    assert L.mage_sparse_attn(ctypes.byref(s), fake, fake, odd, fake, fake, fake, fake, None, None, 0, None) == -6
