@@ -9,25 +9,34 @@
 
 namespace mage {
 
-// One thread per (row, 4 channels).  Split s contributes weight exp2(m_s - M).
+// One workgroup per (query row, KV head): 256 threads = D/4 channel quads x SG split groups.
+// Split s contributes weight exp2(m_s - M); group g walks splits g, g+SG, ... with all its loads
+// in flight, then the groups are added in a fixed order through LDS.
 template <int D>
 __global__ __launch_bounds__(256) void combine_kernel(const KernelArgs a)
 {
-    constexpr int TPR = D / 4;                 // threads per row
-    constexpr int ROWS = 256 / TPR;            // rows per workgroup
-    const int h = blockIdx.y;
-    const int row = blockIdx.x * ROWS + threadIdx.x / TPR;
-    const int c4 = threadIdx.x % TPR;
-    if (row >= a.R) return;
+    constexpr int TPR = D / 4;                 // threads per row of channels
+    constexpr int SG = 256 / TPR;              // split groups
+    __shared__ float red_m[4];
+    __shared__ float4 red_o[SG][TPR];
+    __shared__ float red_l[SG];
+    const int row = blockIdx.x, h = blockIdx.y;
+    const int c4 = threadIdx.x % TPR, sg = threadIdx.x / TPR;
+    const long long base = (long long)h * a.n_split * a.rpad + row;
 
     float M = -INFINITY;
-#pragma unroll 8
-    for (int s = 0; s < a.n_split; ++s) M = fmaxf(M, a.part_m[((long long)h * a.n_split + s) * a.rpad + row]);
+    for (int s = threadIdx.x; s < a.n_split; s += 256) M = fmaxf(M, a.part_m[base + (long long)s * a.rpad]);
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) M = fmaxf(M, __shfl_xor(M, d));
+    if ((threadIdx.x & 63) == 0) red_m[threadIdx.x >> 6] = M;
+    __syncthreads();
+    M = fmaxf(fmaxf(red_m[0], red_m[1]), fmaxf(red_m[2], red_m[3]));
+
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     float lt = 0.f;
-#pragma unroll 8
-    for (int s = 0; s < a.n_split; ++s) {
-        const long long pi = ((long long)h * a.n_split + s) * a.rpad + row;
+#pragma unroll 4
+    for (int s = sg; s < a.n_split; s += SG) {
+        const long long pi = base + (long long)s * a.rpad;
         const float w = exp2f(a.part_m[pi] - M);
         lt = fmaf(w, a.part_l[pi], lt);
         const float4 v = *reinterpret_cast<const float4 *>(a.part_o + pi * D + c4 * 4);
@@ -35,6 +44,21 @@ __global__ __launch_bounds__(256) void combine_kernel(const KernelArgs a)
         acc.y = fmaf(w, v.y, acc.y);
         acc.z = fmaf(w, v.z, acc.z);
         acc.w = fmaf(w, v.w, acc.w);
+    }
+    red_o[sg][c4] = acc;
+    if (c4 == 0) red_l[sg] = lt;
+    __syncthreads();
+    if (sg != 0) return;
+    acc = red_o[0][c4];
+    lt = red_l[0];
+#pragma unroll
+    for (int g = 1; g < SG; ++g) {
+        const float4 v = red_o[g][c4];
+        acc.x += v.x;
+        acc.y += v.y;
+        acc.z += v.z;
+        acc.w += v.w;
+        lt += red_l[g];
     }
     const float inv = 1.f / lt;
     const int gl = row / a.B, qi = row - gl * a.B;
@@ -67,8 +91,7 @@ __global__ __launch_bounds__(256) void lse_kernel(const KernelArgs a, float *lse
 
 hipError_t launch_combine(const KernelArgs &a, int d, hipStream_t stream)
 {
-    const int rows_per_wg = 256 / (d / 4);
-    dim3 grid((a.R + rows_per_wg - 1) / rows_per_wg, a.Hkv), block(256);
+    dim3 grid(a.R, a.Hkv), block(256);
     if (d == 128) hipLaunchKernelGGL((combine_kernel<128>), grid, block, 0, stream, a);
     else if (d == 64) hipLaunchKernelGGL((combine_kernel<64>), grid, block, 0, stream, a);
     else return hipErrorInvalidValue;

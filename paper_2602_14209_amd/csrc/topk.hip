@@ -14,6 +14,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "probe.hpp"
+
 namespace mage {
 
 constexpr int TK_THREADS = 1024;
@@ -99,6 +101,7 @@ __device__ __forceinline__ void radix_step(const uint32_t *u, long long n, int s
             if (run < want && want <= run + c) {
                 bcast[0] = (uint32_t)b;
                 bcast[1] = want - run;
+                bcast[2] = c;
                 break;
             }
             run += c;
@@ -110,13 +113,19 @@ __device__ __forceinline__ void radix_step(const uint32_t *u, long long n, int s
     __syncthreads();
 }
 
-// ascending bitonic sort of a[0..P) in LDS, P a power of two; every thread of the workgroup calls
+// ascending bitonic sort of a[0..P) in LDS, P a power of two; every thread of the workgroup calls.
+// Thread t owns compare-exchange pairs t, t+1024, ...; for distances j <= 32 the 64 pairs of a
+// wavefront touch only that wavefront's own 128 elements, so those stages need no workgroup
+// barrier (LDS operations of one wavefront execute in order).
 template <class T>
 __device__ __forceinline__ void bitonic_sort(T *a, int P)
 {
+    bool need_barrier = true;
     for (int k2 = 2; k2 <= P; k2 <<= 1)
         for (int j = k2 >> 1; j > 0; j >>= 1) {
-            __syncthreads();
+            if (j >= 64 || need_barrier) __syncthreads();
+            else __builtin_amdgcn_wave_barrier();
+            need_barrier = j >= 64;          // the stage after a cross-wavefront stage must see its writes
             for (int i = threadIdx.x; i < P / 2; i += TK_THREADS) {
                 const int lo = ((i & ~(j - 1)) << 1) | (i & (j - 1)), hi = lo | j;
                 const bool up = (lo & k2) == 0;
@@ -154,15 +163,17 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, lo
     __shared__ uint32_t hist[TK_BINS];
     __shared__ uint32_t tmp[TK_WAVES + 1];
     __shared__ uint32_t tmp2[TK_WAVES + 1];
-    __shared__ uint32_t bcast[2];
+    __shared__ uint32_t bcast[3];                        // chosen digit, rank inside its bucket, bucket size
     __shared__ uint32_t n_cand;
     __shared__ uint32_t gmax[TK_GROUPS];                 // group maxima, later the index sort buffer
-    __shared__ unsigned long long cand[TK_CAND];         // (~value bits) << 32 | index
+    __shared__ uint32_t cval[TK_CAND];                   // candidate values (fp32 bit patterns)
+    __shared__ uint32_t cidx[TK_CAND];                   // and their positions
 
     const int h = blockIdx.x;
     const uint32_t *u = reinterpret_cast<const uint32_t *>(alpha) + (long long)h * L;
     int32_t *out = idx_out + (long long)h * k;
 
+    MAGE_PROBE_AT(0);
     if (k <= TK_FILTER_MAX_K) {
         // ---- filter route, sweep 1: strided group maxima (group = slot * 1024 + thread) ----
         // each thread takes 4 consecutive elements per slot (one 16-byte load when the row is aligned)
@@ -185,47 +196,120 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, lo
         for (int s = 0; s < TK_SLOTS; ++s) gmax[s * TK_THREADS + threadIdx.x] = gm[s];
         if (threadIdx.x == 0) n_cand = 0;
         __syncthreads();
+        MAGE_PROBE_AT(1);
         // a lower bound of the k-th largest group maximum (its top 20 bits), hence of the k-th
         // largest element: at least k elements are >= floor_bits
         uint32_t floor_bits = 0, rank = (uint32_t)k;
         radix_step(gmax, TK_GROUPS, 20, 12, floor_bits, rank, hist, tmp, bcast);
         radix_step(gmax, TK_GROUPS, 12, 8, floor_bits, rank, hist, tmp, bcast);
 
+        MAGE_PROBE_AT(2);
         // ---- sweep 2: keep the elements at or above the bound ----
         const int lane = threadIdx.x & 63;
         for (long long base0 = 0; base0 < L; base0 += 4ll * TK_GROUPS) {      // uniform trip count
             uint4 x[TK_SLOTS];
 #pragma unroll
             for (int s = 0; s < TK_SLOTS; ++s) x[s] = load4(u, base0 + 4ll * (s * TK_THREADS + threadIdx.x), L, vec_ok);
+            // count this lane's keepers, reserve room for the whole wavefront with one atomic
+            uint32_t cnt = 0;
 #pragma unroll
             for (int s = 0; s < TK_SLOTS; ++s) {
                 const long long j = base0 + 4ll * (s * TK_THREADS + threadIdx.x);
-                const uint32_t xs[4] = {x[s].x, x[s].y, x[s].z, x[s].w};
+                cnt += (j < L && x[s].x >= floor_bits) + (j + 1 < L && x[s].y >= floor_bits) +
+                       (j + 2 < L && x[s].z >= floor_bits) + (j + 3 < L && x[s].w >= floor_bits);
+            }
+            uint32_t incl = cnt;
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const bool keep = j + c < L && xs[c] >= floor_bits;
-                    const unsigned long long bal = __ballot(keep);
-                    if (bal) {                           // wavefront-aggregated append
-                        uint32_t base = 0;
-                        if (lane == 0) base = atomicAdd(&n_cand, (uint32_t)__popcll(bal));
-                        base = __shfl(base, 0);
-                        const uint32_t pos = base + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
-                        if (keep && pos < TK_CAND) cand[pos] = ((unsigned long long)(~xs[c]) << 32) | (uint32_t)(j + c);
-                    }
+            for (int d = 1; d < 64; d <<= 1) {
+                const uint32_t y = __shfl_up(incl, d);
+                if (lane >= d) incl += y;
+            }
+            const uint32_t wave_total = __shfl(incl, 63);
+            if (wave_total == 0) continue;                 // uniform per wavefront
+            uint32_t base = 0;
+            if (lane == 0) base = atomicAdd(&n_cand, wave_total);
+            uint32_t pos = __shfl(base, 0) + incl - cnt;
+            if (cnt) {
+#pragma unroll
+                for (int s = 0; s < TK_SLOTS; ++s) {
+                    const long long j = base0 + 4ll * (s * TK_THREADS + threadIdx.x);
+                    const uint32_t xs[4] = {x[s].x, x[s].y, x[s].z, x[s].w};
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        if (j + c < L && xs[c] >= floor_bits) {
+                            if (pos < TK_CAND) {
+                                cval[pos] = xs[c];
+                                cidx[pos] = (uint32_t)(j + c);
+                            }
+                            ++pos;
+                        }
                 }
             }
         }
         __syncthreads();
+        MAGE_PROBE_AT(3);
         const uint32_t nc = n_cand;
         if (nc <= TK_CAND) {
-            const int P = pow2_at_least((int)nc);
-            for (int i = nc + threadIdx.x; i < P; i += TK_THREADS) cand[i] = ~0ull;
-            bitonic_sort(cand, P);                       // value descending, index ascending
+            // exact k-th value among the candidates (radix select in LDS) and the number of
+            // candidates equal to it that belong to the set (the ones with the smallest positions)
+            uint32_t thr = 0, want = (uint32_t)k;
+            radix_step(cval, nc, 20, 12, thr, want, hist, tmp, bcast);
+            radix_step(cval, nc, 10, 10, thr, want, hist, tmp, bcast);
+            radix_step(cval, nc, 0, 10, thr, want, hist, tmp, bcast);
+            const uint32_t n_equal = bcast[2];
+            __syncthreads();
+            const bool bitmap = L <= (long long)TK_GROUPS * 32;
+            uint32_t *bits = gmax;                           // reuses the group-maxima buffer
             int32_t *sidx = reinterpret_cast<int32_t *>(gmax);
+            const int words = (int)((L + 31) >> 5);
             const int P2 = pow2_at_least(k);
-            for (int i = threadIdx.x; i < P2; i += TK_THREADS) sidx[i] = i < k ? (int32_t)(uint32_t)cand[i] : 0x7fffffff;
-            bitonic_sort(sidx, P2);
-            for (int i = threadIdx.x; i < k; i += TK_THREADS) out[i] = sidx[i];
+            if (bitmap) for (int i = threadIdx.x; i < words; i += TK_THREADS) bits[i] = 0u;
+            else for (int i = threadIdx.x; i < P2; i += TK_THREADS) sidx[i] = 0x7fffffff;
+            if (threadIdx.x == 0) n_cand = 0;                // now counts the winners (index-sort route)
+            __syncthreads();
+            for (uint32_t i = threadIdx.x; i < nc; i += TK_THREADS) {
+                const uint32_t v = cval[i], j = cidx[i];
+                bool take = v > thr;
+                if (v == thr) {
+                    take = true;
+                    if (n_equal != want) {                   // ties cut: keep the `want` smallest positions
+                        uint32_t below = 0;
+                        for (uint32_t t = 0; t < nc; ++t) below += (cval[t] == thr && cidx[t] < j);
+                        take = below < want;
+                    }
+                }
+                if (take) {
+                    if (bitmap) atomicOr(&bits[j >> 5], 1u << (j & 31));
+                    else sidx[atomicAdd(&n_cand, 1u)] = (int32_t)j;
+                }
+            }
+            __syncthreads();
+            if (bitmap) {
+                // ascending order by walking the bitmap of the L positions
+                const int wpt = (words + TK_THREADS - 1) / TK_THREADS;      // consecutive words per thread (<= 8)
+                uint32_t mine = 0;
+                for (int i = 0; i < wpt; ++i) {
+                    const int wi = threadIdx.x * wpt + i;
+                    if (wi < words) mine += __popc(bits[wi]);
+                }
+                uint32_t total;
+                uint32_t pos = block_scan_incl(mine, tmp, total) - mine;
+                for (int i = 0; i < wpt; ++i) {
+                    const int wi = threadIdx.x * wpt + i;
+                    if (wi < words) {
+                        uint32_t b = bits[wi];
+                        while (b) {
+                            const int bit = __ffs(b) - 1;
+                            out[pos++] = (int32_t)(wi * 32 + bit);
+                            b &= b - 1;
+                        }
+                    }
+                }
+            } else {
+                bitonic_sort(sidx, P2);
+                for (int i = threadIdx.x; i < k; i += TK_THREADS) out[i] = sidx[i];
+            }
+            MAGE_PROBE_AT(4);
             return;
         }
         __syncthreads();                                 // too many ties at the bound: radix route
