@@ -85,10 +85,43 @@ __device__ __forceinline__ void issue_tile(const u16 *kbase, const u16 *vbase, l
     }
 }
 
-// wait for this wavefront's outstanding HBM->LDS loads, then meet the rest of the workgroup
+// The same for a full tile of contiguous cache rows: `kptr[n]` is this lane's source address for
+// load n at the first tile of the split (computed once); tile t lies t * 64 rows further on.
+template <int D, int NW, bool WITH_V>
+__device__ __forceinline__ void issue_tile_stream(const u16 *const (&kptr)[TileGeom<D>::LOADS / NW], long long tile_elems,
+                                                  long long v_minus_k, int t, unsigned char *buf)
+{
+    using G = TileGeom<D>;
+    const int wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int n = 0; n < G::LOADS / NW; ++n) {
+        const int unit = n * NW + wave;
+        const u16 *src = kptr[n] + t * tile_elems;
+        __builtin_amdgcn_global_load_lds(MAGE_GLOBAL_PTR(src), MAGE_LDS_PTR(buf + unit * 1024), 16, 0, 0);
+        if (WITH_V)
+            __builtin_amdgcn_global_load_lds(MAGE_GLOBAL_PTR(src + v_minus_k), MAGE_LDS_PTR(buf + G::MAT_BYTES + unit * 1024), 16, 0, 0);
+    }
+}
+
+template <int D, int NW>
+__device__ __forceinline__ void stream_pointers(const u16 *kc, long long c0, long long row_stride,
+                                                const u16 *(&kptr)[TileGeom<D>::LOADS / NW])
+{
+    using G = TileGeom<D>;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int n = 0; n < G::LOADS / NW; ++n) {
+        const int r = (n * NW + wave) * G::RPI + lane / G::CH;
+        kptr[n] = kc + (c0 + r) * row_stride + ((lane % G::CH) ^ swz<D>(r)) * 8;
+    }
+}
+
+// Wait until at most PENDING of this wavefront's HBM->LDS loads are outstanding (loads complete in
+// issue order, so the oldest tile has landed), then meet the rest of the workgroup.
+template <int PENDING>
 __device__ __forceinline__ void tile_barrier()
 {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PENDING) : "memory");
     __syncthreads();
 }
 
@@ -158,15 +191,17 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 {
     using G = TileGeom<D>;
     constexpr bool WITH_V = (MODE == MODE_ATTN);
+    constexpr int NBUF = WITH_V ? 2 : 3;                            // LDS tile buffers = prefetch distance + 1
+    constexpr int LPT = (G::LOADS / NW) * (WITH_V ? 2 : 1);         // loads one wavefront issues per tile
     constexpr int KS = D / 16;     // MFMA k-steps over the head dimension
     constexpr int DT = D / 32;     // 32-row tiles of O^T
     constexpr int BUF_BYTES = G::MAT_BYTES * (WITH_V ? 2 : 1);
     constexpr int OST = D + 4;     // floats per staged output row
     constexpr int STAGE_BYTES = WITH_V ? 2 * 32 * OST * 4 : 0;
-    static_assert(2 * BUF_BYTES >= STAGE_BYTES, "output staging must fit in the tile buffers");
+    static_assert(NBUF * BUF_BYTES >= STAGE_BYTES, "output staging must fit in the tile buffers");
 
-    // two tile buffers; after the key loop the same memory stages the output transposition
-    __shared__ __attribute__((aligned(1024))) unsigned char smem[2 * BUF_BYTES];
+    // tile buffers; after the key loop the same memory stages the output transposition
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[NBUF * BUF_BYTES];
 
     const int h = blockIdx.x, split = blockIdx.y, rg = blockIdx.z;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -194,10 +229,16 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
         const int left = a.n_blk - (t - sr.cache_tiles) * kBf16Tile;
         return left < kBf16Tile ? left : kBf16Tile;
     };
+    const u16 *kptr[G::LOADS / NW];
+    if (!GATHER) stream_pointers<D, NW>(kc, sr.c0, cache_stride, kptr);
+    const long long tile_elems = (long long)kBf16Tile * cache_stride;
+    const long long v_minus_k = vc - kc;
     auto issue = [&](int t) {
         const int valid = tile_valid(t);
-        unsigned char *buf = smem + (t & 1) * BUF_BYTES;
-        if (t < sr.cache_tiles) {
+        unsigned char *buf = smem + (t % NBUF) * BUF_BYTES;
+        if (!GATHER && t < sr.cache_tiles && valid == kBf16Tile) {
+            issue_tile_stream<D, NW, WITH_V>(kptr, tile_elems, v_minus_k, t, buf);
+        } else if (t < sr.cache_tiles) {
             const long long base = sr.c0 + (long long)t * kBf16Tile;
             issue_tile<D, NW, WITH_V>(kc, vc, cache_stride, buf, [&](int r) -> long long {
                 const long long pos = base + (r < valid ? r : valid - 1);
@@ -209,7 +250,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
         }
     };
 
-    if (ntiles > 0) issue(0);          // first: the longest dependent chain (index -> row)
+#pragma unroll
+    for (int t = 0; t < NBUF - 1; ++t)
+        if (t < ntiles) issue(t);      // first: the longest dependent chain (index -> row)
 
     bf16x8_t qf[KS];
     load_q_frag<D>(a, h, row, qf);
@@ -222,14 +265,20 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     float m_run = -INFINITY, l_run = 0.f;     // running max (log2 domain) and this lane's share of the normaliser
 
     for (int t = 0; t < ntiles; ++t) {
-        tile_barrier();                        // tile t landed; everyone is done with tile t-1
+        // tile t landed (NBUF-2 younger tiles may still be in flight); everyone is done with tile t-1
+        if (t + NBUF - 2 < ntiles) tile_barrier<(NBUF - 2) * LPT>();
+        else tile_barrier<0>();
         if (t == 0) MAGE_PROBE_AT(1);
-        if (t + 1 < ntiles) issue(t + 1);
+        if (t + NBUF - 1 < ntiles) issue(t + NBUF - 1);
         const int valid = tile_valid(t);
-        const unsigned char *kbuf = smem + (t & 1) * BUF_BYTES;
+        const unsigned char *kbuf = smem + (t % NBUF) * BUF_BYTES;
         const unsigned char *vbuf = kbuf + G::MAT_BYTES;
 
+#ifdef MAGE_PROBE_NO_COMPUTE
+        if (false) {
+#else
         if (wave_active) {
+#endif
             // S^T tile: sc[kt][v] = score of query row l32 against key kt*32 + 8*(v/4) + 4*lg + v%4
             f32x16_t sc[2];
 #pragma unroll
@@ -242,7 +291,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 #pragma unroll
                 for (int s = 0; s < KS; ++s) sc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[s], sc[kt], 0, 0, 0);
             }
-            if (valid < kBf16Tile) {
+            if (valid < kBf16Tile) {           // uniform: only the last tile of a slice has padding keys
 #pragma unroll
                 for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
@@ -363,7 +412,9 @@ __global__ __launch_bounds__(NW * 64) void colsum_bf16_kernel(const KernelArgs a
     using G = TileGeom<D>;
     constexpr int KS = D / 16;
     constexpr int BUF_BYTES = G::MAT_BYTES;
-    __shared__ __attribute__((aligned(1024))) unsigned char smem[2 * BUF_BYTES];
+    constexpr int NBUF = 3;                                         // LDS tile buffers = prefetch distance + 1
+    constexpr int LPT = G::LOADS / NW;                              // loads one wavefront issues per tile
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[NBUF * BUF_BYTES];
     __shared__ float red[2][NW][kBf16Tile];
 
     const int h = blockIdx.x, split = blockIdx.y;
@@ -381,13 +432,22 @@ __global__ __launch_bounds__(NW * 64) void colsum_bf16_kernel(const KernelArgs a
         const long long left = sr.c1 - (sr.c0 + (long long)t * kBf16Tile);
         return left < kBf16Tile ? (int)left : kBf16Tile;
     };
+    const u16 *kptr[G::LOADS / NW];
+    stream_pointers<D, NW>(kc, sr.c0, cache_stride, kptr);
+    const long long tile_elems = (long long)kBf16Tile * cache_stride;
     auto issue = [&](int t) {
         const int valid = tile_valid(t);
-        const long long base = sr.c0 + (long long)t * kBf16Tile;
-        issue_tile<D, NW, false>(kc, kc, cache_stride, smem + (t & 1) * BUF_BYTES,
-                                 [&](int r) -> long long { return base + (r < valid ? r : valid - 1); });
+        unsigned char *buf = smem + (t % NBUF) * BUF_BYTES;
+        if (valid == kBf16Tile) {
+            issue_tile_stream<D, NW, false>(kptr, tile_elems, 0, t, buf);
+        } else {
+            const long long base = sr.c0 + (long long)t * kBf16Tile;
+            issue_tile<D, NW, false>(kc, kc, cache_stride, buf, [&](int r) -> long long { return base + (r < valid ? r : valid - 1); });
+        }
     };
-    if (ntiles > 0) issue(0);
+#pragma unroll
+    for (int t = 0; t < NBUF - 1; ++t)
+        if (t < ntiles) issue(t);
 
     bf16x8_t qf[KS];
     load_q_frag<D>(a, h, row0 + l32, qf);
@@ -413,10 +473,11 @@ __global__ __launch_bounds__(NW * 64) void colsum_bf16_kernel(const KernelArgs a
     };
 
     for (int t = 0; t < ntiles; ++t) {
-        tile_barrier();
-        if (t + 1 < ntiles) issue(t + 1);
+        if (t + NBUF - 2 < ntiles) tile_barrier<(NBUF - 2) * LPT>();
+        else tile_barrier<0>();
+        if (t + NBUF - 1 < ntiles) issue(t + NBUF - 1);
         if (t > 0) finish(t - 1);
-        const unsigned char *kbuf = smem + (t & 1) * BUF_BYTES;
+        const unsigned char *kbuf = smem + (t % NBUF) * BUF_BYTES;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt) {
             float col = 0.f;

@@ -133,7 +133,7 @@ size_t mage_workspace_bytes(const mage_shape *shape)
     size_t need = partial_bytes(*shape, dense);
     const size_t b = partial_bytes(*shape, sparse);
     if (b > need) need = b;
-    const size_t c = select_layout(*shape, dense).bytes;
+    const size_t c = select_layout(*shape, plan_dense(*shape, kSelectWorkgroups)).bytes;
     if (c > need) need = c;
     return need;
 }
@@ -145,7 +145,7 @@ int mage_select(const mage_shape *shape, const void *q1, const void *k_cache,
     int rc = check_shape(shape, true);
     if (rc != MAGE_OK) return rc;
     if (!q1 || !k_cache || !idx_out) return MAGE_ERR_NULL;
-    const SplitPlan p = plan_dense(*shape);
+    const SplitPlan p = plan_dense(*shape, kSelectWorkgroups);
     if (shape->dtype == MAGE_BF16 && p.row_groups != 1) return MAGE_ERR_UNSUPPORTED;
     if (!aligned16(q1) || !aligned16(k_cache) || !aligned16(workspace) || !aligned16(alpha_out)) return MAGE_ERR_ALIGN;
     const SelectLayout lay = select_layout(*shape, p);

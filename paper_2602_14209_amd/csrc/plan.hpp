@@ -17,6 +17,7 @@ constexpr int kBf16Tile = 64;   // keys per LDS tile, MFMA path
 constexpr int kF32Tile = 32;    // keys per LDS tile, fp32 vector path
 constexpr int kF32Rows = 64;    // query rows per workgroup, fp32 vector path
 constexpr int kTargetWorkgroups = 512;   // 2 per CU on 256 CUs
+constexpr int kSelectWorkgroups = 2048;  // selection passes: 8 per CU
 
 struct SplitPlan {
     int R;            // query rows sharing one KV head: G*B
@@ -49,14 +50,16 @@ inline void plan_rows(const mage_shape &s, SplitPlan &p)
     p.rpad = p.row_groups * p.rows_per_wg;
 }
 
-// Dense pass over all L cache keys (exact attention; both passes of selection).
-inline SplitPlan plan_dense(const mage_shape &s)
+// Dense pass over all L cache keys.  Exact attention pays a [rows x d] partial per split, so it
+// aims at two workgroups per CU; the two passes of selection leave only a (max, sum) pair per
+// row and split, so they cut the keys much finer (more workgroups in flight, even tail).
+inline SplitPlan plan_dense(const mage_shape &s, int target_workgroups = kTargetWorkgroups)
 {
     SplitPlan p{};
     plan_rows(s, p);
     const int64_t tiles = (s.L + p.tile - 1) / p.tile;
-    const int64_t target = kTargetWorkgroups / ((int64_t)s.Hkv * p.row_groups) > 0
-                               ? kTargetWorkgroups / ((int64_t)s.Hkv * p.row_groups) : 1;
+    const int64_t target = target_workgroups / ((int64_t)s.Hkv * p.row_groups) > 0
+                               ? target_workgroups / ((int64_t)s.Hkv * p.row_groups) : 1;
     int64_t tps = (tiles + target - 1) / target;     // tiles per split
     const int64_t min_tps = s.dtype == MAGE_BF16 ? 4 : 8;
     if (tps < min_tps) tps = min_tps;
