@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--layers", type=int, default=28)
     ap.add_argument("--T", type=int, default=0, help="denoising steps per block (0 = the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 256 MiB device-to-device copy (a kernel of known traffic, used to scale "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--seed", type=int, default=2602)
     return ap.parse_args()
 
@@ -122,6 +125,13 @@ def main():
         "phase2": capture(phase2),
     }
 
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     def time_graph(g, reps, warm):
         for _ in range(warm):
             g.replay()
@@ -147,16 +157,19 @@ def main():
     phase1_us = ms["phase1"] * 1e3 / NL
     ab = algorithmic_bytes(w, k)
 
+    traffic = measured_traffic(w, k)
+
     def roof(name, us, nbytes, kernel):
         gbs = nbytes / (us * 1e-6) / 1e9
         return {"kernel": kernel, "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "bytes_per_launch": nbytes,
+                "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": traffic.get(name), "bytes_per_launch": nbytes,
                 "us_per_launch": round(us, 3)}
 
     rooflines = {
-        "mage_sparse_attn": roof("sparse", sparse_us, ab["sparse_attn"], "attn_bf16_kernel<gather> + combine_kernel"),
-        "mage_exact_attn": roof("exact", exact_us, ab["exact_attn"], "attn_bf16_kernel<dense> + combine_kernel"),
-        "mage_select": roof("select", select_us, ab["select"], "attn_bf16_kernel<stats> + colsum_bf16_kernel + topk_kernel"),
+        "mage_sparse_attn": roof("mage_sparse_attn", sparse_us, ab["sparse_attn"], "sparse_bf16_kernel (one launch per call)"),
+        "mage_exact_attn": roof("mage_exact_attn", exact_us, ab["exact_attn"], "attn_bf16_kernel<dense> + combine_kernel"),
+        "mage_select": roof("mage_select", select_us, ab["select"],
+                            "attn_bf16_kernel<stats> + lse_kernel + colsum_bf16_kernel + topk_kernel"),
     }
 
     result = {
@@ -188,6 +201,18 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, k, args.seed)
     print(json.dumps(result), flush=True)
+
+
+def measured_traffic(w, k):
+    """HBM bytes per call measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a copy
+    of known size) and committed under profiles/; None for a workload that was not profiled."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            table = json.load(f)
+    except (OSError, ValueError):
+        return {}
+    return table.get(f"{w.name}-k{k}", {})
 
 
 def cpu_baseline(w, k, seed):
