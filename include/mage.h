@@ -64,7 +64,7 @@ int mage_version(void);
 /* Static, never-freed description of a status code.  Host only. */
 const char *mage_status_string(int status);
 
-/* Bytes of device workspace that any of the three calls below needs for `shape`
+/* Bytes of device workspace that any of the calls below needs for `shape`
  * (the maximum over them).  Host only, pure.  Returns 0 if `shape` is invalid. */
 size_t mage_workspace_bytes(const mage_shape *shape);
 
@@ -109,6 +109,20 @@ int mage_sparse_attn(const mage_shape *shape, const void *q, const void *k_cache
                      const int32_t *idx, const void *k_blk, const void *v_blk,
                      float *out, float *lse_out,
                      void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Step 1 in one call (Alg. 1 Phase 1, both streams' work on one stream): mage_exact_attn of the
+ * All-[MASK] block AND mage_select of the same queries.  The attention pass already walks every
+ * prefix key, so it also leaves the per-row prefix softmax statistics (max, sum-exp over the L
+ * cache keys only) that selection needs; selection then reads K once instead of twice.  Results
+ * are those of the two separate calls (same definitions; the row statistics come from a different
+ * split of the keys, so alpha can differ in the last bits).
+ * In/out: as mage_exact_attn (q1 is the block's step-1 queries) and mage_select.
+ */
+int mage_step1(const mage_shape *shape, const void *q1, const void *k_cache, const void *v_cache,
+               const void *k_blk, const void *v_blk,
+               float *out, float *lse_out, int32_t *idx_out, float *alpha_out,
+               void *workspace, size_t workspace_bytes, void *hip_stream);
 
 #ifdef __cplusplus
 }

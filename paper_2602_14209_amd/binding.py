@@ -22,7 +22,7 @@ MAGE_BF16 = 1
 MAGE_OK = 0
 
 EXPORTS = ("mage_version", "mage_status_string", "mage_workspace_bytes",
-           "mage_select", "mage_exact_attn", "mage_sparse_attn")
+           "mage_select", "mage_exact_attn", "mage_sparse_attn", "mage_step1")
 
 
 class mage_shape(ctypes.Structure):
@@ -61,6 +61,8 @@ def lib() -> ctypes.CDLL:
         L.mage_exact_attn.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.mage_sparse_attn.restype = ctypes.c_int
         L.mage_sparse_attn.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.mage_step1.restype = ctypes.c_int
+        L.mage_step1.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -121,6 +123,14 @@ def mage_sparse_attn(shape: mage_shape, q, k_cache, v_cache, idx, k_blk, v_blk, 
     return lib().mage_sparse_attn(ctypes.byref(shape), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(idx), _ptr(k_blk),
                                   _ptr(v_blk), _ptr(out), _ptr(lse_out), _ptr(workspace), _wsize(workspace),
                                   _stream(stream))
+
+
+def mage_step1(shape: mage_shape, q1, k_cache, v_cache, k_blk, v_blk, out, lse_out, idx_out, alpha_out, workspace,
+               stream=None) -> int:
+    """Step-1 attention and selection in one call (shared statistics pass); see include/mage.h."""
+    return lib().mage_step1(ctypes.byref(shape), _ptr(q1), _ptr(k_cache), _ptr(v_cache), _ptr(k_blk), _ptr(v_blk),
+                            _ptr(out), _ptr(lse_out), _ptr(idx_out), _ptr(alpha_out), _ptr(workspace),
+                            _wsize(workspace), _stream(stream))
 
 
 def check(status: int, where: str = "mage") -> None:

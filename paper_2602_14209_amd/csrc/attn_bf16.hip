@@ -263,6 +263,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 #pragma unroll
         for (int v = 0; v < 16; ++v) o[i][v] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;     // running max (log2 domain) and this lane's share of the normaliser
+    float m_pre = -INFINITY, l_pre = 0.f;     // the same after the last cache tile (prefix-only statistics)
 
     for (int t = 0; t < ntiles; ++t) {
         // tile t landed (NBUF-2 younger tiles may still be in flight); everyone is done with tile t-1
@@ -273,6 +274,10 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
         const int valid = tile_valid(t);
         const unsigned char *kbuf = smem + (t % NBUF) * BUF_BYTES;
         const unsigned char *vbuf = kbuf + G::MAT_BYTES;
+        if (WITH_V && t == sr.cache_tiles) {   // first in-block tile: freeze the prefix statistics
+            m_pre = m_run;
+            l_pre = l_run;
+        }
 
 #ifdef MAGE_PROBE_NO_COMPUTE
         if (false) {
@@ -343,6 +348,18 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     MAGE_PROBE_AT(2);
+    if (WITH_V && a.stat_m != nullptr) {
+        if (sr.blk_tiles == 0) {
+            m_pre = m_run;
+            l_pre = l_run;
+        }
+        const float lp = l_pre + __shfl_xor(l_pre, 32);
+        if (wave_active && row < a.R && lg == 0) {
+            const long long pi = ((long long)h * a.n_split + split) * a.rpad + row;
+            a.stat_m[pi] = m_pre;
+            a.stat_l[pi] = lp;
+        }
+    }
 
     if (MODE == MODE_STATS) {
         if (wave_active && row < a.R && lg == 0) {

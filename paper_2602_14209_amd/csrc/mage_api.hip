@@ -72,7 +72,8 @@ void carve_partials(const mage_shape &s, const SplitPlan &p, void *workspace, Ke
 int run_attention(const mage_shape *shape, const SplitPlan &p, bool gather,
                   const void *q, const void *k_cache, const void *v_cache, const int32_t *idx,
                   const void *k_blk, const void *v_blk, float *out, float *lse_out,
-                  void *workspace, size_t workspace_bytes, void *hip_stream)
+                  void *workspace, size_t workspace_bytes, void *hip_stream,
+                  float *stat_m = nullptr, float *stat_l = nullptr)
 {
     if (!q || !k_cache || !v_cache || !out || (gather && !idx)) return MAGE_ERR_NULL;
     if ((k_blk == nullptr) != (v_blk == nullptr)) return MAGE_ERR_NULL;
@@ -93,6 +94,8 @@ int run_attention(const mage_shape *shape, const SplitPlan &p, bool gather,
     a.nc = gather ? (long long)shape->k : (long long)shape->L;
     a.out = out;
     a.lse_out = lse_out;
+    a.stat_m = stat_m;
+    a.stat_l = stat_l;
     if (p.n_split > 1) carve_partials(*shape, p, workspace, a);
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -135,6 +138,8 @@ size_t mage_workspace_bytes(const mage_shape *shape)
     if (b > need) need = b;
     const size_t c = select_layout(*shape, plan_dense(*shape, kSelectWorkgroups)).bytes;
     if (c > need) need = c;
+    const size_t e = step1_layout(*shape, dense).bytes;
+    if (e > need) need = e;
     return need;
 }
 
@@ -177,6 +182,54 @@ int mage_select(const mage_shape *shape, const void *q1, const void *k_cache,
     if (e != hipSuccess) return MAGE_ERR_HIP;
     e = launch_topk(a.alpha, shape->Hkv, shape->L, shape->k, idx_out, stream);
     if (e != hipSuccess) return MAGE_ERR_HIP;
+    return MAGE_OK;
+}
+
+int mage_step1(const mage_shape *shape, const void *q1, const void *k_cache, const void *v_cache,
+               const void *k_blk, const void *v_blk, float *out, float *lse_out, int32_t *idx_out, float *alpha_out,
+               void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    int rc = check_shape(shape, true);
+    if (rc != MAGE_OK) return rc;
+    if (!idx_out) return MAGE_ERR_NULL;
+    if (shape->dtype != MAGE_BF16) {
+        // fp32: the two calls back to back (no shared pass in the vector path)
+        rc = run_attention(shape, plan_dense(*shape), false, q1, k_cache, v_cache, nullptr, k_blk, v_blk, out, lse_out,
+                           workspace, workspace_bytes, hip_stream);
+        if (rc != MAGE_OK) return rc;
+        return mage_select(shape, q1, k_cache, idx_out, alpha_out, workspace, workspace_bytes, hip_stream);
+    }
+    const SplitPlan pa = plan_dense(*shape);
+    const SplitPlan ps = plan_dense(*shape, kSelectWorkgroups);
+    if (ps.row_groups != 1) return MAGE_ERR_UNSUPPORTED;
+    if (!aligned16(alpha_out)) return MAGE_ERR_ALIGN;
+    const Step1Layout lay = step1_layout(*shape, pa);
+    if (!workspace || workspace_bytes < lay.bytes) return MAGE_ERR_WORKSPACE;
+    char *w = static_cast<char *>(workspace);
+    float *stat_m = reinterpret_cast<float *>(w + lay.stat_m), *stat_l = reinterpret_cast<float *>(w + lay.stat_l);
+    rc = run_attention(shape, pa, false, q1, k_cache, v_cache, nullptr, k_blk, v_blk, out, lse_out,
+                       w + lay.partials, lay.stat_m - lay.partials, hip_stream, stat_m, stat_l);
+    if (rc != MAGE_OK) return rc;
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    float *lse2 = reinterpret_cast<float *>(w + lay.lse2);
+    KernelArgs r = base_args(*shape, pa);            // merge the attention splits' prefix statistics
+    r.part_m = stat_m;
+    r.part_l = stat_l;
+    if (launch_lse(r, lse2, stream) != hipSuccess) return MAGE_ERR_HIP;
+    KernelArgs a = base_args(*shape, ps);            // column sums on selection's own, finer split
+    a.q = q1;
+    a.kc = k_cache;
+    a.vc = k_cache;
+    a.kblk = k_cache;
+    a.vblk = k_cache;
+    a.n_blk = 0;
+    a.blk_split = -1;
+    a.nc = shape->L;
+    a.lse2 = lse2;
+    a.alpha = alpha_out ? alpha_out : reinterpret_cast<float *>(w + lay.alpha);
+    if (bf16_colsum(a, shape->d, ps.waves, stream) != hipSuccess) return MAGE_ERR_HIP;
+    if (launch_topk(a.alpha, shape->Hkv, shape->L, shape->k, idx_out, stream) != hipSuccess) return MAGE_ERR_HIP;
     return MAGE_OK;
 }
 

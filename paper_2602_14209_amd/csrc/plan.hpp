@@ -113,12 +113,33 @@ inline SelectLayout select_layout(const mage_shape &s, const SplitPlan &p)
     return l;
 }
 
+// Fused step 1 (exact attention that also feeds selection): the attention partials, then the
+// prefix statistics per attention split, then selection's lse2 and alpha.
+struct Step1Layout {
+    size_t partials, stat_m, stat_l, lse2, alpha, bytes;
+};
+
+inline Step1Layout step1_layout(const mage_shape &s, const SplitPlan &attn)
+{
+    Step1Layout l{};
+    const size_t rows = (size_t)s.Hkv * attn.n_split * attn.rpad;
+    size_t off = 0;
+    l.partials = off; off += partial_bytes(s, attn);
+    l.stat_m = off;   off += align_up(rows * sizeof(float), 256);
+    l.stat_l = off;   off += align_up(rows * sizeof(float), 256);
+    l.lse2 = off;     off += align_up((size_t)s.Hkv * attn.rpad * sizeof(float), 256);
+    l.alpha = off;    off += align_up((size_t)s.Hkv * (size_t)s.L * sizeof(float), 256);
+    l.bytes = off;
+    return l;
+}
+
 // Arguments shared by the attention / statistics / column-sum kernels of both element types.
 struct KernelArgs {
     const void *q, *kc, *vc, *kblk, *vblk;
     const int32_t *idx;      // gather indices [Hkv][nc] or nullptr
     float *out, *lse_out;    // final outputs (used directly when n_split == 1)
     float *part_o, *part_m, *part_l;
+    float *stat_m, *stat_l;  // exact attention, optional: prefix-only (cache keys) statistics per split, as part_m/part_l
     const float *lse2;       // column-sum pass: per-row log2-domain log-sum-exp [Hkv][rpad]
     float *alpha;            // column-sum pass: [Hkv][L]
     int B, Hq, Hkv, G, R, rpad;

@@ -51,6 +51,12 @@ class Problem:
         torch.cuda.synchronize()
         return self.idx.cpu().numpy(), (self.alpha.cpu().numpy() if with_alpha else None)
 
+    def step1(self):
+        mb.check(mb.mage_step1(self.shape, self.q, self.kc, self.vc, self.kb, self.vb, self.out, self.lse, self.idx,
+                               self.alpha, self.ws), "mage_step1")
+        torch.cuda.synchronize()
+        return self.out.cpu().numpy(), self.lse.cpu().numpy(), self.idx.cpu().numpy(), self.alpha.cpu().numpy()
+
     def exact(self):
         mb.check(mb.mage_exact_attn(self.shape, self.q, self.kc, self.vc, self.kb, self.vb, self.out, self.lse, self.ws),
                  "mage_exact_attn")

@@ -30,6 +30,12 @@ def _run_workload(oracle_mod, w: Workload, seed: int, ks=None, steps=None, blk=T
                                              x["k_blk"][0] if blk else None, x["v_blk"][0] if blk else None)
         o, l = p.exact()
         check_out(o, o_ref, l, l_ref, w.dtype)
+        if w.G * w.B <= 256 or w.dtype == "f32":
+            p.out.fill_(float("nan")); p.idx.fill_(-1); p.alpha.fill_(float("nan"))
+            o, l, idx3, alpha3 = p.step1()                # fused step 1: same definitions, shared pass
+            check_out(o, o_ref, l, l_ref, w.dtype)
+            check_alpha(alpha3, ref["alpha32"])
+            check_index_sets(idx3, ref["idx"], ref["alpha32"], w.L)
         for t in range(1, T):
             p.set_q(x["q"][t])
             if blk:
@@ -162,6 +168,10 @@ def test_c4_full_size_headline_shape(oracle_mod):
     rows = [0, 13, 31]
     o_ref, l_ref = oracle_mod.exact_attn(x["q"][0][rows], x["k_cache"], x["v_cache"], x["k_blk"][0], x["v_blk"][0])
     check_out(o[rows], o_ref, l[rows], l_ref, w.dtype)
+    o, l, idx3, alpha3 = p.step1()
+    check_out(o[rows], o_ref, l[rows], l_ref, w.dtype)
+    check_alpha(alpha3, ref["alpha32"])
+    check_index_sets(idx3, ref["idx"], ref["alpha32"], w.L)
     for kk in w.ks:
         if kk == k:
             pk, ref_k = p, ref["idx"]

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared_symbols():
     text = open(os.path.join(ROOT, "include", "mage.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(mage_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(mage_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -57,6 +57,7 @@ def test_argument_validation_happens_before_any_launch(kw, code):
     L = mb.lib()
     assert L.mage_select(ctypes.byref(s), fake, fake, fake, None, fake, 1 << 40, None) == code
     assert L.mage_sparse_attn(ctypes.byref(s), fake, fake, fake, fake, fake, fake, fake, None, fake, 1 << 40, None) == code
+    assert L.mage_step1(ctypes.byref(s), fake, fake, fake, fake, fake, fake, None, fake, None, fake, 1 << 40, None) == code
     if "k" not in kw:
         assert L.mage_exact_attn(ctypes.byref(s), fake, fake, fake, fake, fake, fake, None, fake, 1 << 40, None) == code
 
@@ -77,6 +78,8 @@ def test_null_alignment_and_workspace_errors():
     assert L.mage_exact_attn(ctypes.byref(s), fake, fake, odd, fake, fake, fake, None, fake, big, None) == -6
     assert L.mage_exact_attn(ctypes.byref(s), fake, fake, fake, fake, fake, fake, None, fake, 16, None) == -4
     assert L.mage_sparse_attn(ctypes.byref(s), fake, fake, fake, None, fake, fake, fake, None, fake, big, None) == -1
+    assert L.mage_step1(ctypes.byref(s), fake, fake, fake, fake, fake, fake, None, None, None, fake, big, None) == -1
+    assert L.mage_step1(ctypes.byref(s), fake, fake, fake, fake, fake, fake, None, fake, None, fake, 16, None) == -4
     # the bf16 sparse step keeps its partials on chip and needs no workspace; the fp32 one does
     sf = mb.make_shape(32, 32, 8, 128, 4096, 512, "f32")
     assert L.mage_sparse_attn(ctypes.byref(sf), fake, fake, fake, fake, fake, fake, fake, None, fake, 16, None) == -4
