@@ -203,7 +203,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     // tile buffers; after the key loop the same memory stages the output transposition
     __shared__ __attribute__((aligned(1024))) unsigned char smem[NBUF * BUF_BYTES];
 
-    const int h = blockIdx.x, split = blockIdx.y, rg = blockIdx.z;
+    // key splits vary fastest over the grid: consecutive workgroups (dealt round-robin to the XCDs)
+    // stream different key ranges of the same head, so every XCD touches every HBM channel
+    const int split = blockIdx.x, h = blockIdx.y, rg = blockIdx.z;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, lg = lane >> 5;
     const int row0 = (rg * NW + wave) * 32;           // first row of this wavefront's M tile
@@ -434,7 +436,7 @@ __global__ __launch_bounds__(NW * 64) void colsum_bf16_kernel(const KernelArgs a
     __shared__ __attribute__((aligned(1024))) unsigned char smem[NBUF * BUF_BYTES];
     __shared__ float red[2][NW][kBf16Tile];
 
-    const int h = blockIdx.x, split = blockIdx.y;
+    const int split = blockIdx.x, h = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, lg = lane >> 5;
     const int row0 = wave * 32;
@@ -524,7 +526,7 @@ __global__ __launch_bounds__(NW * 64) void colsum_bf16_kernel(const KernelArgs a
 template <int D, int NW, int MODE, bool GATHER>
 static hipError_t launch_attn(const KernelArgs &a, int row_groups, hipStream_t stream)
 {
-    dim3 grid(a.Hkv, a.n_split, row_groups), block(NW * 64);
+    dim3 grid(a.n_split, a.Hkv, row_groups), block(NW * 64);
     hipLaunchKernelGGL((attn_bf16_kernel<D, NW, MODE, GATHER>), grid, block, 0, stream, a);
     return hipGetLastError();
 }
@@ -532,7 +534,7 @@ static hipError_t launch_attn(const KernelArgs &a, int row_groups, hipStream_t s
 template <int D, int NW>
 static hipError_t launch_colsum(const KernelArgs &a, hipStream_t stream)
 {
-    dim3 grid(a.Hkv, a.n_split), block(NW * 64);
+    dim3 grid(a.n_split, a.Hkv), block(NW * 64);
     hipLaunchKernelGGL((colsum_bf16_kernel<D, NW>), grid, block, 0, stream, a);
     return hipGetLastError();
 }

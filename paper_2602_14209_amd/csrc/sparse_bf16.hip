@@ -63,6 +63,7 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
     const int row = rt * 16 + l16;
 
     MAGE_PROBE_AT(0);
+    MAGE_PROBE_LAST_AT(0);
     const int n_keys = (int)a.nc + a.n_blk;
     const int ntiles = (n_keys + SP_KT - 1) / SP_KT;
     const int npass = (ntiles + SP_MAXT - 1) / SP_MAXT;
@@ -204,10 +205,12 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
     }
 
     MAGE_PROBE_AT(4);
+    MAGE_PROBE_LAST_AT(4);
     // ---- merge the eight wavefronts through LDS ----
     float l_w = l_run + __shfl_xor(l_run, 16);
     l_w += __shfl_xor(l_w, 32);
     __syncthreads();                                         // every wavefront is done reading V
+    MAGE_PROBE_AT(6);
     if (lg4 == 0) {
         ml[0][wave][l16] = m_run;
         ml[1][wave][l16] = l_w;
@@ -216,6 +219,7 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) part[(wave * DT + dt) * 64 + lane] = o[dt];
     __syncthreads();
+    MAGE_PROBE_AT(7);
 
     float M = ml[0][0][l16];
 #pragma unroll
