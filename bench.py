@@ -66,11 +66,29 @@ def main():
     torch.cuda.set_device(dev)
     shape = mb.make_shape(w.B, w.Hq, w.Hkv, w.d, w.L, k, w.dtype)
 
-    layers = [make_layer_device(w, args.seed + 1000 * 4 + l, dev, steps=T) for l in range(NL)]
+    # All layers live in one allocation per array ([layer, ...]); a layer is a view.  The same memory
+    # doubles as a batch of NL independent sequences for the batched (bandwidth-mode) launch.
+    dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    big_k = torch.empty((NL, w.L, w.Hkv, w.d), dtype=dt, device=dev)
+    big_v = torch.empty_like(big_k)
+    big_q = torch.empty((T, NL, w.B, w.Hq, w.d), dtype=dt, device=dev)
+    big_kb = torch.empty((T, NL, w.B, w.Hkv, w.d), dtype=dt, device=dev)
+    big_vb = torch.empty_like(big_kb)
+    for l in range(NL):
+        x = make_layer_device(w, args.seed + 1000 * 4 + l, dev, steps=T)
+        big_k[l].copy_(x["k_cache"]); big_v[l].copy_(x["v_cache"])
+        big_q[:, l].copy_(x["q"]); big_kb[:, l].copy_(x["k_blk"]); big_vb[:, l].copy_(x["v_blk"])
+        del x
+    layers = [{"q": big_q[:, l], "k_cache": big_k[l], "v_cache": big_v[l], "k_blk": big_kb[:, l], "v_blk": big_vb[:, l]}
+              for l in range(NL)]
     ws_main = mb.alloc_workspace(shape)
     ws_side = mb.alloc_workspace(shape)
-    idx = [torch.zeros((w.Hkv, k), dtype=torch.int32, device=dev) for _ in range(NL)]
+    big_idx = torch.zeros((NL, w.Hkv, k), dtype=torch.int32, device=dev)
+    idx = [big_idx[l] for l in range(NL)]
     out = torch.empty((w.B, w.Hq, w.d), dtype=torch.float32, device=dev)
+    out_b = torch.empty((NL, w.B, w.Hq, w.d), dtype=torch.float32, device=dev)
+    k_sel = torch.empty((NL, k, w.Hkv, w.d), dtype=dt, device=dev)
+    v_sel = torch.empty_like(k_sel)
     torch.cuda.synchronize()
 
     main_s = torch.cuda.Stream(device=dev)
@@ -94,6 +112,19 @@ def main():
         x = layers[l]
         mb.check(mb.mage_sparse_attn(shape, x["q"][t], x["k_cache"], x["v_cache"], idx[l], x["k_blk"][t],
                                      x["v_blk"][t], out, None, ws_main, stream), "mage_sparse_attn")
+
+    def compact(l, stream):
+        x = layers[l]
+        mb.check(mb.mage_compact(shape, x["k_cache"], x["v_cache"], idx[l], k_sel[l], v_sel[l], stream), "mage_compact")
+
+    def sparse_compact(l, t, stream):
+        x = layers[l]
+        mb.check(mb.mage_sparse_attn_compact(shape, x["q"][t], k_sel[l], v_sel[l], x["k_blk"][t], x["v_blk"][t], out,
+                                             None, ws_main, stream), "mage_sparse_attn_compact")
+
+    def sparse_batched(t, stream):
+        mb.check(mb.mage_sparse_attn_batched(shape, NL, big_q[t], big_k, big_v, big_idx, big_kb[t], big_vb[t], out_b,
+                                             None, stream), "mage_sparse_attn_batched")
 
     def phase1(overlap=True):
         if overlap:
@@ -130,6 +161,9 @@ def main():
         "exact_only": capture(lambda: [exact(l, main_s) for l in range(NL)]),
         "select_only": capture(lambda: [select(l, main_s, ws_main) for l in range(NL)]),
         "phase2": capture(phase2),
+        "compact": capture(lambda: [compact(l, main_s) for l in range(NL)]),
+        "phase2_compact": capture(lambda: [sparse_compact(l, t, main_s) for t in range(1, T) for l in range(NL)]),
+        "phase2_batched": capture(lambda: [sparse_batched(t, main_s) for t in range(1, T)]),
     }
 
     if args.calibrate_copy:
@@ -164,6 +198,9 @@ def main():
     phase1_us = ms["phase1"] * 1e3 / NL
     step1_us = ms["step1_fused"] * 1e3 / NL
     ab = algorithmic_bytes(w, k)
+    compact_us = ms["compact"] * 1e3 / NL
+    sparse_compact_us = ms["phase2_compact"] * 1e3 / n_sparse
+    batched_launch_us = ms["phase2_batched"] * 1e3 / (T - 1)          # one launch = NL sequences
 
     traffic = measured_traffic(w, k)
 
@@ -203,6 +240,13 @@ def main():
         "step1_fused_us_per_layer": round(step1_us, 2),
         "two_stream_phase1_us_per_layer": round(phase1_us, 2),
         "block_ms": {"mage": round(ms_step, 4), "exact_baseline_est": round(exact_us * NL * T / 1e3, 4)},
+        "sparse_step_compact_us": round(sparse_compact_us, 3),
+        "compact_us_per_layer": round(compact_us, 2),
+        "sparse_step_batched": {"sequences_per_launch": NL, "us_per_launch": round(batched_launch_us, 2),
+                                "us_per_sequence": round(batched_launch_us / NL, 3),
+                                "hbm_gbs": round(NL * ab["sparse_attn"] / (batched_launch_us * 1e-6) / 1e9, 1),
+                                "frac_of_8TBs": round(NL * ab["sparse_attn"] / (batched_launch_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                                "note": "bandwidth mode: independent sequences in one launch, not a per-step latency"},
         "wall_ms_per_step": round(wall_step, 4),
         "roofline": rooflines["mage_sparse_attn"],
         "rooflines": rooflines,

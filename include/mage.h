@@ -124,6 +124,37 @@ int mage_step1(const mage_shape *shape, const void *q1, const void *k_cache, con
                float *out, float *lse_out, int32_t *idx_out, float *alpha_out,
                void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Compacted selection.  The index set is fixed for steps 2..T (Sec. 4 Phase 2), so the selected
+ * rows can be copied once per block into a cache of length k,
+ *   k_sel[p,h,:] = k_cache[idx[h,p],h,:],  v_sel likewise,   p in [0,k),
+ * and every later step attends it without an index indirection.
+ * In:  k_cache, v_cache [L,Hkv,d]; idx [Hkv,k] (entries in [0,L)).
+ * Out: k_sel, v_sel [k,Hkv,d], same element type.  No workspace.
+ */
+int mage_compact(const mage_shape *shape, const void *k_cache, const void *v_cache, const int32_t *idx,
+                 void *k_sel, void *v_sel, void *hip_stream);
+
+/*
+ * mage_sparse_attn on rows compacted by mage_compact: softmax over the k rows of k_sel / v_sel
+ * [k,Hkv,d] plus the B in-block keys.  Same result as mage_sparse_attn with the index set the
+ * rows were compacted with (up to the order of fp32 additions).  shape->L is not used.
+ */
+int mage_sparse_attn_compact(const mage_shape *shape, const void *q, const void *k_sel, const void *v_sel,
+                             const void *k_blk, const void *v_blk, float *out, float *lse_out,
+                             void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * mage_sparse_attn for n_seq independent sequences in one launch (decoding a batch of blocks):
+ * every array gains a leading sequence axis -- q, out [n_seq,B,Hq,d]; k_cache, v_cache
+ * [n_seq,L,Hkv,d]; idx [n_seq,Hkv,k]; k_blk, v_blk [n_seq,B,Hkv,d]; lse_out [n_seq,B,Hq].
+ * The launch then carries enough independent work to be bound by HBM bandwidth rather than by
+ * the latency of one small gather.  MAGE_BF16 only (MAGE_ERR_UNSUPPORTED otherwise).
+ */
+int mage_sparse_attn_batched(const mage_shape *shape, int n_seq, const void *q, const void *k_cache,
+                             const void *v_cache, const int32_t *idx, const void *k_blk, const void *v_blk,
+                             float *out, float *lse_out, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

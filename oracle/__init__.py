@@ -11,4 +11,5 @@ from .mage_oracle import (  # noqa: F401
     select,
     exact_attn,
     sparse_attn,
+    compact,
 )

@@ -279,3 +279,22 @@ int mage_oracle_attn(int B, int Hq, int Hkv, int d, int64_t L,
     }
     return fail ? -1 : 0;
 }
+
+/*
+ * Compacted selection (Sec. 4 Phase 2: the index set is fixed for steps 2..T, so the selected
+ * rows may be copied once): dst[p,h,:] = src[idx[h,p],h,:] for p in [0,k).  src [L,Hkv,d],
+ * idx [Hkv,k], dst [k,Hkv,d].  A copy: bit-exact by construction.
+ */
+int mage_oracle_compact(int Hkv, int d, int64_t L, int k, const float *src, const int32_t *idx, float *dst)
+{
+    if (Hkv <= 0 || d <= 0 || L <= 0 || k <= 0 || !src || !idx || !dst)
+        return -1;
+    for (int h = 0; h < Hkv; ++h)
+        for (int p = 0; p < k; ++p) {
+            const int32_t j = idx[(size_t)h * k + p];
+            if (j < 0 || (int64_t)j >= L)
+                return -1;
+            memcpy(dst + ((size_t)p * Hkv + h) * d, src + ((size_t)j * Hkv + h) * d, sizeof(float) * (size_t)d);
+        }
+    return 0;
+}

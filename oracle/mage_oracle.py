@@ -51,6 +51,8 @@ def _load():
         lib.mage_oracle_attn.argtypes = [
             ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int64,
             _f32p, _f32p, _f32p, _i32p, ctypes.c_int, _f32p, _f32p, ctypes.c_int, _f32p, _f32p]
+        lib.mage_oracle_compact.restype = ctypes.c_int
+        lib.mage_oracle_compact.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int, _f32p, _i32p, _f32p]
         _lib = lib
     return _lib
 
@@ -154,3 +156,18 @@ def exact_attn(q, k_cache, v_cache, k_blk=None, v_blk=None):
 def sparse_attn(q, k_cache, v_cache, idx, k_blk=None, v_blk=None):
     """Sparse attention over cache[idx[kv(g)]] plus the in-block keys -> (out, lse)."""
     return _attn(q, k_cache, v_cache, idx, k_blk, v_blk)
+
+
+def compact(cache, idx):
+    """Rows selected by idx[Hkv,k] copied into a cache of length k: out[p,h,:] = cache[idx[h,p],h,:]."""
+    cache = _f32(cache)
+    L, Hkv, d = cache.shape
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    if idx.ndim != 2 or idx.shape[0] != Hkv:
+        raise ValueError("idx must be [Hkv,k]")
+    k = idx.shape[1]
+    out = np.empty((k, Hkv, d), np.float32)
+    rc = _load().mage_oracle_compact(Hkv, d, L, k, _ptr(cache, _f32p), _ptr(idx, _i32p), _ptr(out, _f32p))
+    if rc:
+        raise RuntimeError("mage_oracle_compact failed")
+    return out

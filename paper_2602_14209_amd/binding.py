@@ -22,7 +22,8 @@ MAGE_BF16 = 1
 MAGE_OK = 0
 
 EXPORTS = ("mage_version", "mage_status_string", "mage_workspace_bytes",
-           "mage_select", "mage_exact_attn", "mage_sparse_attn", "mage_step1")
+           "mage_select", "mage_exact_attn", "mage_sparse_attn", "mage_step1",
+           "mage_compact", "mage_sparse_attn_compact", "mage_sparse_attn_batched")
 
 
 class mage_shape(ctypes.Structure):
@@ -61,6 +62,12 @@ def lib() -> ctypes.CDLL:
         L.mage_exact_attn.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.mage_sparse_attn.restype = ctypes.c_int
         L.mage_sparse_attn.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.mage_compact.restype = ctypes.c_int
+        L.mage_compact.argtypes = [shp, vp, vp, vp, vp, vp, vp]
+        L.mage_sparse_attn_compact.restype = ctypes.c_int
+        L.mage_sparse_attn_compact.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.mage_sparse_attn_batched.restype = ctypes.c_int
+        L.mage_sparse_attn_batched.argtypes = [shp, ctypes.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.mage_step1.restype = ctypes.c_int
         L.mage_step1.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         _lib = L
@@ -131,6 +138,28 @@ def mage_step1(shape: mage_shape, q1, k_cache, v_cache, k_blk, v_blk, out, lse_o
     return lib().mage_step1(ctypes.byref(shape), _ptr(q1), _ptr(k_cache), _ptr(v_cache), _ptr(k_blk), _ptr(v_blk),
                             _ptr(out), _ptr(lse_out), _ptr(idx_out), _ptr(alpha_out), _ptr(workspace),
                             _wsize(workspace), _stream(stream))
+
+
+def mage_compact(shape: mage_shape, k_cache, v_cache, idx, k_sel, v_sel, stream=None) -> int:
+    """Copy the selected rows into a cache of length k; see include/mage.h."""
+    return lib().mage_compact(ctypes.byref(shape), _ptr(k_cache), _ptr(v_cache), _ptr(idx), _ptr(k_sel), _ptr(v_sel),
+                              _stream(stream))
+
+
+def mage_sparse_attn_compact(shape: mage_shape, q, k_sel, v_sel, k_blk, v_blk, out, lse_out, workspace,
+                             stream=None) -> int:
+    """Sparse step on compacted rows; see include/mage.h."""
+    return lib().mage_sparse_attn_compact(ctypes.byref(shape), _ptr(q), _ptr(k_sel), _ptr(v_sel), _ptr(k_blk),
+                                          _ptr(v_blk), _ptr(out), _ptr(lse_out), _ptr(workspace), _wsize(workspace),
+                                          _stream(stream))
+
+
+def mage_sparse_attn_batched(shape: mage_shape, n_seq: int, q, k_cache, v_cache, idx, k_blk, v_blk, out, lse_out,
+                             stream=None) -> int:
+    """Sparse step of n_seq independent sequences in one launch; see include/mage.h."""
+    return lib().mage_sparse_attn_batched(ctypes.byref(shape), int(n_seq), _ptr(q), _ptr(k_cache), _ptr(v_cache),
+                                          _ptr(idx), _ptr(k_blk), _ptr(v_blk), _ptr(out), _ptr(lse_out),
+                                          _stream(stream))
 
 
 def check(status: int, where: str = "mage") -> None:

@@ -154,12 +154,12 @@ __device__ __forceinline__ bf16x8_t read_vt_frag(const unsigned char *vbuf, int 
 // Query fragment of this lane: row (l % 32) of the wavefront's M tile, 8 consecutive channels
 // per MFMA k-step.  Row r of a KV head's row space is (g_local = r / B, q = r % B).
 template <int D>
-__device__ __forceinline__ void load_q_frag(const KernelArgs &a, int h, int row, bf16x8_t (&qf)[D / 16])
+__device__ __forceinline__ void load_q_frag(const KernelArgs &a, const u16 *q, int h, int row, bf16x8_t (&qf)[D / 16])
 {
     const int lg = (threadIdx.x & 63) >> 5;
     if (row < a.R) {
         const int gl = row / a.B, qi = row - gl * a.B;
-        const u16 *src = static_cast<const u16 *>(a.q) + ((long long)qi * a.Hq + (long long)h * a.G + gl) * D + 8 * lg;
+        const u16 *src = q + ((long long)qi * a.Hq + (long long)h * a.G + gl) * D + 8 * lg;
 #pragma unroll
         for (int ks = 0; ks < D / 16; ++ks) qf[ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(src + ks * 16));
     } else {
@@ -205,23 +205,27 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 
     // key splits vary fastest over the grid: consecutive workgroups (dealt round-robin to the XCDs)
     // stream different key ranges of the same head, so every XCD touches every HBM channel
-    const int split = blockIdx.x, h = blockIdx.y, rg = blockIdx.z;
+    // A batched launch (independent sequences, unsplit keys) uses the x axis for the sequence.
+    const bool batched = a.seq_kv != 0;
+    const long long z = batched ? blockIdx.x : 0;
+    const int split = batched ? 0 : blockIdx.x, h = blockIdx.y, rg = blockIdx.z;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, lg = lane >> 5;
     const int row0 = (rg * NW + wave) * 32;           // first row of this wavefront's M tile
     const int row = row0 + l32;
     const bool wave_active = row0 < a.R;
 
+    MAGE_PROBE_DECL;
     MAGE_PROBE_AT(0);
     const SplitRange sr = split_range(a, split);
     const int ntiles = sr.cache_tiles + sr.blk_tiles;
 
     const long long cache_stride = (long long)a.Hkv * D;
-    const u16 *kc = static_cast<const u16 *>(a.kc) + (long long)h * D;
-    const u16 *vc = static_cast<const u16 *>(a.vc) + (long long)h * D;
-    const u16 *kb = static_cast<const u16 *>(a.kblk) + (long long)h * D;
-    const u16 *vb = static_cast<const u16 *>(a.vblk) + (long long)h * D;
-    const int32_t *idx = GATHER ? a.idx + (long long)h * a.nc : nullptr;
+    const u16 *kc = static_cast<const u16 *>(a.kc) + z * a.seq_kv + (long long)h * D;
+    const u16 *vc = static_cast<const u16 *>(a.vc) + z * a.seq_kv + (long long)h * D;
+    const u16 *kb = static_cast<const u16 *>(a.kblk) + z * a.seq_blk + (long long)h * D;
+    const u16 *vb = static_cast<const u16 *>(a.vblk) + z * a.seq_blk + (long long)h * D;
+    const int32_t *idx = GATHER ? a.idx + z * a.seq_idx + (long long)h * a.nc : nullptr;
 
     auto tile_valid = [&](int t) -> int {
         if (t < sr.cache_tiles) {
@@ -257,7 +261,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
         if (t < ntiles) issue(t);      // first: the longest dependent chain (index -> row)
 
     bf16x8_t qf[KS];
-    load_q_frag<D>(a, h, row, qf);
+    load_q_frag<D>(a, static_cast<const u16 *>(a.q) + z * a.seq_q, h, row, qf);
 
     f32x16_t o[WITH_V ? DT : 1];
 #pragma unroll
@@ -399,7 +403,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
                     float *dst;
                     if (direct) {
                         const int gl = orow / a.B, qi = orow - gl * a.B;
-                        dst = a.out + ((long long)qi * a.Hq + (long long)h * a.G + gl) * D;
+                        dst = a.out + z * a.seq_out + ((long long)qi * a.Hq + (long long)h * a.G + gl) * D;
                     } else {
                         dst = a.part_o + (((long long)h * a.n_split + split) * a.rpad + orow) * D;
                     }
@@ -410,11 +414,12 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
         __syncthreads();
     }
     MAGE_PROBE_AT(3);
+    MAGE_PROBE_FLUSH();
     if (!wave_active || row >= a.R || lg != 0) return;
     if (direct) {
         if (a.lse_out) {
             const int gl = row / a.B, qi = row - gl * a.B;
-            a.lse_out[(long long)qi * a.Hq + (long long)h * a.G + gl] = (m_run + log2f(l_tot)) * 0.6931471805599453f;
+            a.lse_out[z * a.seq_lse + (long long)qi * a.Hq + (long long)h * a.G + gl] = (m_run + log2f(l_tot)) * 0.6931471805599453f;
         }
     } else {
         const long long pi = ((long long)h * a.n_split + split) * a.rpad + row;
@@ -469,7 +474,7 @@ __global__ __launch_bounds__(NW * 64) void colsum_bf16_kernel(const KernelArgs a
         if (t < ntiles) issue(t);
 
     bf16x8_t qf[KS];
-    load_q_frag<D>(a, h, row0 + l32, qf);
+    load_q_frag<D>(a, static_cast<const u16 *>(a.q), h, row0 + l32, qf);
 
     // per-register row statistics: register v is query row row0 + 8*(v/4) + 4*lg + v%4
     float lse2[16];
@@ -546,6 +551,20 @@ hipError_t bf16_attn(const KernelArgs &a, int d, int waves, int row_groups, bool
     if (d == 64 && waves == 4) return gather ? launch_attn<64, 4, MODE_ATTN, true>(a, row_groups, stream) : launch_attn<64, 4, MODE_ATTN, false>(a, row_groups, stream);
     if (d == 64 && waves == 8) return gather ? launch_attn<64, 8, MODE_ATTN, true>(a, row_groups, stream) : launch_attn<64, 8, MODE_ATTN, false>(a, row_groups, stream);
     return hipErrorInvalidValue;
+}
+
+// Batched sparse step: n_seq independent sequences, one workgroup per (sequence, KV head, row
+// group) walks all k + B keys of its head, so every selected row is fetched by exactly one
+// workgroup and nothing is merged across workgroups.
+hipError_t bf16_attn_batched(const KernelArgs &a, int d, int waves, int row_groups, int n_seq, hipStream_t stream)
+{
+    dim3 grid(n_seq, a.Hkv, row_groups), block(waves * 64);
+    if (d == 128 && waves == 4) hipLaunchKernelGGL((attn_bf16_kernel<128, 4, MODE_ATTN, true>), grid, block, 0, stream, a);
+    else if (d == 128 && waves == 8) hipLaunchKernelGGL((attn_bf16_kernel<128, 8, MODE_ATTN, true>), grid, block, 0, stream, a);
+    else if (d == 64 && waves == 4) hipLaunchKernelGGL((attn_bf16_kernel<64, 4, MODE_ATTN, true>), grid, block, 0, stream, a);
+    else if (d == 64 && waves == 8) hipLaunchKernelGGL((attn_bf16_kernel<64, 8, MODE_ATTN, true>), grid, block, 0, stream, a);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
 }
 
 hipError_t bf16_stats(const KernelArgs &a, int d, int waves, int row_groups, hipStream_t stream)

@@ -8,9 +8,12 @@
 
 namespace mage {
 hipError_t bf16_attn(const KernelArgs &a, int d, int waves, int row_groups, bool gather, hipStream_t stream);
+hipError_t bf16_attn_batched(const KernelArgs &a, int d, int waves, int row_groups, int n_seq, hipStream_t stream);
 hipError_t bf16_stats(const KernelArgs &a, int d, int waves, int row_groups, hipStream_t stream);
 hipError_t bf16_colsum(const KernelArgs &a, int d, int waves, hipStream_t stream);
-hipError_t bf16_sparse(const KernelArgs &a, int d, hipStream_t stream);
+hipError_t bf16_sparse(const KernelArgs &a, int d, bool compact, int n_seq, hipStream_t stream);
+hipError_t launch_compact(const void *k_src, const void *v_src, const int32_t *idx, void *k_dst, void *v_dst,
+                          int Hkv, int d, int k, int esz, hipStream_t stream);
 hipError_t f32_attn(const KernelArgs &a, int d, int row_groups, bool gather, hipStream_t stream);
 hipError_t f32_stats(const KernelArgs &a, int d, int row_groups, hipStream_t stream);
 hipError_t f32_colsum(const KernelArgs &a, int d, hipStream_t stream);
@@ -106,6 +109,51 @@ int run_attention(const mage_shape *shape, const SplitPlan &p, bool gather,
         e = launch_combine(a, shape->d, stream);
         if (e != hipSuccess) return MAGE_ERR_HIP;
     }
+    return MAGE_OK;
+}
+
+// bf16 sparse step: one kernel, partials merged on chip, no workspace.  `compact`: the cache
+// argument already holds the k selected rows; n_seq > 1: strided batch of independent sequences.
+int run_sparse_bf16(const mage_shape *shape, bool compact, int n_seq, const void *q, const void *k_cache,
+                    const void *v_cache, const int32_t *idx, const void *k_blk, const void *v_blk,
+                    float *out, float *lse_out, void *hip_stream)
+{
+    if (!q || !k_cache || !v_cache || !out || (!compact && !idx)) return MAGE_ERR_NULL;
+    if ((k_blk == nullptr) != (v_blk == nullptr)) return MAGE_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(k_blk) || !aligned16(v_blk) ||
+        !aligned16(out))
+        return MAGE_ERR_ALIGN;
+    SplitPlan p{};
+    plan_rows(*shape, p);
+    p.n_split = 1;
+    KernelArgs a = base_args(*shape, p);
+    a.q = q;
+    a.kc = k_cache;
+    a.vc = v_cache;
+    a.kblk = k_blk ? k_blk : k_cache;
+    a.vblk = v_blk ? v_blk : v_cache;
+    a.n_blk = k_blk ? shape->B : 0;
+    a.idx = idx;
+    a.nc = shape->k;
+    a.out = out;
+    a.lse_out = lse_out;
+    if (n_seq > 1) {
+        a.seq_q = (long long)shape->B * shape->Hq * shape->d;
+        a.seq_kv = (long long)shape->L * shape->Hkv * shape->d;
+        a.seq_idx = (long long)shape->Hkv * shape->k;
+        a.seq_blk = k_blk ? (long long)shape->B * shape->Hkv * shape->d : 0;
+        a.seq_out = a.seq_q;
+        a.seq_lse = (long long)shape->B * shape->Hq;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (n_seq > 1 && !compact) {
+        // enough independent work to fill the chip: the tiled kernel with unsplit keys reads every
+        // selected row once per sequence (the latency-oriented kernel re-reads it per row tile)
+        a.kps = (int)align_up((size_t)shape->k, kBf16Tile);
+        a.blk_split = 0;
+        return bf16_attn_batched(a, shape->d, p.waves, p.row_groups, n_seq, stream) == hipSuccess ? MAGE_OK : MAGE_ERR_HIP;
+    }
+    if (bf16_sparse(a, shape->d, compact, n_seq, stream) != hipSuccess) return MAGE_ERR_HIP;
     return MAGE_OK;
 }
 
@@ -252,29 +300,48 @@ int mage_sparse_attn(const mage_shape *shape, const void *q, const void *k_cache
     if (shape->dtype != MAGE_BF16)
         return run_attention(shape, plan_sparse(*shape), true, q, k_cache, v_cache, idx, k_blk, v_blk, out, lse_out,
                              workspace, workspace_bytes, hip_stream);
+    return run_sparse_bf16(shape, false, 1, q, k_cache, v_cache, idx, k_blk, v_blk, out, lse_out, hip_stream);
+}
 
-    // bf16: one kernel, no partials in HBM, no workspace
-    if (!q || !k_cache || !v_cache || !out || !idx) return MAGE_ERR_NULL;
-    if ((k_blk == nullptr) != (v_blk == nullptr)) return MAGE_ERR_NULL;
-    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(k_blk) || !aligned16(v_blk) ||
-        !aligned16(out))
-        return MAGE_ERR_ALIGN;
-    SplitPlan p{};
-    plan_rows(*shape, p);
-    p.n_split = 1;
-    KernelArgs a = base_args(*shape, p);
-    a.q = q;
-    a.kc = k_cache;
-    a.vc = v_cache;
-    a.kblk = k_blk ? k_blk : k_cache;
-    a.vblk = v_blk ? v_blk : v_cache;
-    a.n_blk = k_blk ? shape->B : 0;
-    a.idx = idx;
-    a.nc = shape->k;
-    a.out = out;
-    a.lse_out = lse_out;
-    if (bf16_sparse(a, shape->d, static_cast<hipStream_t>(hip_stream)) != hipSuccess) return MAGE_ERR_HIP;
+int mage_compact(const mage_shape *shape, const void *k_cache, const void *v_cache, const int32_t *idx,
+                 void *k_sel, void *v_sel, void *hip_stream)
+{
+    const int rc = check_shape(shape, true);
+    if (rc != MAGE_OK) return rc;
+    if (!k_cache || !v_cache || !idx || !k_sel || !v_sel) return MAGE_ERR_NULL;
+    if (!aligned16(k_cache) || !aligned16(v_cache) || !aligned16(k_sel) || !aligned16(v_sel)) return MAGE_ERR_ALIGN;
+    const int esz = shape->dtype == MAGE_BF16 ? 2 : 4;
+    if (launch_compact(k_cache, v_cache, idx, k_sel, v_sel, shape->Hkv, shape->d, shape->k, esz,
+                       static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+        return MAGE_ERR_HIP;
     return MAGE_OK;
+}
+
+int mage_sparse_attn_compact(const mage_shape *shape, const void *q, const void *k_sel, const void *v_sel,
+                             const void *k_blk, const void *v_blk, float *out, float *lse_out,
+                             void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    const int rc = check_shape(shape, true);
+    if (rc != MAGE_OK) return rc;
+    if (shape->dtype != MAGE_BF16) {
+        // fp32: the compacted rows are a cache of length k; attend all of it
+        mage_shape s = *shape;
+        s.L = shape->k;
+        return run_attention(&s, plan_dense(s), false, q, k_sel, v_sel, nullptr, k_blk, v_blk, out, lse_out,
+                             workspace, workspace_bytes, hip_stream);
+    }
+    return run_sparse_bf16(shape, true, 1, q, k_sel, v_sel, nullptr, k_blk, v_blk, out, lse_out, hip_stream);
+}
+
+int mage_sparse_attn_batched(const mage_shape *shape, int n_seq, const void *q, const void *k_cache,
+                             const void *v_cache, const int32_t *idx, const void *k_blk, const void *v_blk,
+                             float *out, float *lse_out, void *hip_stream)
+{
+    const int rc = check_shape(shape, true);
+    if (rc != MAGE_OK) return rc;
+    if (n_seq <= 0 || n_seq > 65535) return MAGE_ERR_SHAPE;
+    if (shape->dtype != MAGE_BF16) return MAGE_ERR_UNSUPPORTED;
+    return run_sparse_bf16(shape, false, n_seq, q, k_cache, v_cache, idx, k_blk, v_blk, out, lse_out, hip_stream);
 }
 
 }  // extern "C"

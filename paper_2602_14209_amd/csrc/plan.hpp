@@ -146,6 +146,8 @@ struct KernelArgs {
     long long L;             // rows in the cache
     long long nc;            // cache keys attended: L (dense) or k (gather)
     int kps, n_split, blk_split, n_blk;
+    // batched launches (grid z = sequence): element strides between consecutive sequences, 0 when not batched
+    long long seq_q, seq_kv, seq_idx, seq_blk, seq_out, seq_lse;
     float scale_log2;        // log2(e) / sqrt(d)
     float inv_rows;          // 1 / (G*B)
 };

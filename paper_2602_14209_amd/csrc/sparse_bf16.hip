@@ -6,8 +6,8 @@
 //   - one workgroup per (KV head, 16 query rows); its 8 wavefronts split the KEYS (tiles of 16
 //     key positions, round-robin), so no partial result ever leaves the compute unit: the eight
 //     partial (max, sum, O) are merged through LDS and every output row is written once;
-//   - every load of a pass is in flight at once: the index entries, then K rows straight into
-//     MFMA operand registers (a lane's fragment is 16 contiguous bytes of one row) and V rows
+//   - every load of a pass is in flight at once: the index entries, then K rows into registers
+//     (coalesced 64-byte pieces, moved to their MFMA operand lanes by a lane permute) and V rows
 //     straight into LDS (global_load_lds), from where transposing reads (ds_read_b64_tr_b16)
 //     deliver V^T fragments;
 //   - workgroups of one KV head sit on the same XCD when Hkv is a multiple of 8 (linear
@@ -38,7 +38,9 @@ constexpr int SP_MAXT = SP_WAVES * SP_TPW;   // tiles per pass: all of LDS holds
 // chunk swizzle of a 16-row V tile: rows 0..7 (one half of a transposing read) spread over all banks
 __device__ __forceinline__ int sp_swz(int r) { return ((r & 7) << 1) | (r >> 3); }
 
-template <int D>
+// COMPACT: the k cache positions are rows 0..k-1 of a compacted cache (no index set to read).
+// Grid z = sequence of a batched launch.
+template <int D, bool COMPACT>
 __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2))) void sparse_bf16_kernel(const KernelArgs a)
 {
     constexpr int KS = D / 32;                  // MFMA k-steps of the score product
@@ -62,25 +64,26 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
     const int l16 = lane & 15, lg4 = lane >> 4;
     const int row = rt * 16 + l16;
 
+    MAGE_PROBE_DECL;
     MAGE_PROBE_AT(0);
-    MAGE_PROBE_LAST_AT(0);
     const int n_keys = (int)a.nc + a.n_blk;
     const int ntiles = (n_keys + SP_KT - 1) / SP_KT;
     const int npass = (ntiles + SP_MAXT - 1) / SP_MAXT;
     const int tpp = (ntiles + npass - 1) / npass;           // tiles per pass, balanced
 
     const long long stride = (long long)a.Hkv * D;
-    const u16 *kc = static_cast<const u16 *>(a.kc) + (long long)h * D;
-    const u16 *vc = static_cast<const u16 *>(a.vc) + (long long)h * D;
-    const u16 *kb = static_cast<const u16 *>(a.kblk) + (long long)h * D;
-    const u16 *vb = static_cast<const u16 *>(a.vblk) + (long long)h * D;
-    const int32_t *idx = a.idx + (long long)h * a.nc;
+    const long long z = blockIdx.z;
+    const u16 *kc = static_cast<const u16 *>(a.kc) + z * a.seq_kv + (long long)h * D;
+    const u16 *vc = static_cast<const u16 *>(a.vc) + z * a.seq_kv + (long long)h * D;
+    const u16 *kb = static_cast<const u16 *>(a.kblk) + z * a.seq_blk + (long long)h * D;
+    const u16 *vb = static_cast<const u16 *>(a.vblk) + z * a.seq_blk + (long long)h * D;
+    const int32_t *idx = COMPACT ? nullptr : a.idx + z * a.seq_idx + (long long)h * a.nc;
 
     // query fragment: row l16 of this row tile, channels 32*ks + 8*lg4 .. +7
     bf16x8_t qf[KS];
     if (row < a.R) {
         const int gl = row / a.B, qi = row - gl * a.B;
-        const u16 *src = static_cast<const u16 *>(a.q) + ((long long)qi * a.Hq + (long long)h * a.G + gl) * D + 8 * lg4;
+        const u16 *src = static_cast<const u16 *>(a.q) + z * a.seq_q + ((long long)qi * a.Hq + (long long)h * a.G + gl) * D + 8 * lg4;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) qf[ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(src + ks * 32));
     } else {
@@ -111,19 +114,21 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
             int p = tile_of[j] * SP_KT + l16;
             p = p < n_keys ? p : n_keys - 1;                // padding positions re-read the last key (masked below)
             const int pc = p < (int)a.nc ? p : (int)a.nc - 1;
-            const int ci = idx[pc];
+            const int ci = COMPACT ? pc : idx[pc];
             enc[j] = p < (int)a.nc ? ci : -1 - (p - (int)a.nc);
         }
-        bf16x8_t kf[SP_TPW][KS];
+        // K fragments.  The MFMA wants lane (16*c + r) to hold channels [32*ks + 8*c, +8) of tile row r,
+        // but a load in that pattern touches 64 separate 16-byte pieces per instruction.  Load
+        // coalesced instead -- lane 4*r + c fetches that same piece, so each lane quad reads 64
+        // contiguous bytes of one row -- and move the pieces to their MFMA lanes with a lane permute.
+        uint4 kraw[SP_TPW][KS];
+        auto load_k = [&](int j) {
+            const int e = __shfl(enc[j], lane >> 2);
+            const u16 *src = e >= 0 ? kc + (long long)e * stride : kb + (long long)(-1 - e) * stride;
 #pragma unroll
-        for (int j = 0; j < SP_TPW; ++j) {
-            const u16 *src = enc[j] >= 0 ? kc + (long long)enc[j] * stride : kb + (long long)(-1 - enc[j]) * stride;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                kf[j][ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(src + ks * 32 + 8 * lg4));
-        }
-#pragma unroll
-        for (int j = 0; j < SP_TPW; ++j) {
+            for (int ks = 0; ks < KS; ++ks) kraw[j][ks] = *reinterpret_cast<const uint4 *>(src + ks * 32 + 8 * (lane & 3));
+        };
+        auto load_v = [&](int j) {
             unsigned char *dst = vlds + (j * SP_WAVES + wave) * TILE_BYTES;
 #pragma unroll
             for (int n = 0; n < VLOADS; ++n) {
@@ -134,9 +139,35 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
                 __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + chunk * 8),
                                                  (__attribute__((address_space(3))) void *)(dst + n * 1024), 16, 0, 0);
             }
-        }
+        };
+        // the first SP_TPW-1 tile slots unconditionally; the last slot is filled for few wavefronts
+        // only, so it sits behind a branch (nothing right after the branches depends on a pending load)
+        // (all K before any V, so that the scores can start while V is still arriving)
+#pragma unroll
+        for (int j = 0; j < SP_TPW - 1; ++j) load_k(j);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) kraw[SP_TPW - 1][ks] = make_uint4(0, 0, 0, 0);
+        if (my_tiles == SP_TPW) load_k(SP_TPW - 1);
+#pragma unroll
+        for (int j = 0; j < SP_TPW - 1; ++j) load_v(j);
+        if (my_tiles == SP_TPW) load_v(SP_TPW - 1);
 
         __builtin_amdgcn_sched_barrier(0);     // keep every load ahead of the first MFMA (and its wait)
+        bf16x8_t kf[SP_TPW][KS];
+        {
+            const int from = 4 * (4 * l16 + lg4);            // byte address of the source lane for ds_bpermute
+#pragma unroll
+            for (int j = 0; j < SP_TPW; ++j)
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    uint4 t;
+                    t.x = __builtin_amdgcn_ds_bpermute(from, kraw[j][ks].x);
+                    t.y = __builtin_amdgcn_ds_bpermute(from, kraw[j][ks].y);
+                    t.z = __builtin_amdgcn_ds_bpermute(from, kraw[j][ks].z);
+                    t.w = __builtin_amdgcn_ds_bpermute(from, kraw[j][ks].w);
+                    kf[j][ks] = __builtin_bit_cast(bf16x8_t, t);
+                }
+        }
         MAGE_PROBE_AT(1);
         // ---- scores: sc[j][v] = S^T(key 4*lg4 + v of tile j, query row l16) ----
         f32x4_t sc[SP_TPW];
@@ -205,7 +236,6 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
     }
 
     MAGE_PROBE_AT(4);
-    MAGE_PROBE_LAST_AT(4);
     // ---- merge the eight wavefronts through LDS ----
     float l_w = l_run + __shfl_xor(l_run, 16);
     l_w += __shfl_xor(l_w, 32);
@@ -230,26 +260,71 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
         wgt[w] = __builtin_amdgcn_exp2f(ml[0][w][l16] - M);
         lt = fmaf(wgt[w], ml[1][w][l16], lt);
     }
-    if (row >= a.R) return;
+    if (row >= a.R) {
+        MAGE_PROBE_FLUSH();
+        return;
+    }
     const int gl = row / a.B, qi = row - gl * a.B;
     const long long orow = (long long)qi * a.Hq + (long long)h * a.G + gl;
+    float *out = a.out + z * a.seq_out;
     const float inv = 1.f / lt;
     for (int dt = wave; dt < DT; dt += SP_WAVES) {
         f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int w = 0; w < SP_WAVES; ++w) acc += part[(w * DT + dt) * 64 + lane] * wgt[w];
-        *reinterpret_cast<f32x4_t *>(a.out + orow * D + 16 * dt + 4 * lg4) = acc * inv;
+        *reinterpret_cast<f32x4_t *>(out + orow * D + 16 * dt + 4 * lg4) = acc * inv;
     }
     MAGE_PROBE_AT(5);
-    if (a.lse_out && wave == 0 && lg4 == 0) a.lse_out[orow] = (M + log2f(lt)) * 0.6931471805599453f;
+    MAGE_PROBE_FLUSH();
+    if (a.lse_out && wave == 0 && lg4 == 0) a.lse_out[z * a.seq_lse + orow] = (M + log2f(lt)) * 0.6931471805599453f;
 }
 
-hipError_t bf16_sparse(const KernelArgs &a, int d, hipStream_t stream)
+// Copies the selected rows into a cache of length k: dst[p,h,:] = src[idx[h,p],h,:] (16 bytes per
+// thread, a row per D/8 consecutive threads).  The index set is fixed for steps 2..T, so this is
+// done once per block.
+template <int ESZ>
+__global__ __launch_bounds__(256) void compact_kernel(const unsigned char *__restrict__ k_src, const unsigned char *__restrict__ v_src,
+                                                      const int32_t *__restrict__ idx, unsigned char *__restrict__ k_dst,
+                                                      unsigned char *__restrict__ v_dst, int Hkv, int d, int k)
 {
-    dim3 grid(a.Hkv, (a.R + 15) / 16), block(SP_WAVES * 64);
-    if (d == 128) hipLaunchKernelGGL((sparse_bf16_kernel<128>), grid, block, 0, stream, a);
-    else if (d == 64) hipLaunchKernelGGL((sparse_bf16_kernel<64>), grid, block, 0, stream, a);
-    else return hipErrorInvalidValue;
+    const int cpr = d * ESZ / 16;                                // 16-byte chunks per row
+    const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+    const long long rowid = t / cpr;                             // (p, h)
+    const int c = (int)(t % cpr);
+    if (rowid >= (long long)k * Hkv) return;
+    const int p = (int)(rowid / Hkv), h = (int)(rowid % Hkv);
+    const long long src = ((long long)idx[(long long)h * k + p] * Hkv + h) * d * ESZ + c * 16;
+    const long long dst = rowid * d * ESZ + c * 16;
+    *reinterpret_cast<uint4 *>(k_dst + dst) = *reinterpret_cast<const uint4 *>(k_src + src);
+    *reinterpret_cast<uint4 *>(v_dst + dst) = *reinterpret_cast<const uint4 *>(v_src + src);
+}
+
+hipError_t launch_compact(const void *k_src, const void *v_src, const int32_t *idx, void *k_dst, void *v_dst,
+                          int Hkv, int d, int k, int esz, hipStream_t stream)
+{
+    const long long threads = (long long)k * Hkv * (d * esz / 16);
+    dim3 grid((unsigned)((threads + 255) / 256)), block(256);
+    if (esz == 2)
+        hipLaunchKernelGGL(compact_kernel<2>, grid, block, 0, stream, (const unsigned char *)k_src, (const unsigned char *)v_src, idx,
+                           (unsigned char *)k_dst, (unsigned char *)v_dst, Hkv, d, k);
+    else
+        hipLaunchKernelGGL(compact_kernel<4>, grid, block, 0, stream, (const unsigned char *)k_src, (const unsigned char *)v_src, idx,
+                           (unsigned char *)k_dst, (unsigned char *)v_dst, Hkv, d, k);
+    return hipGetLastError();
+}
+
+hipError_t bf16_sparse(const KernelArgs &a, int d, bool compact, int n_seq, hipStream_t stream)
+{
+    dim3 grid(a.Hkv, (a.R + 15) / 16, n_seq), block(SP_WAVES * 64);
+    if (d == 128) {
+        if (compact) hipLaunchKernelGGL((sparse_bf16_kernel<128, true>), grid, block, 0, stream, a);
+        else hipLaunchKernelGGL((sparse_bf16_kernel<128, false>), grid, block, 0, stream, a);
+    } else if (d == 64) {
+        if (compact) hipLaunchKernelGGL((sparse_bf16_kernel<64, true>), grid, block, 0, stream, a);
+        else hipLaunchKernelGGL((sparse_bf16_kernel<64, false>), grid, block, 0, stream, a);
+    } else {
+        return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 

@@ -173,6 +173,7 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, lo
     const uint32_t *u = reinterpret_cast<const uint32_t *>(alpha) + (long long)h * L;
     int32_t *out = idx_out + (long long)h * k;
 
+    MAGE_PROBE_DECL;
     MAGE_PROBE_AT(0);
     if (k <= TK_FILTER_MAX_K) {
         // ---- filter route, sweep 1: strided group maxima (group = slot * 1024 + thread) ----
@@ -310,6 +311,7 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, lo
                 for (int i = threadIdx.x; i < k; i += TK_THREADS) out[i] = sidx[i];
             }
             MAGE_PROBE_AT(4);
+            MAGE_PROBE_FLUSH();
             return;
         }
         __syncthreads();                                 // too many ties at the bound: radix route

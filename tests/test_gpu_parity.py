@@ -185,3 +185,63 @@ def test_c4_full_size_headline_shape(oracle_mod):
         o_ref, l_ref = oracle_mod.sparse_attn(x["q"][1], x["k_cache"], x["v_cache"], ref_k, x["k_blk"][1], x["v_blk"][1])
         o, l = pk.sparse(ref_k)
         check_out(o, o_ref, l, l_ref, w.dtype)
+
+
+@pytest.mark.parametrize("case", [
+    ("k1", "bf16", 8, 2, 128, 3000, 32, 200),
+    ("k2", "bf16", 6, 2, 64, 500, 7, 37),
+    ("k3", "f32", 4, 2, 64, 300, 5, 50),
+    ("k4", "bf16", 32, 8, 128, 20000, 32, 1024),      # two passes of the sparse kernel
+])
+def test_compacted_rows(oracle_mod, case):
+    """mage_compact is a copy (bit-exact); mage_sparse_attn_compact equals the sparse step."""
+    import torch
+    import paper_2602_14209_amd.binding as mb
+    from gpu_util import Problem, check_out, to_device
+    name, dtype, Hq, Hkv, d, L, B, k = case
+    w = Workload(name, dtype, Hq=Hq, Hkv=Hkv, d=d, L=L, B=B, ks=(k,), T=2, heavy_frac=0.02, heavy_scale=3.0)
+    x = make_layer(w, 321)
+    print(f"[parity] compact {case}", flush=True)
+    p = Problem(x["q"][1], x["k_cache"], x["v_cache"], x["k_blk"][1], x["v_blk"][1], k, dtype)
+    rng = np.random.default_rng(9)
+    idx = np.stack([rng.permutation(L)[:k] for _ in range(Hkv)]).astype(np.int32)     # unsorted on purpose
+    idx_d = torch.from_numpy(idx).cuda()
+    k_sel = torch.zeros((k, Hkv, d), dtype=p.kc.dtype, device="cuda")
+    v_sel = torch.zeros_like(k_sel)
+    mb.check(mb.mage_compact(p.shape, p.kc, p.vc, idx_d, k_sel, v_sel), "mage_compact")
+    torch.cuda.synchronize()
+    want_k = to_device(oracle_mod.compact(x["k_cache"], idx), dtype)
+    want_v = to_device(oracle_mod.compact(x["v_cache"], idx), dtype)
+    as_bits = (lambda t: t.view(torch.int16)) if dtype == "bf16" else (lambda t: t.view(torch.int32))
+    assert torch.equal(as_bits(k_sel), as_bits(want_k)) and torch.equal(as_bits(v_sel), as_bits(want_v))
+    o_ref, l_ref = oracle_mod.sparse_attn(x["q"][1], x["k_cache"], x["v_cache"], idx, x["k_blk"][1], x["v_blk"][1])
+    p.out.fill_(float("nan"))
+    mb.check(mb.mage_sparse_attn_compact(p.shape, p.q, k_sel, v_sel, p.kb, p.vb, p.out, p.lse, p.ws), "compact attn")
+    torch.cuda.synchronize()
+    check_out(p.out.cpu().numpy(), o_ref, p.lse.cpu().numpy(), l_ref, dtype)
+    o, l = p.sparse(idx)
+    check_out(o, o_ref, l, l_ref, dtype)
+
+
+def test_batched_sparse_step(oracle_mod):
+    """n_seq independent sequences in one launch equal n_seq single calls (and the oracle)."""
+    import torch
+    import paper_2602_14209_amd.binding as mb
+    from gpu_util import check_out, to_device
+    n_seq = 3
+    w = Workload("bt", "bf16", Hq=8, Hkv=2, d=128, L=2500, B=32, ks=(300,), T=2, heavy_frac=0.02, heavy_scale=3.0)
+    k = 300
+    xs = [make_layer(w, 500 + s) for s in range(n_seq)]
+    rng = np.random.default_rng(4)
+    idx = np.stack([np.stack([np.sort(rng.choice(w.L, k, replace=False)) for _ in range(w.Hkv)]) for _ in range(n_seq)]).astype(np.int32)
+    stack = lambda name, t=None: to_device(np.stack([x[name] if t is None else x[name][t] for x in xs]), "bf16")
+    q, kc, vc, kb, vb = stack("q", 1), stack("k_cache"), stack("v_cache"), stack("k_blk", 1), stack("v_blk", 1)
+    out = torch.full((n_seq, w.B, w.Hq, w.d), float("nan"), dtype=torch.float32, device="cuda")
+    lse = torch.full((n_seq, w.B, w.Hq), float("nan"), dtype=torch.float32, device="cuda")
+    shape = mb.make_shape(w.B, w.Hq, w.Hkv, w.d, w.L, k, "bf16")
+    print("[parity] batched sparse step", flush=True)
+    mb.check(mb.mage_sparse_attn_batched(shape, n_seq, q, kc, vc, torch.from_numpy(idx).cuda(), kb, vb, out, lse), "batched")
+    torch.cuda.synchronize()
+    for s in range(n_seq):
+        o_ref, l_ref = oracle_mod.sparse_attn(xs[s]["q"][1], xs[s]["k_cache"], xs[s]["v_cache"], idx[s], xs[s]["k_blk"][1], xs[s]["v_blk"][1])
+        check_out(out[s].cpu().numpy(), o_ref, lse[s].cpu().numpy(), l_ref, "bf16")

@@ -58,6 +58,9 @@ def test_argument_validation_happens_before_any_launch(kw, code):
     assert L.mage_select(ctypes.byref(s), fake, fake, fake, None, fake, 1 << 40, None) == code
     assert L.mage_sparse_attn(ctypes.byref(s), fake, fake, fake, fake, fake, fake, fake, None, fake, 1 << 40, None) == code
     assert L.mage_step1(ctypes.byref(s), fake, fake, fake, fake, fake, fake, None, fake, None, fake, 1 << 40, None) == code
+    assert L.mage_compact(ctypes.byref(s), fake, fake, fake, fake, fake, None) == code
+    assert L.mage_sparse_attn_compact(ctypes.byref(s), fake, fake, fake, fake, fake, fake, None, fake, 1 << 40, None) == code
+    assert L.mage_sparse_attn_batched(ctypes.byref(s), 2, fake, fake, fake, fake, fake, fake, fake, None, None) == code
     if "k" not in kw:
         assert L.mage_exact_attn(ctypes.byref(s), fake, fake, fake, fake, fake, fake, None, fake, 1 << 40, None) == code
 
@@ -78,6 +81,13 @@ def test_null_alignment_and_workspace_errors():
     assert L.mage_exact_attn(ctypes.byref(s), fake, fake, odd, fake, fake, fake, None, fake, big, None) == -6
     assert L.mage_exact_attn(ctypes.byref(s), fake, fake, fake, fake, fake, fake, None, fake, 16, None) == -4
     assert L.mage_sparse_attn(ctypes.byref(s), fake, fake, fake, None, fake, fake, fake, None, fake, big, None) == -1
+    assert L.mage_compact(ctypes.byref(s), fake, fake, None, fake, fake, None) == -1
+    assert L.mage_compact(ctypes.byref(s), fake, odd, fake, fake, fake, None) == -6
+    assert L.mage_sparse_attn_compact(ctypes.byref(s), None, fake, fake, fake, fake, fake, None, None, 0, None) == -1
+    assert L.mage_sparse_attn_batched(ctypes.byref(s), 0, fake, fake, fake, fake, fake, fake, fake, None, None) == -2
+    assert L.mage_sparse_attn_batched(ctypes.byref(s), 2, fake, fake, fake, None, fake, fake, fake, None, None) == -1
+    sf32 = mb.make_shape(32, 32, 8, 128, 4096, 512, "f32")
+    assert L.mage_sparse_attn_batched(ctypes.byref(sf32), 2, fake, fake, fake, fake, fake, fake, fake, None, None) == -3
     assert L.mage_step1(ctypes.byref(s), fake, fake, fake, fake, fake, fake, None, None, None, fake, big, None) == -1
     assert L.mage_step1(ctypes.byref(s), fake, fake, fake, fake, fake, fake, None, fake, None, fake, 16, None) == -4
     # the bf16 sparse step keeps its partials on chip and needs no workspace; the fp32 one does

@@ -323,3 +323,23 @@ def test_sparse_rejects_out_of_range_index(oracle_mod):
         oracle_mod.sparse_attn(q, kc, kc, np.array([[8]], np.int32))
     with pytest.raises(RuntimeError):
         oracle_mod.sparse_attn(q, kc, kc, np.array([[-1]], np.int32))
+
+
+def test_compact_is_fancy_indexing_and_commutes_with_attention(oracle_mod):
+    rng = _rng(30)
+    B, Hq, Hkv, d, L, k = 3, 4, 2, 64, 120, 11
+    q = rng.standard_normal((B, Hq, d)).astype(np.float32)
+    kc = rng.standard_normal((L, Hkv, d)).astype(np.float32)
+    vc = rng.standard_normal((L, Hkv, d)).astype(np.float32)
+    kb = rng.standard_normal((B, Hkv, d)).astype(np.float32)
+    vb = rng.standard_normal((B, Hkv, d)).astype(np.float32)
+    idx = np.stack([rng.permutation(L)[:k] for _ in range(Hkv)]).astype(np.int32)
+    ks, vs = oracle_mod.compact(kc, idx), oracle_mod.compact(vc, idx)
+    want = np.stack([kc[idx[h], h] for h in range(Hkv)], axis=1)        # numpy fancy indexing, [k,Hkv,d]
+    assert np.array_equal(ks, want)
+    # attending the compacted rows exactly is attending the selected rows sparsely
+    o1, l1 = oracle_mod.sparse_attn(q, kc, vc, idx, kb, vb)
+    o2, l2 = oracle_mod.exact_attn(q, ks, vs, kb, vb)
+    assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
+    with pytest.raises(RuntimeError):
+        oracle_mod.compact(kc, np.full((Hkv, 2), L, np.int32))
