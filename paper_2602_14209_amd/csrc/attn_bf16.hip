@@ -27,6 +27,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <utility>
+
 #include "plan.hpp"
 #include "probe.hpp"
 
@@ -38,6 +40,8 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x8_t __attribute__((ext_vector_type(8)));
 typedef unsigned short u16;
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
 
 enum { MODE_ATTN = 0, MODE_STATS = 1 };
 
@@ -121,34 +125,147 @@ __device__ __forceinline__ void stream_pointers(const u16 *kc, long long c0, lon
 template <int PENDING>
 __device__ __forceinline__ void tile_barrier()
 {
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PENDING) : "memory");
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(PENDING) : "memory");
     __syncthreads();
 }
 
-// K fragment: key row `rk` of the tile, channels [16*ks + 8*lg, +8)
-template <int D>
-__device__ __forceinline__ bf16x8_t read_k_frag(const unsigned char *kbuf, int rk, int ks, int lg)
-{
-    const int chunk = (2 * ks + lg) ^ swz<D>(rk);
-    return as_bf16x8(*reinterpret_cast<const uint4 *>(kbuf + rk * TileGeom<D>::ROW_BYTES + chunk * 16));
-}
+// Fragment reads.  The swizzle only changes address bits 4..7 (below the row pitch), and so do the
+// per-read terms (MFMA k-step for K, O^T tile for V); a row offset leaves those bits alone.  A read
+// address is therefore (lane constant) ^ (compile-time constant) + (compile-time offset): one
+// VALU op per read and three live address registers for the whole tile loop.
+struct FragAddr {
+    unsigned k;      // K fragment of key row l32, k-step 0
+    unsigned v[2];   // the two transposing reads of a V^T fragment at key block 0, O^T tile 0
+};
 
-// V^T fragment for O^T tile dt: lane holds channel dt*32 + (lane & 31) of the 8 keys
-// key0 + {0,1,2,3, 8,9,10,11}.  Within each 16-lane block, lane i' addresses 4 channels
-// (4*(i' & 3) ..) of key (i' >> 2); the transposing read hands lane i the 4 keys at channel i.
 template <int D>
-__device__ __forceinline__ bf16x8_t read_vt_frag(const unsigned char *vbuf, int key0, int dt, int lane)
+__device__ __forceinline__ FragAddr frag_addr(int lane)
 {
+    constexpr int ROW = TileGeom<D>::ROW_BYTES;
+    FragAddr f;
+    const int l32 = lane & 31, lg = lane >> 5;
+    // chunk (2*ks + lg) ^ swz = (2*ks) ^ (lg ^ swz): bit 0 belongs to lg alone
+    f.k = (unsigned)(l32 * ROW) | (unsigned)((lg ^ swz<D>(l32)) << 4);
+    // V^T: within each 16-lane block, lane i' addresses 4 channels (4*(i' & 3) ..) of key (i' >> 2);
+    // the transposing read hands lane i the 4 keys at channel i.  Channel chunk of O^T tile dt is
+    // 4*dt + low with low = 2*(blk & 1) + (q >> 1); key = 16*(2*kt + m2) + 8*b + 4*lg + j.
     const int blk = lane >> 4, ip = lane & 15;
     const int j = ip >> 2, q = ip & 3;
-    const int d = dt * 32 + 16 * (blk & 1) + 4 * q;
-    const int key_a = key0 + j, key_b = key0 + 8 + j;
-    const unsigned char *pa = vbuf + key_a * TileGeom<D>::ROW_BYTES + (((d >> 3) ^ swz<D>(key_a)) * 16) + 8 * (q & 1);
-    const unsigned char *pb = vbuf + key_b * TileGeom<D>::ROW_BYTES + (((d >> 3) ^ swz<D>(key_b)) * 16) + 8 * (q & 1);
-    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t *)(pa));
-    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t *)(pb));
-    const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(bf16x8_t, both);
+    const int low = 2 * (blk & 1) + (q >> 1);
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+        const int key = 8 * b + 4 * lg + j;
+        f.v[b] = (unsigned)(key * ROW) | (unsigned)((low ^ swz<D>(key)) << 4) | (unsigned)(8 * (q & 1));
+    }
+    return f;
+}
+
+// The LDS reads of the tile loop are inline assembly.  The compiler orders every LDS access it
+// knows of behind ALL outstanding direct-to-LDS loads (it cannot tell the ring buffers apart), which
+// would put the whole HBM latency of the prefetch of tile t+1 in front of the arithmetic of tile t.
+// The price is that the waits are ours: lds_wait<N> holds the named registers until at most N
+// younger LDS operations of this wavefront are outstanding (LDS returns data in issue order).
+template <int OFF>
+__device__ __forceinline__ u32x4_t lds_read_b128(unsigned addr)
+{
+    u32x4_t r;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+    return r;
+}
+
+// Transposing read: within each 16-lane block, lane i' addresses 4 channels of one key; lane i
+// receives channel i of 4 keys.
+template <int OFF>
+__device__ __forceinline__ u32x2_t lds_read_tr16_b64(unsigned addr)
+{
+    u32x2_t r;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+    return r;
+}
+
+template <int N>
+__device__ __forceinline__ void lds_wait(u32x4_t &r)
+{
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(r) : "n"(N));
+}
+
+template <int N>
+__device__ __forceinline__ void lds_wait(u32x2_t &a, u32x2_t &b)
+{
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
+}
+
+template <int OFF>
+__device__ __forceinline__ float lds_read_f32(unsigned addr)
+{
+    float r;
+    asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+    return r;
+}
+
+template <int N>
+__device__ __forceinline__ void lds_wait(float &r)
+{
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(r) : "n"(N));
+}
+
+__device__ __forceinline__ unsigned lds_addr(const void *p) { return (unsigned)(uintptr_t)MAGE_LDS_PTR(p); }
+
+template <int... I, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F &&f)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
+
+// Scores of one 64-key tile against the wavefront's 32 query rows: two 32-key halves, K fragments
+// (key row kt*32 + l32, channels [16*ks + 8*lg, +8)) read KS deep ahead of the MFMA that uses them.
+// KEYS_AS_A: S^T = K Q^T (a lane holds 16 keys of one query row); otherwise S = Q K^T.
+template <int D, bool KEYS_AS_A>
+__device__ __forceinline__ void qk_tile(unsigned ka, const bf16x8_t (&qf)[D / 16], f32x16_t (&sc)[2])
+{
+    constexpr int KS = D / 16;
+    constexpr int HALF = 32 * TileGeom<D>::ROW_BYTES;
+    u32x4_t k0[KS], k1[KS];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) sc[0][v] = sc[1][v] = 0.f;
+    static_for<KS>([&](auto S) {
+        constexpr int ks = decltype(S)::value;
+        k0[ks] = lds_read_b128<0>(ka ^ (unsigned)(ks << 5));
+    });
+    static_for<KS>([&](auto S) {
+        constexpr int ks = decltype(S)::value;
+        lds_wait<KS - 1>(k0[ks]);
+        const bf16x8_t kf = __builtin_bit_cast(bf16x8_t, k0[ks]);
+        sc[0] = KEYS_AS_A ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sc[0], 0, 0, 0)
+                          : __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[ks], kf, sc[0], 0, 0, 0);
+        k1[ks] = lds_read_b128<HALF>(ka ^ (unsigned)(ks << 5));
+    });
+    static_for<KS>([&](auto S) {
+        constexpr int ks = decltype(S)::value;
+        lds_wait<KS - 1 - ks>(k1[ks]);
+        const bf16x8_t kf = __builtin_bit_cast(bf16x8_t, k1[ks]);
+        sc[1] = KEYS_AS_A ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sc[1], 0, 0, 0)
+                          : __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[ks], kf, sc[1], 0, 0, 0);
+    });
+}
+
+// V^T fragments of key group g (16 keys: 16*g + 4*lg + {0..3, 8..11}) for all O^T tiles: lane
+// holds channel dt*32 + (lane & 31).
+template <int D, int GRP>
+__device__ __forceinline__ void issue_vt_group(const unsigned (&va)[2], u32x2_t (&vf)[D / 32][2])
+{
+    constexpr int OFF = GRP * 16 * TileGeom<D>::ROW_BYTES;
+    static_for<D / 32>([&](auto T) {
+        constexpr int dt = decltype(T)::value;
+        vf[dt][0] = lds_read_tr16_b64<OFF>(va[0] ^ (unsigned)(dt << 6));
+        vf[dt][1] = lds_read_tr16_b64<OFF>(va[1] ^ (unsigned)(dt << 6));
+    });
 }
 
 // Query fragment of this lane: row (l % 32) of the wavefront's M tile, 8 consecutive channels
@@ -168,20 +285,25 @@ __device__ __forceinline__ void load_q_frag(const KernelArgs &a, const u16 *q, i
     }
 }
 
-// Which keys does split `s` cover?  Cache keys [c0, c1) and, on the block split, n_blk block keys.
+// Which keys does split `s` cover?  Cache tiles are dealt round-robin: split s < n_cyc owns the
+// 64-key tiles s, s + n_cyc, s + 2*n_cyc, ...  Workgroups that run at the same time then read one
+// moving window of consecutive memory instead of one far-apart stream each, which is the access
+// pattern the memory controllers serve fastest.  The block split adds the n_blk in-block keys.
 struct SplitRange {
-    long long c0, c1;
+    long long first;      // first key of this split's first tile
+    long long step;       // keys between consecutive tiles of this split
+    long long nc;         // cache keys in all
     int cache_tiles, blk_tiles;
 };
 
 __device__ __forceinline__ SplitRange split_range(const KernelArgs &a, int s)
 {
     SplitRange r;
-    r.c0 = (long long)s * a.kps;
-    r.c1 = r.c0 + a.kps;
-    if (r.c1 > a.nc) r.c1 = a.nc;
-    if (r.c0 > r.c1) r.c0 = r.c1;
-    r.cache_tiles = (int)((r.c1 - r.c0 + kBf16Tile - 1) / kBf16Tile);
+    const long long total = (a.nc + kBf16Tile - 1) / kBf16Tile;
+    r.first = (long long)s * kBf16Tile;
+    r.step = (long long)a.n_cyc * kBf16Tile;
+    r.nc = a.nc;
+    r.cache_tiles = (s < a.n_cyc && total > s) ? (int)((total - s + a.n_cyc - 1) / a.n_cyc) : 0;
     r.blk_tiles = (s == a.blk_split) ? (a.n_blk + kBf16Tile - 1) / kBf16Tile : 0;
     return r;
 }
@@ -229,15 +351,15 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 
     auto tile_valid = [&](int t) -> int {
         if (t < sr.cache_tiles) {
-            const long long left = sr.c1 - (sr.c0 + (long long)t * kBf16Tile);
+            const long long left = sr.nc - (sr.first + t * sr.step);
             return left < kBf16Tile ? (int)left : kBf16Tile;
         }
         const int left = a.n_blk - (t - sr.cache_tiles) * kBf16Tile;
         return left < kBf16Tile ? left : kBf16Tile;
     };
     const u16 *kptr[G::LOADS / NW];
-    if (!GATHER) stream_pointers<D, NW>(kc, sr.c0, cache_stride, kptr);
-    const long long tile_elems = (long long)kBf16Tile * cache_stride;
+    if (!GATHER) stream_pointers<D, NW>(kc, sr.first, cache_stride, kptr);
+    const long long tile_elems = sr.step * cache_stride;
     const long long v_minus_k = vc - kc;
     auto issue = [&](int t) {
         const int valid = tile_valid(t);
@@ -245,7 +367,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
         if (!GATHER && t < sr.cache_tiles && valid == kBf16Tile) {
             issue_tile_stream<D, NW, WITH_V>(kptr, tile_elems, v_minus_k, t, buf);
         } else if (t < sr.cache_tiles) {
-            const long long base = sr.c0 + (long long)t * kBf16Tile;
+            const long long base = sr.first + t * sr.step;
             issue_tile<D, NW, WITH_V>(kc, vc, cache_stride, buf, [&](int r) -> long long {
                 const long long pos = base + (r < valid ? r : valid - 1);
                 return GATHER ? (long long)idx[pos] : pos;
@@ -262,6 +384,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 
     bf16x8_t qf[KS];
     load_q_frag<D>(a, static_cast<const u16 *>(a.q) + z * a.seq_q, h, row, qf);
+    FragAddr fa = frag_addr<D>(lane);
+    const unsigned smem_addr = lds_addr(smem);
 
     f32x16_t o[WITH_V ? DT : 1];
 #pragma unroll
@@ -278,8 +402,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
         if (t == 0) MAGE_PROBE_AT(1);
         if (t + NBUF - 1 < ntiles) issue(t + NBUF - 1);
         const int valid = tile_valid(t);
-        const unsigned char *kbuf = smem + (t % NBUF) * BUF_BYTES;
-        const unsigned char *vbuf = kbuf + G::MAT_BYTES;
+        const unsigned tile_addr = smem_addr + (t % NBUF) * BUF_BYTES;
+        // keep the per-read address arithmetic inside the loop: hoisted, it would pin 48 registers
+        asm volatile("" : "+v"(fa.k), "+v"(fa.v[0]), "+v"(fa.v[1]));
         if (WITH_V && t == sr.cache_tiles) {   // first in-block tile: freeze the prefix statistics
             m_pre = m_run;
             l_pre = l_run;
@@ -292,16 +417,11 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 #endif
             // S^T tile: sc[kt][v] = score of query row l32 against key kt*32 + 8*(v/4) + 4*lg + v%4
             f32x16_t sc[2];
-#pragma unroll
-            for (int kt = 0; kt < 2; ++kt) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) sc[kt][v] = 0.f;
-                bf16x8_t kf[KS];
-#pragma unroll
-                for (int s = 0; s < KS; ++s) kf[s] = read_k_frag<D>(kbuf, kt * 32 + l32, s, lg);
-#pragma unroll
-                for (int s = 0; s < KS; ++s) sc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[s], sc[kt], 0, 0, 0);
-            }
+            qk_tile<D, true>(tile_addr + fa.k, qf, sc);
+            // the first V^T fragments travel while the softmax runs
+            const unsigned va[2] = {tile_addr + G::MAT_BYTES + fa.v[0], tile_addr + G::MAT_BYTES + fa.v[1]};
+            u32x2_t vf[2][WITH_V ? DT : 1][2];
+            if constexpr (WITH_V) issue_vt_group<D, 0>(va, vf[0]);
             if (valid < kBf16Tile) {           // uniform: only the last tile of a slice has padding keys
 #pragma unroll
                 for (int kt = 0; kt < 2; ++kt)
@@ -328,26 +448,28 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
                 }
             l_run = l_run * corr + psum;
 
-            if (WITH_V) {
+            if constexpr (WITH_V) {
                 if (__any(grew)) {             // rescale only when some row's maximum moved
 #pragma unroll
                     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
                         for (int v = 0; v < 16; ++v) o[dt][v] *= corr;
                 }
+                // key group g = 2*kt + m2: P^T fragment from sc[kt][8*m2 ..], V^T fragments of
+                // group g+1 requested before group g is consumed
+                static_for<4>([&](auto GI) {
+                    constexpr int g = decltype(GI)::value;
+                    bf16x8_t pf;
 #pragma unroll
-                for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-                    for (int m2 = 0; m2 < 2; ++m2) {
-                        bf16x8_t pf;
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) pf[e] = (__bf16)sc[kt][8 * m2 + e];
-                        bf16x8_t vf[DT];
-#pragma unroll
-                        for (int dt = 0; dt < DT; ++dt) vf[dt] = read_vt_frag<D>(vbuf, kt * 32 + m2 * 16 + 4 * lg, dt, lane);
-#pragma unroll
-                        for (int dt = 0; dt < DT; ++dt) o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt], pf, o[dt], 0, 0, 0);
-                    }
+                    for (int e = 0; e < 8; ++e) pf[e] = (__bf16)sc[g >> 1][8 * (g & 1) + e];
+                    if constexpr (g < 3) issue_vt_group<D, g + 1>(va, vf[(g + 1) & 1]);
+                    static_for<DT>([&](auto T) {
+                        constexpr int dt = decltype(T)::value;
+                        lds_wait<(g < 3 ? 2 * DT : 0) + 2 * (DT - 1 - dt)>(vf[g & 1][dt][0], vf[g & 1][dt][1]);
+                        const u32x4_t both = {vf[g & 1][dt][0][0], vf[g & 1][dt][0][1], vf[g & 1][dt][1][0], vf[g & 1][dt][1][1]};
+                        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, both), pf, o[dt], 0, 0, 0);
+                    });
+                });
             }
         }
     }
@@ -453,19 +575,19 @@ __global__ __launch_bounds__(NW * 64) void colsum_bf16_kernel(const KernelArgs a
     const u16 *kc = static_cast<const u16 *>(a.kc) + (long long)h * D;
 
     auto tile_valid = [&](int t) -> int {
-        const long long left = sr.c1 - (sr.c0 + (long long)t * kBf16Tile);
+        const long long left = sr.nc - (sr.first + t * sr.step);
         return left < kBf16Tile ? (int)left : kBf16Tile;
     };
     const u16 *kptr[G::LOADS / NW];
-    stream_pointers<D, NW>(kc, sr.c0, cache_stride, kptr);
-    const long long tile_elems = (long long)kBf16Tile * cache_stride;
+    stream_pointers<D, NW>(kc, sr.first, cache_stride, kptr);
+    const long long tile_elems = sr.step * cache_stride;
     auto issue = [&](int t) {
         const int valid = tile_valid(t);
         unsigned char *buf = smem + (t % NBUF) * BUF_BYTES;
         if (valid == kBf16Tile) {
             issue_tile_stream<D, NW, false>(kptr, tile_elems, 0, t, buf);
         } else {
-            const long long base = sr.c0 + (long long)t * kBf16Tile;
+            const long long base = sr.first + t * sr.step;
             issue_tile<D, NW, false>(kc, kc, cache_stride, buf, [&](int r) -> long long { return base + (r < valid ? r : valid - 1); });
         }
     };
@@ -475,6 +597,8 @@ __global__ __launch_bounds__(NW * 64) void colsum_bf16_kernel(const KernelArgs a
 
     bf16x8_t qf[KS];
     load_q_frag<D>(a, static_cast<const u16 *>(a.q), h, row0 + l32, qf);
+    FragAddr fa = frag_addr<D>(lane);
+    const unsigned smem_addr = lds_addr(smem);
 
     // per-register row statistics: register v is query row row0 + 8*(v/4) + 4*lg + v%4
     float lse2[16];
@@ -485,14 +609,25 @@ __global__ __launch_bounds__(NW * 64) void colsum_bf16_kernel(const KernelArgs a
     }
 
     // The cross-wavefront sum of tile t is finished after the barrier of tile t+1 (the `red`
-    // buffer alternates), so the loop needs one barrier per tile.
+    // buffer alternates), so the loop needs one barrier per tile.  `red` is read and written with
+    // inline assembly for the same reason as the tiles.
+    const unsigned red_addr = lds_addr(red);
     auto finish = [&](int t) {
         const int valid = tile_valid(t);
         if (threadIdx.x < kBf16Tile && (int)threadIdx.x < valid) {
+            const unsigned src = red_addr + ((t & 1) * NW * kBf16Tile + threadIdx.x) * 4;
+            float part[NW];
+            static_for<NW>([&](auto W) {
+                constexpr int w = decltype(W)::value;
+                part[w] = lds_read_f32<w * kBf16Tile * 4>(src);
+            });
             float acc = 0.f;
-#pragma unroll
-            for (int w = 0; w < NW; ++w) acc += red[t & 1][w][threadIdx.x];
-            a.alpha[(long long)h * a.L + sr.c0 + (long long)t * kBf16Tile + threadIdx.x] = acc * a.inv_rows;
+            static_for<NW>([&](auto W) {
+                constexpr int w = decltype(W)::value;
+                lds_wait<NW - 1 - w>(part[w]);
+                acc += part[w];
+            });
+            a.alpha[(long long)h * a.L + sr.first + t * sr.step + threadIdx.x] = acc * a.inv_rows;
         }
     };
 
@@ -501,28 +636,27 @@ __global__ __launch_bounds__(NW * 64) void colsum_bf16_kernel(const KernelArgs a
         else tile_barrier<0>();
         if (t + NBUF - 1 < ntiles) issue(t + NBUF - 1);
         if (t > 0) finish(t - 1);
-        const unsigned char *kbuf = smem + (t % NBUF) * BUF_BYTES;
+        const unsigned tile_addr = smem_addr + (t % NBUF) * BUF_BYTES;
+        asm volatile("" : "+v"(fa.k));
+        float col[2] = {0.f, 0.f};
+        if (wave_active) {
+            // sc[kt][v] = score of query row row0 + 8*(v/4) + 4*lg + v%4 against key kt*32 + l32
+            f32x16_t sc[2];
+            qk_tile<D, false>(tile_addr + fa.k, qf, sc);
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt) {
-            float col = 0.f;
-            if (wave_active) {
-                f32x16_t sc;
+            for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
-                for (int v = 0; v < 16; ++v) sc[v] = 0.f;
-                bf16x8_t kf[KS];
-#pragma unroll
-                for (int s = 0; s < KS; ++s) kf[s] = read_k_frag<D>(kbuf, kt * 32 + l32, s, lg);
-#pragma unroll
-                for (int s = 0; s < KS; ++s) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[s], kf[s], sc, 0, 0, 0);
-#pragma unroll
-                for (int v = 0; v < 16; ++v) col += __builtin_amdgcn_exp2f(fmaf(sc[v], a.scale_log2, -lse2[v]));
-                col += __shfl_xor(col, 32);
+                for (int v = 0; v < 16; ++v) col[kt] += __builtin_amdgcn_exp2f(fmaf(sc[kt][v], a.scale_log2, -lse2[v]));
+                col[kt] += __shfl_xor(col[kt], 32);
             }
-            if (lg == 0) red[t & 1][wave][kt * 32 + l32] = col;
+        }
+        if (lg == 0) {
+            const unsigned dst = red_addr + (((t & 1) * NW + wave) * kBf16Tile + l32) * 4;
+            asm volatile("ds_write_b32 %0, %1\n\tds_write_b32 %0, %2 offset:128" ::"v"(dst), "v"(col[0]), "v"(col[1]) : "memory");
         }
     }
     if (ntiles > 0) {
-        __syncthreads();
+        tile_barrier<0>();
         finish(ntiles - 1);
     }
 }

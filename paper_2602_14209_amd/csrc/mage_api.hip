@@ -56,6 +56,7 @@ KernelArgs base_args(const mage_shape &s, const SplitPlan &p)
     a.kps = p.kps;
     a.n_split = p.n_split;
     a.blk_split = p.blk_split;
+    a.n_cyc = p.n_cyc;
     a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)s.d));
     a.inv_rows = (float)(1.0 / (double)p.R);
     return a;
@@ -126,6 +127,7 @@ int run_sparse_bf16(const mage_shape *shape, bool compact, int n_seq, const void
     SplitPlan p{};
     plan_rows(*shape, p);
     p.n_split = 1;
+    p.n_cyc = 1;
     KernelArgs a = base_args(*shape, p);
     a.q = q;
     a.kc = k_cache;

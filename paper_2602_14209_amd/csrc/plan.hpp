@@ -28,6 +28,7 @@ struct SplitPlan {
     int tile;         // keys per tile
     int kps;          // cache keys per split (multiple of tile)
     int n_split;      // splits along the key axis, including a block-only split if any
+    int n_cyc;        // splits that own cache keys (the first n_cyc)
     int blk_split;    // split that also attends the in-block keys
 };
 
@@ -66,6 +67,7 @@ inline SplitPlan plan_dense(const mage_shape &s, int target_workgroups = kTarget
     p.n_split = (int)((tiles + tps - 1) / tps);
     p.kps = (int)(tps * p.tile);
     p.blk_split = p.n_split - 1;
+    p.n_cyc = p.n_split;
     return p;
 }
 
@@ -80,6 +82,7 @@ inline SplitPlan plan_sparse(const mage_shape &s)
     const int64_t tps = (tiles + max_splits - 1) / max_splits;
     const int n_cache = (int)((tiles + tps - 1) / tps);
     p.kps = (int)(tps * p.tile);
+    p.n_cyc = n_cache;
     if (s.k >= p.tile) {
         p.n_split = n_cache + 1;
         p.blk_split = n_cache;
@@ -146,6 +149,7 @@ struct KernelArgs {
     long long L;             // rows in the cache
     long long nc;            // cache keys attended: L (dense) or k (gather)
     int kps, n_split, blk_split, n_blk;
+    int n_cyc;               // MFMA path: split s < n_cyc owns the cache tiles s, s + n_cyc, s + 2*n_cyc, ...
     // batched launches (grid z = sequence): element strides between consecutive sequences, 0 when not batched
     long long seq_q, seq_kv, seq_idx, seq_blk, seq_out, seq_lse;
     float scale_log2;        // log2(e) / sqrt(d)
