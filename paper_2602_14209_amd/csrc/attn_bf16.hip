@@ -255,6 +255,27 @@ __device__ __forceinline__ void qk_tile(unsigned ka, const bf16x8_t (&qf)[D / 16
     });
 }
 
+// The same for one 32-key half of a tile (key row l32 of the half that `ka` points at).
+template <int D, bool KEYS_AS_A>
+__device__ __forceinline__ void qk_half(unsigned ka, const bf16x8_t (&qf)[D / 16], f32x16_t &sc)
+{
+    constexpr int KS = D / 16;
+    u32x4_t k0[KS];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) sc[v] = 0.f;
+    static_for<KS>([&](auto S) {
+        constexpr int ks = decltype(S)::value;
+        k0[ks] = lds_read_b128<0>(ka ^ (unsigned)(ks << 5));
+    });
+    static_for<KS>([&](auto S) {
+        constexpr int ks = decltype(S)::value;
+        lds_wait<KS - 1 - ks>(k0[ks]);
+        const bf16x8_t kf = __builtin_bit_cast(bf16x8_t, k0[ks]);
+        sc = KEYS_AS_A ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sc, 0, 0, 0)
+                       : __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[ks], kf, sc, 0, 0, 0);
+    });
+}
+
 // V^T fragments of key group g (16 keys: 16*g + 4*lg + {0..3, 8..11}) for all O^T tiles: lane
 // holds channel dt*32 + (lane & 31).
 template <int D, int GRP>
@@ -308,32 +329,57 @@ __device__ __forceinline__ SplitRange split_range(const KernelArgs &a, int s)
     return r;
 }
 
-template <int D, int NW, int MODE, bool GATHER>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) void attn_bf16_kernel(const KernelArgs a)
+// Attention / row-statistics pass.  A workgroup is 8 wavefronts: 4 row groups (32 query rows
+// each) x 2 key halves of every 64-key tile, one workgroup per CU with a ring of tile buffers that
+// fills the LDS, so that four to seven tiles are in flight while one is consumed.  The two
+// halves keep separate online-softmax states, merged through LDS after the last tile.
+constexpr int kAttnWaves = 8;
+constexpr int kAttnRows = 128;   // query rows per workgroup (4 row groups of 32)
+
+template <int D, int MODE>
+struct AttnGeom {
+    static constexpr bool WITH_V = (MODE == MODE_ATTN);
+    static constexpr int BUF_BYTES = TileGeom<D>::MAT_BYTES * (WITH_V ? 2 : 1);
+    // LDS tile buffers = prefetch distance + 1.  Attention is register-bound to one workgroup per
+    // CU and hides its arithmetic best with three tiles in flight; the K-only pass is lighter on
+    // registers and runs two workgroups per CU with two tiles in flight each.
+    static constexpr int NBUF = WITH_V ? 4 : 3;
+    static constexpr int LPT = (TileGeom<D>::LOADS / kAttnWaves) * (WITH_V ? 2 : 1);            // loads one wavefront issues per tile
+    static constexpr int MAX_WAVES_PER_SIMD = WITH_V ? 2 : 4;
+};
+
+template <int D, int MODE, bool GATHER>
+__global__ __launch_bounds__(kAttnWaves * 64) __attribute__((amdgpu_waves_per_eu(2, AttnGeom<D, MODE>::MAX_WAVES_PER_SIMD)))
+void attn_bf16_kernel(const KernelArgs a)
 {
     using G = TileGeom<D>;
-    constexpr bool WITH_V = (MODE == MODE_ATTN);
-    constexpr int NBUF = WITH_V ? 2 : 3;                            // LDS tile buffers = prefetch distance + 1
-    constexpr int LPT = (G::LOADS / NW) * (WITH_V ? 2 : 1);         // loads one wavefront issues per tile
+    using AG = AttnGeom<D, MODE>;
+    constexpr int NW = kAttnWaves;
+    constexpr bool WITH_V = AG::WITH_V;
+    constexpr int NBUF = AG::NBUF, LPT = AG::LPT, BUF_BYTES = AG::BUF_BYTES;
     constexpr int KS = D / 16;     // MFMA k-steps over the head dimension
     constexpr int DT = D / 32;     // 32-row tiles of O^T
-    constexpr int BUF_BYTES = G::MAT_BYTES * (WITH_V ? 2 : 1);
+    constexpr int HALF = 32 * G::ROW_BYTES;
     constexpr int OST = D + 4;     // floats per staged output row
-    constexpr int STAGE_BYTES = WITH_V ? 2 * 32 * OST * 4 : 0;
-    static_assert(NBUF * BUF_BYTES >= STAGE_BYTES, "output staging must fit in the tile buffers");
+    constexpr int MERGE_FLOATS = 4 * DT * 16 * 64;      // O^T accumulators of the four upper-half wavefronts
+    constexpr int MERGE_BYTES = ((WITH_V ? MERGE_FLOATS : 0) + 4 * 4 * 64) * 4;
+    constexpr int SMEM_BYTES = NBUF * BUF_BYTES > MERGE_BYTES ? NBUF * BUF_BYTES : MERGE_BYTES;
+    static_assert(SMEM_BYTES >= 2 * 32 * OST * 4, "output staging must fit in the tile buffers");
+    static_assert((NBUF - 2) * LPT < 64, "outstanding loads must fit the counter");
 
-    // tile buffers; after the key loop the same memory stages the output transposition
-    __shared__ __attribute__((aligned(1024))) unsigned char smem[NBUF * BUF_BYTES];
+    // tile buffers; after the key loop the same memory carries the merge and the output transposition
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[SMEM_BYTES];
 
     // key splits vary fastest over the grid: consecutive workgroups (dealt round-robin to the XCDs)
-    // stream different key ranges of the same head, so every XCD touches every HBM channel
+    // stream neighbouring tiles of the same head, so every XCD touches every HBM channel.
     // A batched launch (independent sequences, unsplit keys) uses the x axis for the sequence.
     const bool batched = a.seq_kv != 0;
     const long long z = batched ? blockIdx.x : 0;
     const int split = batched ? 0 : blockIdx.x, h = blockIdx.y, rg = blockIdx.z;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, lg = lane >> 5;
-    const int row0 = (rg * NW + wave) * 32;           // first row of this wavefront's M tile
+    const int rgw = wave & 3, kh = wave >> 2;            // row group and key half of this wavefront
+    const int row0 = rg * kAttnRows + rgw * 32;              // first row of this wavefront's M tile
     const int row = row0 + l32;
     const bool wave_active = row0 < a.R;
 
@@ -385,6 +431,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     bf16x8_t qf[KS];
     load_q_frag<D>(a, static_cast<const u16 *>(a.q) + z * a.seq_q, h, row, qf);
     FragAddr fa = frag_addr<D>(lane);
+    fa.k += kh * HALF;                 // this wavefront's half of every tile
+    fa.v[0] += kh * HALF;
+    fa.v[1] += kh * HALF;
     const unsigned smem_addr = lds_addr(smem);
 
     f32x16_t o[WITH_V ? DT : 1];
@@ -403,7 +452,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
         if (t + NBUF - 1 < ntiles) issue(t + NBUF - 1);
         const int valid = tile_valid(t);
         const unsigned tile_addr = smem_addr + (t % NBUF) * BUF_BYTES;
-        // keep the per-read address arithmetic inside the loop: hoisted, it would pin 48 registers
+        // keep the per-read address arithmetic inside the loop: hoisted, it would pin dozens of registers
         asm volatile("" : "+v"(fa.k), "+v"(fa.v[0]), "+v"(fa.v[1]));
         if (WITH_V && t == sr.cache_tiles) {   // first in-block tile: freeze the prefix statistics
             m_pre = m_run;
@@ -415,37 +464,34 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 #else
         if (wave_active) {
 #endif
-            // S^T tile: sc[kt][v] = score of query row l32 against key kt*32 + 8*(v/4) + 4*lg + v%4
-            f32x16_t sc[2];
-            qk_tile<D, true>(tile_addr + fa.k, qf, sc);
+            // S^T: sc[v] = score of query row l32 against key kh*32 + 8*(v/4) + 4*lg + v%4
+            f32x16_t sc;
+            qk_half<D, true>(tile_addr + fa.k, qf, sc);
             // the first V^T fragments travel while the softmax runs
             const unsigned va[2] = {tile_addr + G::MAT_BYTES + fa.v[0], tile_addr + G::MAT_BYTES + fa.v[1]};
             u32x2_t vf[2][WITH_V ? DT : 1][2];
             if constexpr (WITH_V) issue_vt_group<D, 0>(va, vf[0]);
             if (valid < kBf16Tile) {           // uniform: only the last tile of a slice has padding keys
 #pragma unroll
-                for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v)
-                        if (kt * 32 + 8 * (v >> 2) + 4 * lg + (v & 3) >= valid) sc[kt][v] = -INFINITY;
+                for (int v = 0; v < 16; ++v)
+                    if (kh * 32 + 8 * (v >> 2) + 4 * lg + (v & 3) >= valid) sc[v] = -INFINITY;
             }
-            float mx = fmaxf(sc[0][0], sc[1][0]);
+            float mx = sc[0];
 #pragma unroll
-            for (int v = 1; v < 16; ++v) mx = fmaxf(mx, fmaxf(sc[0][v], sc[1][v]));
+            for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sc[v]);
             mx = fmaxf(mx, __shfl_xor(mx, 32)) * a.scale_log2;
-            const float m_new = fmaxf(m_run, mx);
+            // finite floor: a half tile of padding keys must not turn the running maximum into -inf - -inf
+            const float m_new = fmaxf(fmaxf(m_run, mx), -3.0e38f);
             const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
             const bool grew = m_new > m_run;
             m_run = m_new;
             float psum = 0.f;
 #pragma unroll
-            for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const float p = __builtin_amdgcn_exp2f(fmaf(sc[kt][v], a.scale_log2, -m_new));
-                    sc[kt][v] = p;
-                    psum += p;
-                }
+            for (int v = 0; v < 16; ++v) {
+                const float p = __builtin_amdgcn_exp2f(fmaf(sc[v], a.scale_log2, -m_new));
+                sc[v] = p;
+                psum += p;
+            }
             l_run = l_run * corr + psum;
 
             if constexpr (WITH_V) {
@@ -455,18 +501,18 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 #pragma unroll
                         for (int v = 0; v < 16; ++v) o[dt][v] *= corr;
                 }
-                // key group g = 2*kt + m2: P^T fragment from sc[kt][8*m2 ..], V^T fragments of
-                // group g+1 requested before group g is consumed
-                static_for<4>([&](auto GI) {
+                // key group g (16 keys): P^T fragment from sc[8*g ..]; the V^T fragments of group 1
+                // are requested before group 0 is consumed
+                static_for<2>([&](auto GI) {
                     constexpr int g = decltype(GI)::value;
                     bf16x8_t pf;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) pf[e] = (__bf16)sc[g >> 1][8 * (g & 1) + e];
-                    if constexpr (g < 3) issue_vt_group<D, g + 1>(va, vf[(g + 1) & 1]);
+                    for (int e = 0; e < 8; ++e) pf[e] = (__bf16)sc[8 * g + e];
+                    if constexpr (g == 0) issue_vt_group<D, 1>(va, vf[1]);
                     static_for<DT>([&](auto T) {
                         constexpr int dt = decltype(T)::value;
-                        lds_wait<(g < 3 ? 2 * DT : 0) + 2 * (DT - 1 - dt)>(vf[g & 1][dt][0], vf[g & 1][dt][1]);
-                        const u32x4_t both = {vf[g & 1][dt][0][0], vf[g & 1][dt][0][1], vf[g & 1][dt][1][0], vf[g & 1][dt][1][1]};
+                        lds_wait<(g == 0 ? 2 * DT : 0) + 2 * (DT - 1 - dt)>(vf[g][dt][0], vf[g][dt][1]);
+                        const u32x4_t both = {vf[g][dt][0][0], vf[g][dt][0][1], vf[g][dt][1][0], vf[g][dt][1][1]};
                         o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, both), pf, o[dt], 0, 0, 0);
                     });
                 });
@@ -474,23 +520,67 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
         }
     }
 
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    float l_tot = l_run + __shfl_xor(l_run, 32);
+    float lp_tot = l_pre + __shfl_xor(l_pre, 32);
+    if (sr.blk_tiles == 0) {
+        m_pre = m_run;
+        lp_tot = l_tot;
+    }
     MAGE_PROBE_AT(2);
-    if (WITH_V && a.stat_m != nullptr) {
-        if (sr.blk_tiles == 0) {
-            m_pre = m_run;
-            l_pre = l_run;
+
+    // Merge the upper key half into the lower one.  O^T travels as 16-byte lane-contiguous pieces.
+    float *mrg = reinterpret_cast<float *>(smem);
+    float *mrg_stat = mrg + (WITH_V ? MERGE_FLOATS : 0) + rgw * 4 * 64 + lane;
+    __syncthreads();                    // every wavefront is done reading the last tile
+    if (kh == 1 && wave_active) {
+        if constexpr (WITH_V) {
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int v4 = 0; v4 < 4; ++v4) {
+                    const f32x4_t val = {o[dt][4 * v4], o[dt][4 * v4 + 1], o[dt][4 * v4 + 2], o[dt][4 * v4 + 3]};
+                    *reinterpret_cast<f32x4_t *>(mrg + (((rgw * DT + dt) * 4 + v4) * 64 + lane) * 4) = val;
+                }
         }
-        const float lp = l_pre + __shfl_xor(l_pre, 32);
-        if (wave_active && row < a.R && lg == 0) {
+        mrg_stat[0] = m_run;
+        mrg_stat[64] = l_tot;
+        mrg_stat[128] = m_pre;
+        mrg_stat[192] = lp_tot;
+    }
+    __syncthreads();
+    if (kh == 0 && wave_active) {
+        const float m_b = mrg_stat[0], l_b = mrg_stat[64], mp_b = mrg_stat[128], lp_b = mrg_stat[192];
+        const float m = fmaxf(m_run, m_b);
+        const float fa_ = m_run == m ? 1.f : __builtin_amdgcn_exp2f(m_run - m);
+        const float fb_ = m_b == m ? 1.f : __builtin_amdgcn_exp2f(m_b - m);
+        l_tot = l_tot * fa_ + l_b * fb_;
+        m_run = m;
+        const float mp = fmaxf(m_pre, mp_b);
+        lp_tot = lp_tot * (m_pre == mp ? 1.f : __builtin_amdgcn_exp2f(m_pre - mp)) + lp_b * (mp_b == mp ? 1.f : __builtin_amdgcn_exp2f(mp_b - mp));
+        m_pre = mp;
+        if constexpr (WITH_V) {
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int v4 = 0; v4 < 4; ++v4) {
+                    const f32x4_t ob = *reinterpret_cast<const f32x4_t *>(mrg + (((rgw * DT + dt) * 4 + v4) * 64 + lane) * 4);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[dt][4 * v4 + e] = o[dt][4 * v4 + e] * fa_ + ob[e] * fb_;
+                }
+        }
+    }
+    const bool owner = kh == 0 && wave_active;
+
+    if (WITH_V && a.stat_m != nullptr) {
+        if (owner && row < a.R && lg == 0) {
             const long long pi = ((long long)h * a.n_split + split) * a.rpad + row;
             a.stat_m[pi] = m_pre;
-            a.stat_l[pi] = lp;
+            a.stat_l[pi] = lp_tot;
         }
     }
 
     if (MODE == MODE_STATS) {
-        if (wave_active && row < a.R && lg == 0) {
+        if (owner && row < a.R && lg == 0) {
             const long long pi = ((long long)h * a.n_split + split) * a.rpad + row;
             a.part_m[pi] = m_run;
             a.part_l[pi] = l_tot;
@@ -505,10 +595,10 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     constexpr int RPS = 64 / LPR;       // rows per store instruction
     const bool direct = a.n_split == 1;
     const float inv = direct ? 1.f / l_tot : 1.f;
-    float *stage = reinterpret_cast<float *>(smem) + (wave & 1) * 32 * OST;
-    __syncthreads();                    // every wavefront is done reading the last tile
-    for (int round = 0; round < NW / 2; ++round) {
-        if ((wave >> 1) == round && wave_active) {
+    float *stage = reinterpret_cast<float *>(smem) + (rgw & 1) * 32 * OST;
+    __syncthreads();                    // the merge area has been read
+    for (int round = 0; round < 2; ++round) {
+        if ((rgw >> 1) == round && owner) {
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -537,7 +627,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     }
     MAGE_PROBE_AT(3);
     MAGE_PROBE_FLUSH();
-    if (!wave_active || row >= a.R || lg != 0) return;
+    if (!owner || row >= a.R || lg != 0) return;
     if (direct) {
         if (a.lse_out) {
             const int gl = row / a.B, qi = row - gl * a.B;
@@ -562,6 +652,8 @@ __global__ __launch_bounds__(NW * 64) void colsum_bf16_kernel(const KernelArgs a
     constexpr int LPT = G::LOADS / NW;                              // loads one wavefront issues per tile
     __shared__ __attribute__((aligned(1024))) unsigned char smem[NBUF * BUF_BYTES];
     __shared__ float red[2][NW][kBf16Tile];
+    __shared__ float ring[kColsumTiles][kBf16Tile];
+    static_assert(kColsumTiles % NW == 0, "flush deals the ring slots to the wavefronts");
 
     const int split = blockIdx.x, h = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -574,8 +666,9 @@ __global__ __launch_bounds__(NW * 64) void colsum_bf16_kernel(const KernelArgs a
     const long long cache_stride = (long long)a.Hkv * D;
     const u16 *kc = static_cast<const u16 *>(a.kc) + (long long)h * D;
 
+    auto tile_key = [&](int t) -> long long { return sr.first + t * sr.step; };
     auto tile_valid = [&](int t) -> int {
-        const long long left = sr.nc - (sr.first + t * sr.step);
+        const long long left = sr.nc - tile_key(t);
         return left < kBf16Tile ? (int)left : kBf16Tile;
     };
     const u16 *kptr[G::LOADS / NW];
@@ -587,7 +680,7 @@ __global__ __launch_bounds__(NW * 64) void colsum_bf16_kernel(const KernelArgs a
         if (valid == kBf16Tile) {
             issue_tile_stream<D, NW, false>(kptr, tile_elems, 0, t, buf);
         } else {
-            const long long base = sr.first + t * sr.step;
+            const long long base = tile_key(t);
             issue_tile<D, NW, false>(kc, kc, cache_stride, buf, [&](int r) -> long long { return base + (r < valid ? r : valid - 1); });
         }
     };
@@ -609,12 +702,13 @@ __global__ __launch_bounds__(NW * 64) void colsum_bf16_kernel(const KernelArgs a
     }
 
     // The cross-wavefront sum of tile t is finished after the barrier of tile t+1 (the `red`
-    // buffer alternates), so the loop needs one barrier per tile.  `red` is read and written with
-    // inline assembly for the same reason as the tiles.
-    const unsigned red_addr = lds_addr(red);
+    // buffer alternates), so the loop needs one barrier per tile.  Finished sums wait in `ring` and
+    // leave together: a global store inside the loop would sit in the same counter as the tile
+    // loads and hold up the wavefront that issued it at every barrier.  `red` and `ring` are read
+    // and written with inline assembly for the same reason as the tiles.
+    const unsigned red_addr = lds_addr(red), ring_addr = lds_addr(ring);
     auto finish = [&](int t) {
-        const int valid = tile_valid(t);
-        if (threadIdx.x < kBf16Tile && (int)threadIdx.x < valid) {
+        if (threadIdx.x < kBf16Tile) {
             const unsigned src = red_addr + ((t & 1) * NW * kBf16Tile + threadIdx.x) * 4;
             float part[NW];
             static_for<NW>([&](auto W) {
@@ -627,15 +721,47 @@ __global__ __launch_bounds__(NW * 64) void colsum_bf16_kernel(const KernelArgs a
                 lds_wait<NW - 1 - w>(part[w]);
                 acc += part[w];
             });
-            a.alpha[(long long)h * a.L + sr.first + t * sr.step + threadIdx.x] = acc * a.inv_rows;
+            acc *= a.inv_rows;
+            const unsigned dst = ring_addr + ((t % kColsumTiles) * kBf16Tile + threadIdx.x) * 4;
+            asm volatile("ds_write_b32 %0, %1" ::"v"(dst), "v"(acc) : "memory");
         }
     };
+    // write out the sums of tiles [t0, t0 + n), n <= kColsumTiles; the caller has put a barrier
+    // between the last finish() and this
+    auto flush = [&](int t0, int n) {
+#pragma unroll
+        for (int j = 0; j < kColsumTiles / NW; ++j) {
+            const int slot = j * NW + wave;
+            const int t = t0 + slot;
+            if (slot < n) {                                  // uniform per wavefront
+                const bool live = lane < tile_valid(t);
+                float v = 0.f;
+                if (live) {
+                    v = lds_read_f32<0>(ring_addr + ((t % kColsumTiles) * kBf16Tile + lane) * 4);
+                    lds_wait<0>(v);
+                    a.alpha[(long long)h * a.L + tile_key(t) + lane] = v;
+                }
+                if (a.gmax != nullptr) {                     // maxima of 16 consecutive keys, for the top-k filter
+                    float g = v;
+#pragma unroll
+                    for (int d = 1; d < kGroupKeys; d <<= 1) g = fmaxf(g, __shfl_xor(g, d));
+                    if (live && (lane & (kGroupKeys - 1)) == 0)
+                        a.gmax[(long long)h * ((a.L + kGroupKeys - 1) / kGroupKeys) + (tile_key(t) + lane) / kGroupKeys] = g;
+                }
+            }
+        }
+    };
+    auto lds_barrier = [] {
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __syncthreads();
+    };
 
+    int flushed = 0;          // tiles [0, flushed) have left the ring
     for (int t = 0; t < ntiles; ++t) {
         if (t + NBUF - 2 < ntiles) tile_barrier<(NBUF - 2) * LPT>();
         else tile_barrier<0>();
         if (t + NBUF - 1 < ntiles) issue(t + NBUF - 1);
-        if (t > 0) finish(t - 1);
+        if (t > flushed) finish(t - 1);
         const unsigned tile_addr = smem_addr + (t % NBUF) * BUF_BYTES;
         asm volatile("" : "+v"(fa.k));
         float col[2] = {0.f, 0.f};
@@ -654,19 +780,22 @@ __global__ __launch_bounds__(NW * 64) void colsum_bf16_kernel(const KernelArgs a
             const unsigned dst = red_addr + (((t & 1) * NW + wave) * kBf16Tile + l32) * 4;
             asm volatile("ds_write_b32 %0, %1\n\tds_write_b32 %0, %2 offset:128" ::"v"(dst), "v"(col[0]), "v"(col[1]) : "memory");
         }
-    }
-    if (ntiles > 0) {
-        tile_barrier<0>();
-        finish(ntiles - 1);
+        if (t - flushed == kColsumTiles - 1 || t == ntiles - 1) {   // ring full, or done: drain it
+            lds_barrier();
+            finish(t);
+            lds_barrier();
+            flush(flushed, t + 1 - flushed);
+            flushed = t + 1;
+        }
     }
 }
 
 // ------------------------------------------------------------------------------ launchers
-template <int D, int NW, int MODE, bool GATHER>
-static hipError_t launch_attn(const KernelArgs &a, int row_groups, hipStream_t stream)
+template <int D, int MODE, bool GATHER>
+static hipError_t launch_attn(const KernelArgs &a, int row_groups, int grid_x, hipStream_t stream)
 {
-    dim3 grid(a.n_split, a.Hkv, row_groups), block(NW * 64);
-    hipLaunchKernelGGL((attn_bf16_kernel<D, NW, MODE, GATHER>), grid, block, 0, stream, a);
+    dim3 grid(grid_x, a.Hkv, row_groups), block(kAttnWaves * 64);
+    hipLaunchKernelGGL((attn_bf16_kernel<D, MODE, GATHER>), grid, block, 0, stream, a);
     return hipGetLastError();
 }
 
@@ -678,35 +807,27 @@ static hipError_t launch_colsum(const KernelArgs &a, hipStream_t stream)
     return hipGetLastError();
 }
 
-hipError_t bf16_attn(const KernelArgs &a, int d, int waves, int row_groups, bool gather, hipStream_t stream)
+hipError_t bf16_attn(const KernelArgs &a, int d, int row_groups, bool gather, hipStream_t stream)
 {
-    if (d == 128 && waves == 4) return gather ? launch_attn<128, 4, MODE_ATTN, true>(a, row_groups, stream) : launch_attn<128, 4, MODE_ATTN, false>(a, row_groups, stream);
-    if (d == 128 && waves == 8) return gather ? launch_attn<128, 8, MODE_ATTN, true>(a, row_groups, stream) : launch_attn<128, 8, MODE_ATTN, false>(a, row_groups, stream);
-    if (d == 64 && waves == 4) return gather ? launch_attn<64, 4, MODE_ATTN, true>(a, row_groups, stream) : launch_attn<64, 4, MODE_ATTN, false>(a, row_groups, stream);
-    if (d == 64 && waves == 8) return gather ? launch_attn<64, 8, MODE_ATTN, true>(a, row_groups, stream) : launch_attn<64, 8, MODE_ATTN, false>(a, row_groups, stream);
+    if (d == 128) return gather ? launch_attn<128, MODE_ATTN, true>(a, row_groups, a.n_split, stream) : launch_attn<128, MODE_ATTN, false>(a, row_groups, a.n_split, stream);
+    if (d == 64) return gather ? launch_attn<64, MODE_ATTN, true>(a, row_groups, a.n_split, stream) : launch_attn<64, MODE_ATTN, false>(a, row_groups, a.n_split, stream);
     return hipErrorInvalidValue;
 }
 
 // Batched sparse step: n_seq independent sequences, one workgroup per (sequence, KV head, row
 // group) walks all k + B keys of its head, so every selected row is fetched by exactly one
 // workgroup and nothing is merged across workgroups.
-hipError_t bf16_attn_batched(const KernelArgs &a, int d, int waves, int row_groups, int n_seq, hipStream_t stream)
+hipError_t bf16_attn_batched(const KernelArgs &a, int d, int row_groups, int n_seq, hipStream_t stream)
 {
-    dim3 grid(n_seq, a.Hkv, row_groups), block(waves * 64);
-    if (d == 128 && waves == 4) hipLaunchKernelGGL((attn_bf16_kernel<128, 4, MODE_ATTN, true>), grid, block, 0, stream, a);
-    else if (d == 128 && waves == 8) hipLaunchKernelGGL((attn_bf16_kernel<128, 8, MODE_ATTN, true>), grid, block, 0, stream, a);
-    else if (d == 64 && waves == 4) hipLaunchKernelGGL((attn_bf16_kernel<64, 4, MODE_ATTN, true>), grid, block, 0, stream, a);
-    else if (d == 64 && waves == 8) hipLaunchKernelGGL((attn_bf16_kernel<64, 8, MODE_ATTN, true>), grid, block, 0, stream, a);
-    else return hipErrorInvalidValue;
-    return hipGetLastError();
+    if (d == 128) return launch_attn<128, MODE_ATTN, true>(a, row_groups, n_seq, stream);
+    if (d == 64) return launch_attn<64, MODE_ATTN, true>(a, row_groups, n_seq, stream);
+    return hipErrorInvalidValue;
 }
 
-hipError_t bf16_stats(const KernelArgs &a, int d, int waves, int row_groups, hipStream_t stream)
+hipError_t bf16_stats(const KernelArgs &a, int d, int row_groups, hipStream_t stream)
 {
-    if (d == 128 && waves == 4) return launch_attn<128, 4, MODE_STATS, false>(a, row_groups, stream);
-    if (d == 128 && waves == 8) return launch_attn<128, 8, MODE_STATS, false>(a, row_groups, stream);
-    if (d == 64 && waves == 4) return launch_attn<64, 4, MODE_STATS, false>(a, row_groups, stream);
-    if (d == 64 && waves == 8) return launch_attn<64, 8, MODE_STATS, false>(a, row_groups, stream);
+    if (d == 128) return launch_attn<128, MODE_STATS, false>(a, row_groups, a.n_split, stream);
+    if (d == 64) return launch_attn<64, MODE_STATS, false>(a, row_groups, a.n_split, stream);
     return hipErrorInvalidValue;
 }
 

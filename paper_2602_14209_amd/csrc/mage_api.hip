@@ -7,9 +7,9 @@
 #include "plan.hpp"
 
 namespace mage {
-hipError_t bf16_attn(const KernelArgs &a, int d, int waves, int row_groups, bool gather, hipStream_t stream);
-hipError_t bf16_attn_batched(const KernelArgs &a, int d, int waves, int row_groups, int n_seq, hipStream_t stream);
-hipError_t bf16_stats(const KernelArgs &a, int d, int waves, int row_groups, hipStream_t stream);
+hipError_t bf16_attn(const KernelArgs &a, int d, int row_groups, bool gather, hipStream_t stream);
+hipError_t bf16_attn_batched(const KernelArgs &a, int d, int row_groups, int n_seq, hipStream_t stream);
+hipError_t bf16_stats(const KernelArgs &a, int d, int row_groups, hipStream_t stream);
 hipError_t bf16_colsum(const KernelArgs &a, int d, int waves, hipStream_t stream);
 hipError_t bf16_sparse(const KernelArgs &a, int d, bool compact, int n_seq, hipStream_t stream);
 hipError_t launch_compact(const void *k_src, const void *v_src, const int32_t *idx, void *k_dst, void *v_dst,
@@ -19,7 +19,7 @@ hipError_t f32_stats(const KernelArgs &a, int d, int row_groups, hipStream_t str
 hipError_t f32_colsum(const KernelArgs &a, int d, hipStream_t stream);
 hipError_t launch_combine(const KernelArgs &a, int d, hipStream_t stream);
 hipError_t launch_lse(const KernelArgs &a, float *lse2_out, hipStream_t stream);
-hipError_t launch_topk(const float *alpha, int Hkv, long long L, int k, int32_t *idx_out, hipStream_t stream);
+hipError_t launch_topk(const float *alpha, const float *group_max, int Hkv, long long L, int k, int32_t *idx_out, hipStream_t stream);
 }  // namespace mage
 
 using namespace mage;
@@ -103,7 +103,7 @@ int run_attention(const mage_shape *shape, const SplitPlan &p, bool gather,
     if (p.n_split > 1) carve_partials(*shape, p, workspace, a);
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    hipError_t e = shape->dtype == MAGE_BF16 ? bf16_attn(a, shape->d, p.waves, p.row_groups, gather, stream)
+    hipError_t e = shape->dtype == MAGE_BF16 ? bf16_attn(a, shape->d, p.row_groups, gather, stream)
                                              : f32_attn(a, shape->d, p.row_groups, gather, stream);
     if (e != hipSuccess) return MAGE_ERR_HIP;
     if (p.n_split > 1) {
@@ -153,7 +153,7 @@ int run_sparse_bf16(const mage_shape *shape, bool compact, int n_seq, const void
         // selected row once per sequence (the latency-oriented kernel re-reads it per row tile)
         a.kps = (int)align_up((size_t)shape->k, kBf16Tile);
         a.blk_split = 0;
-        return bf16_attn_batched(a, shape->d, p.waves, p.row_groups, n_seq, stream) == hipSuccess ? MAGE_OK : MAGE_ERR_HIP;
+        return bf16_attn_batched(a, shape->d, p.row_groups, n_seq, stream) == hipSuccess ? MAGE_OK : MAGE_ERR_HIP;
     }
     if (bf16_sparse(a, shape->d, compact, n_seq, stream) != hipSuccess) return MAGE_ERR_HIP;
     return MAGE_OK;
@@ -186,7 +186,7 @@ size_t mage_workspace_bytes(const mage_shape *shape)
     size_t need = partial_bytes(*shape, dense);
     const size_t b = partial_bytes(*shape, sparse);
     if (b > need) need = b;
-    const size_t c = select_layout(*shape, plan_dense(*shape, kSelectWorkgroups)).bytes;
+    const size_t c = select_layout(*shape, plan_stats(*shape)).bytes;
     if (c > need) need = c;
     const size_t e = step1_layout(*shape, dense).bytes;
     if (e > need) need = e;
@@ -200,8 +200,8 @@ int mage_select(const mage_shape *shape, const void *q1, const void *k_cache,
     int rc = check_shape(shape, true);
     if (rc != MAGE_OK) return rc;
     if (!q1 || !k_cache || !idx_out) return MAGE_ERR_NULL;
-    const SplitPlan p = plan_dense(*shape, kSelectWorkgroups);
-    if (shape->dtype == MAGE_BF16 && p.row_groups != 1) return MAGE_ERR_UNSUPPORTED;
+    const SplitPlan p = plan_stats(*shape), pc = plan_colsum(*shape);
+    if (shape->dtype == MAGE_BF16 && p.rpad > 256) return MAGE_ERR_UNSUPPORTED;   // the column-sum pass keeps all rows of a head in one workgroup
     if (!aligned16(q1) || !aligned16(k_cache) || !aligned16(workspace) || !aligned16(alpha_out)) return MAGE_ERR_ALIGN;
     const SelectLayout lay = select_layout(*shape, p);
     if (!workspace || workspace_bytes < lay.bytes) return MAGE_ERR_WORKSPACE;
@@ -224,13 +224,18 @@ int mage_select(const mage_shape *shape, const void *q1, const void *k_cache,
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const bool bf = shape->dtype == MAGE_BF16;
-    hipError_t e = bf ? bf16_stats(a, shape->d, p.waves, p.row_groups, stream) : f32_stats(a, shape->d, p.row_groups, stream);
+    a.gmax = bf ? reinterpret_cast<float *>(w + lay.gmax) : nullptr;   // the MFMA column sums also leave group maxima for the top-k filter
+    hipError_t e = bf ? bf16_stats(a, shape->d, p.row_groups, stream) : f32_stats(a, shape->d, p.row_groups, stream);
     if (e != hipSuccess) return MAGE_ERR_HIP;
     e = launch_lse(a, lse2, stream);
     if (e != hipSuccess) return MAGE_ERR_HIP;
-    e = bf ? bf16_colsum(a, shape->d, p.waves, stream) : f32_colsum(a, shape->d, stream);
+    KernelArgs c = a;                                // the column sums have their own split of the keys
+    c.kps = pc.kps;
+    c.n_split = pc.n_split;
+    c.n_cyc = pc.n_cyc;
+    e = bf ? bf16_colsum(c, shape->d, pc.waves, stream) : f32_colsum(c, shape->d, stream);
     if (e != hipSuccess) return MAGE_ERR_HIP;
-    e = launch_topk(a.alpha, shape->Hkv, shape->L, shape->k, idx_out, stream);
+    e = launch_topk(a.alpha, a.gmax, shape->Hkv, shape->L, shape->k, idx_out, stream);
     if (e != hipSuccess) return MAGE_ERR_HIP;
     return MAGE_OK;
 }
@@ -250,8 +255,8 @@ int mage_step1(const mage_shape *shape, const void *q1, const void *k_cache, con
         return mage_select(shape, q1, k_cache, idx_out, alpha_out, workspace, workspace_bytes, hip_stream);
     }
     const SplitPlan pa = plan_dense(*shape);
-    const SplitPlan ps = plan_dense(*shape, kSelectWorkgroups);
-    if (ps.row_groups != 1) return MAGE_ERR_UNSUPPORTED;
+    const SplitPlan ps = plan_colsum(*shape);
+    if (ps.rpad > 256) return MAGE_ERR_UNSUPPORTED;
     if (!aligned16(alpha_out)) return MAGE_ERR_ALIGN;
     const Step1Layout lay = step1_layout(*shape, pa);
     if (!workspace || workspace_bytes < lay.bytes) return MAGE_ERR_WORKSPACE;
@@ -278,8 +283,9 @@ int mage_step1(const mage_shape *shape, const void *q1, const void *k_cache, con
     a.nc = shape->L;
     a.lse2 = lse2;
     a.alpha = alpha_out ? alpha_out : reinterpret_cast<float *>(w + lay.alpha);
+    a.gmax = reinterpret_cast<float *>(w + lay.gmax);
     if (bf16_colsum(a, shape->d, ps.waves, stream) != hipSuccess) return MAGE_ERR_HIP;
-    if (launch_topk(a.alpha, shape->Hkv, shape->L, shape->k, idx_out, stream) != hipSuccess) return MAGE_ERR_HIP;
+    if (launch_topk(a.alpha, a.gmax, shape->Hkv, shape->L, shape->k, idx_out, stream) != hipSuccess) return MAGE_ERR_HIP;
     return MAGE_OK;
 }
 

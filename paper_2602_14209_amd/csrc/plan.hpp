@@ -16,15 +16,17 @@ namespace mage {
 constexpr int kBf16Tile = 64;   // keys per LDS tile, MFMA path
 constexpr int kF32Tile = 32;    // keys per LDS tile, fp32 vector path
 constexpr int kF32Rows = 64;    // query rows per workgroup, fp32 vector path
-constexpr int kTargetWorkgroups = 512;   // 2 per CU on 256 CUs
-constexpr int kSelectWorkgroups = 2048;  // selection passes: 8 per CU
+constexpr int kTargetWorkgroups = 512;   // fp32 vector path: 2 per CU on 256 CUs
+constexpr int kBf16Workgroups = 256;     // MFMA path: one 8-wavefront workgroup per CU (its tile ring fills the LDS)
+constexpr int kStatsWorkgroups = 512;    // MFMA row-statistics pass: two workgroups per CU
+constexpr int kSelectWorkgroups = 2048;  // column-sum pass (and both fp32 selection passes): 8 per CU
 
 struct SplitPlan {
     int R;            // query rows sharing one KV head: G*B
     int rows_per_wg;  // rows one workgroup covers
     int row_groups;   // workgroups along the row axis
     int rpad;         // row_groups * rows_per_wg
-    int waves;        // wavefronts per workgroup
+    int waves;        // wavefronts per workgroup of the column-sum pass (one per 32 rows; MFMA path)
     int tile;         // keys per tile
     int kps;          // cache keys per split (multiple of tile)
     int n_split;      // splits along the key axis, including a block-only split if any
@@ -39,8 +41,8 @@ inline void plan_rows(const mage_shape &s, SplitPlan &p)
 {
     p.R = (s.Hq / s.Hkv) * s.B;
     if (s.dtype == MAGE_BF16) {
+        p.rows_per_wg = 128;
         p.waves = p.R > 128 ? 8 : 4;
-        p.rows_per_wg = p.waves * 32;
         p.tile = kBf16Tile;
     } else {
         p.waves = 4;
@@ -54,10 +56,11 @@ inline void plan_rows(const mage_shape &s, SplitPlan &p)
 // Dense pass over all L cache keys.  Exact attention pays a [rows x d] partial per split, so it
 // aims at two workgroups per CU; the two passes of selection leave only a (max, sum) pair per
 // row and split, so they cut the keys much finer (more workgroups in flight, even tail).
-inline SplitPlan plan_dense(const mage_shape &s, int target_workgroups = kTargetWorkgroups)
+inline SplitPlan plan_dense(const mage_shape &s, int target_workgroups = 0)
 {
     SplitPlan p{};
     plan_rows(s, p);
+    if (target_workgroups == 0) target_workgroups = s.dtype == MAGE_BF16 ? kBf16Workgroups : kTargetWorkgroups;
     const int64_t tiles = (s.L + p.tile - 1) / p.tile;
     const int64_t target = target_workgroups / ((int64_t)s.Hkv * p.row_groups) > 0
                                ? target_workgroups / ((int64_t)s.Hkv * p.row_groups) : 1;
@@ -68,6 +71,29 @@ inline SplitPlan plan_dense(const mage_shape &s, int target_workgroups = kTarget
     p.kps = (int)(tps * p.tile);
     p.blk_split = p.n_split - 1;
     p.n_cyc = p.n_split;
+    return p;
+}
+
+// Selection, first pass (row statistics).  The fp32 vector path uses one plan for both passes.
+inline SplitPlan plan_stats(const mage_shape &s)
+{
+    return plan_dense(s, s.dtype == MAGE_BF16 ? kStatsWorkgroups : kSelectWorkgroups);
+}
+
+// Selection, second pass (column sums).  The MFMA kernel parks the sums of up to kColsumTiles tiles
+// in LDS and writes them out together, so its splits are at most that long.
+constexpr int kColsumTiles = 8;
+constexpr int kGroupKeys = 16;           // keys per group maximum handed from the column sums to the top-k filter
+inline SplitPlan plan_colsum(const mage_shape &s)
+{
+    SplitPlan p = plan_dense(s, kSelectWorkgroups);
+    if (s.dtype == MAGE_BF16 && p.kps > kColsumTiles * p.tile) {
+        const int64_t tiles = (s.L + p.tile - 1) / p.tile;
+        p.kps = kColsumTiles * p.tile;
+        p.n_split = (int)((tiles + kColsumTiles - 1) / kColsumTiles);
+        p.n_cyc = p.n_split;
+        p.blk_split = p.n_split - 1;
+    }
     return p;
 }
 
@@ -100,7 +126,7 @@ inline size_t partial_bytes(const mage_shape &s, const SplitPlan &p)
 }
 
 struct SelectLayout {
-    size_t part_m, part_l, lse2, alpha, bytes;
+    size_t part_m, part_l, lse2, alpha, gmax, bytes;
 };
 
 inline SelectLayout select_layout(const mage_shape &s, const SplitPlan &p)
@@ -112,6 +138,7 @@ inline SelectLayout select_layout(const mage_shape &s, const SplitPlan &p)
     l.part_l = off; off += align_up(rows * sizeof(float), 256);
     l.lse2 = off;   off += align_up((size_t)s.Hkv * p.rpad * sizeof(float), 256);
     l.alpha = off;  off += align_up((size_t)s.Hkv * (size_t)s.L * sizeof(float), 256);
+    l.gmax = off;   off += align_up((size_t)s.Hkv * (size_t)((s.L + kGroupKeys - 1) / kGroupKeys) * sizeof(float), 256);
     l.bytes = off;
     return l;
 }
@@ -119,7 +146,7 @@ inline SelectLayout select_layout(const mage_shape &s, const SplitPlan &p)
 // Fused step 1 (exact attention that also feeds selection): the attention partials, then the
 // prefix statistics per attention split, then selection's lse2 and alpha.
 struct Step1Layout {
-    size_t partials, stat_m, stat_l, lse2, alpha, bytes;
+    size_t partials, stat_m, stat_l, lse2, alpha, gmax, bytes;
 };
 
 inline Step1Layout step1_layout(const mage_shape &s, const SplitPlan &attn)
@@ -132,6 +159,7 @@ inline Step1Layout step1_layout(const mage_shape &s, const SplitPlan &attn)
     l.stat_l = off;   off += align_up(rows * sizeof(float), 256);
     l.lse2 = off;     off += align_up((size_t)s.Hkv * attn.rpad * sizeof(float), 256);
     l.alpha = off;    off += align_up((size_t)s.Hkv * (size_t)s.L * sizeof(float), 256);
+    l.gmax = off;     off += align_up((size_t)s.Hkv * (size_t)((s.L + kGroupKeys - 1) / kGroupKeys) * sizeof(float), 256);
     l.bytes = off;
     return l;
 }
@@ -145,6 +173,7 @@ struct KernelArgs {
     float *stat_m, *stat_l;  // exact attention, optional: prefix-only (cache keys) statistics per split, as part_m/part_l
     const float *lse2;       // column-sum pass: per-row log2-domain log-sum-exp [Hkv][rpad]
     float *alpha;            // column-sum pass: [Hkv][L]
+    float *gmax;             // column-sum pass, optional: [Hkv][ceil(L / kGroupKeys)] maxima of alpha over groups of consecutive keys
     int B, Hq, Hkv, G, R, rpad;
     long long L;             // rows in the cache
     long long nc;            // cache keys attended: L (dense) or k (gather)

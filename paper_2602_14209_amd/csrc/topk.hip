@@ -4,16 +4,20 @@
 // integers is the order of the values.
 //
 // One workgroup of 1024 threads per KV head.  Two routes, chosen per head at run time:
-//   filter route (k small against L, the method's regime): the k-th largest of 8192 strided
-//     group maxima is a lower bound of the k-th largest element, so one more sweep keeps only
-//     the few elements at or above it; those are sorted in LDS by (value desc, index asc), the
-//     first k taken and sorted by index.
+//   filter route (k small against L, the method's regime): the k-th largest of the maxima of
+//     disjoint groups of elements is a lower bound of the k-th largest element, so only the few
+//     elements at or above it can belong to the set; a radix select over those candidates in LDS
+//     finds the k-th value and the ties to keep, and a bitmap walk emits the positions in order.
+//     The group maxima either come with the row (the column-sum pass leaves one per kGroupKeys
+//     consecutive keys; only the groups at or above the bound are then read at all) or are
+//     taken here over 8192 strided groups in a first sweep of the row.
 //   radix route (any k, any tie structure; also the overflow exit of the filter route): three
 //     MSB-first radix-select steps over the whole row find the k-th value and the number of
 //     ties to keep, then an ordered sweep emits the set.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "plan.hpp"
 #include "probe.hpp"
 
 namespace mage {
@@ -158,7 +162,7 @@ __device__ __forceinline__ int pow2_at_least(int n)
     return p;
 }
 
-__global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, long long L, int k, int32_t *idx_out)
+__global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, const float *group_max, long long L, int k, int32_t *idx_out)
 {
     __shared__ uint32_t hist[TK_BINS];
     __shared__ uint32_t tmp[TK_WAVES + 1];
@@ -168,6 +172,8 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, lo
     __shared__ uint32_t gmax[TK_GROUPS];                 // group maxima, later the index sort buffer
     __shared__ uint32_t cval[TK_CAND];                   // candidate values (fp32 bit patterns)
     __shared__ uint32_t cidx[TK_CAND];                   // and their positions
+    __shared__ uint32_t glist[TK_CAND];                  // groups at or above the bound (handed-in maxima only)
+    __shared__ uint32_t n_hit;
 
     const int h = blockIdx.x;
     const uint32_t *u = reinterpret_cast<const uint32_t *>(alpha) + (long long)h * L;
@@ -176,49 +182,54 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, lo
     MAGE_PROBE_DECL;
     MAGE_PROBE_AT(0);
     if (k <= TK_FILTER_MAX_K) {
-        // ---- filter route, sweep 1: strided group maxima (group = slot * 1024 + thread) ----
-        // each thread takes 4 consecutive elements per slot (one 16-byte load when the row is aligned)
         const bool vec_ok = (L & 3) == 0 && (reinterpret_cast<uintptr_t>(u) & 15) == 0;
-        uint32_t gm[TK_SLOTS];
-#pragma unroll
-        for (int s = 0; s < TK_SLOTS; ++s) gm[s] = 0u;
-        for (long long base0 = 0; base0 < L; base0 += 4ll * TK_GROUPS) {
-            uint4 x[TK_SLOTS];
-#pragma unroll
-            for (int s = 0; s < TK_SLOTS; ++s) x[s] = load4(u, base0 + 4ll * (s * TK_THREADS + threadIdx.x), L, vec_ok);
-#pragma unroll
-            for (int s = 0; s < TK_SLOTS; ++s) {
-                const uint32_t a = x[s].x > x[s].y ? x[s].x : x[s].y, b = x[s].z > x[s].w ? x[s].z : x[s].w;
-                const uint32_t c = a > b ? a : b;
-                gm[s] = c > gm[s] ? c : gm[s];
+        const int lane = threadIdx.x & 63;
+        const long long ng = (L + kGroupKeys - 1) / kGroupKeys;       // handed-in group maxima
+        const uint32_t *gsrc = gmax;                                   // where the maxima are ranked from
+        long long gcount = TK_GROUPS;
+        if (group_max != nullptr) {
+            const uint32_t *gg = reinterpret_cast<const uint32_t *>(group_max) + (long long)h * ng;
+            if (ng <= TK_GROUPS) {
+                for (int i = threadIdx.x; i < TK_GROUPS; i += TK_THREADS) gmax[i] = i < ng ? gg[i] : 0u;
+            } else {
+                gsrc = gg;
             }
-        }
+            gcount = ng <= TK_GROUPS ? TK_GROUPS : ng;
+        } else {
+            // ---- sweep 1: strided group maxima (group = slot * 1024 + thread); each thread takes 4
+            // consecutive elements per slot (one 16-byte load when the row is aligned)
+            uint32_t gm[TK_SLOTS];
 #pragma unroll
-        for (int s = 0; s < TK_SLOTS; ++s) gmax[s * TK_THREADS + threadIdx.x] = gm[s];
-        if (threadIdx.x == 0) n_cand = 0;
+            for (int s = 0; s < TK_SLOTS; ++s) gm[s] = 0u;
+            for (long long base0 = 0; base0 < L; base0 += 4ll * TK_GROUPS) {
+                uint4 x[TK_SLOTS];
+#pragma unroll
+                for (int s = 0; s < TK_SLOTS; ++s) x[s] = load4(u, base0 + 4ll * (s * TK_THREADS + threadIdx.x), L, vec_ok);
+#pragma unroll
+                for (int s = 0; s < TK_SLOTS; ++s) {
+                    const uint32_t a = x[s].x > x[s].y ? x[s].x : x[s].y, b = x[s].z > x[s].w ? x[s].z : x[s].w;
+                    const uint32_t c = a > b ? a : b;
+                    gm[s] = c > gm[s] ? c : gm[s];
+                }
+            }
+#pragma unroll
+            for (int s = 0; s < TK_SLOTS; ++s) gmax[s * TK_THREADS + threadIdx.x] = gm[s];
+        }
+        if (threadIdx.x == 0) {
+            n_cand = 0;
+            n_hit = 0;
+        }
         __syncthreads();
         MAGE_PROBE_AT(1);
         // a lower bound of the k-th largest group maximum (its top 20 bits), hence of the k-th
         // largest element: at least k elements are >= floor_bits
         uint32_t floor_bits = 0, rank = (uint32_t)k;
-        radix_step(gmax, TK_GROUPS, 20, 12, floor_bits, rank, hist, tmp, bcast);
-        radix_step(gmax, TK_GROUPS, 12, 8, floor_bits, rank, hist, tmp, bcast);
+        radix_step(gsrc, gcount, 20, 12, floor_bits, rank, hist, tmp, bcast);
+        radix_step(gsrc, gcount, 12, 8, floor_bits, rank, hist, tmp, bcast);
 
         MAGE_PROBE_AT(2);
-        // ---- sweep 2: keep the elements at or above the bound ----
-        const int lane = threadIdx.x & 63;
-        for (long long base0 = 0; base0 < L; base0 += 4ll * TK_GROUPS) {      // uniform trip count
-            uint4 x[TK_SLOTS];
-#pragma unroll
-            for (int s = 0; s < TK_SLOTS; ++s) x[s] = load4(u, base0 + 4ll * (s * TK_THREADS + threadIdx.x), L, vec_ok);
-            // count this lane's keepers, reserve room for the whole wavefront with one atomic
-            uint32_t cnt = 0;
-#pragma unroll
-            for (int s = 0; s < TK_SLOTS; ++s) {
-                const long long j = base0 + 4ll * (s * TK_THREADS + threadIdx.x);
-                cnt += (j < L && x[s].x >= floor_bits) + (j + 1 < L && x[s].y >= floor_bits) +
-                       (j + 2 < L && x[s].z >= floor_bits) + (j + 3 < L && x[s].w >= floor_bits);
-            }
+        // appends this thread's `cnt` keepers among x[0..NX) (positions j[i] .. j[i]+3) to the candidates
+        auto keep = [&](const uint4 *x, const long long *j, int nx, uint32_t cnt) {
             uint32_t incl = cnt;
 #pragma unroll
             for (int d = 1; d < 64; d <<= 1) {
@@ -226,31 +237,108 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, lo
                 if (lane >= d) incl += y;
             }
             const uint32_t wave_total = __shfl(incl, 63);
-            if (wave_total == 0) continue;                 // uniform per wavefront
+            if (wave_total == 0) return;                   // uniform per wavefront
             uint32_t base = 0;
             if (lane == 0) base = atomicAdd(&n_cand, wave_total);
             uint32_t pos = __shfl(base, 0) + incl - cnt;
             if (cnt) {
-#pragma unroll
-                for (int s = 0; s < TK_SLOTS; ++s) {
-                    const long long j = base0 + 4ll * (s * TK_THREADS + threadIdx.x);
+                for (int s = 0; s < nx; ++s) {
                     const uint32_t xs[4] = {x[s].x, x[s].y, x[s].z, x[s].w};
 #pragma unroll
                     for (int c = 0; c < 4; ++c)
-                        if (j + c < L && xs[c] >= floor_bits) {
+                        if (j[s] >= 0 && j[s] + c < L && xs[c] >= floor_bits) {
                             if (pos < TK_CAND) {
                                 cval[pos] = xs[c];
-                                cidx[pos] = (uint32_t)(j + c);
+                                cidx[pos] = (uint32_t)(j[s] + c);
                             }
                             ++pos;
                         }
                 }
             }
+        };
+        bool overflow = false;
+        if (group_max != nullptr) {
+            // ---- the groups at or above the bound, then only their elements ----
+            for (long long g0 = 0; g0 < ng; g0 += (long long)TK_THREADS * TK_SLOTS) {     // uniform trip count
+                uint32_t gv[TK_SLOTS];
+#pragma unroll
+                for (int s = 0; s < TK_SLOTS; ++s) {
+                    const long long g = g0 + (long long)s * TK_THREADS + threadIdx.x;
+                    gv[s] = g < ng ? gsrc[g] : 0u;
+                }
+                uint32_t cnt = 0;
+#pragma unroll
+                for (int s = 0; s < TK_SLOTS; ++s) {
+                    const long long g = g0 + (long long)s * TK_THREADS + threadIdx.x;
+                    cnt += (g < ng && gv[s] >= floor_bits);
+                }
+                uint32_t incl = cnt;
+#pragma unroll
+                for (int d = 1; d < 64; d <<= 1) {
+                    const uint32_t y = __shfl_up(incl, d);
+                    if (lane >= d) incl += y;
+                }
+                const uint32_t wave_total = __shfl(incl, 63);
+                if (wave_total == 0) continue;
+                uint32_t base = 0;
+                if (lane == 0) base = atomicAdd(&n_hit, wave_total);
+                uint32_t pos = __shfl(base, 0) + incl - cnt;
+#pragma unroll
+                for (int s = 0; s < TK_SLOTS; ++s) {
+                    const long long g = g0 + (long long)s * TK_THREADS + threadIdx.x;
+                    if (g < ng && gv[s] >= floor_bits) {
+                        if (pos < TK_CAND) glist[pos] = (uint32_t)g;
+                        ++pos;
+                    }
+                }
+            }
+            __syncthreads();
+            const uint32_t nh = n_hit;
+            overflow = nh > TK_CAND;
+            if (!overflow) {
+                constexpr int QPG = kGroupKeys / 4;            // 16-byte pieces per group
+                constexpr int NX = 4;                           // pieces in flight per thread
+                const uint32_t items = nh * QPG;
+                for (uint32_t i0 = 0; i0 < items; i0 += TK_THREADS * NX) {                // uniform trip count
+                    uint4 x[NX];
+                    long long j[NX];
+#pragma unroll
+                    for (int s = 0; s < NX; ++s) {
+                        const uint32_t i = i0 + s * TK_THREADS + threadIdx.x;
+                        j[s] = i < items ? (long long)glist[i / QPG] * kGroupKeys + 4 * (i % QPG) : -1;
+                        x[s] = j[s] >= 0 ? load4(u, j[s], L, vec_ok) : make_uint4(0, 0, 0, 0);
+                    }
+                    uint32_t cnt = 0;
+#pragma unroll
+                    for (int s = 0; s < NX; ++s)
+                        if (j[s] >= 0)
+                            cnt += (j[s] < L && x[s].x >= floor_bits) + (j[s] + 1 < L && x[s].y >= floor_bits) +
+                                   (j[s] + 2 < L && x[s].z >= floor_bits) + (j[s] + 3 < L && x[s].w >= floor_bits);
+                    keep(x, j, NX, cnt);
+                }
+            }
+        } else {
+            // ---- sweep 2: keep the elements at or above the bound ----
+            for (long long base0 = 0; base0 < L; base0 += 4ll * TK_GROUPS) {      // uniform trip count
+                uint4 x[TK_SLOTS];
+                long long j[TK_SLOTS];
+#pragma unroll
+                for (int s = 0; s < TK_SLOTS; ++s) {
+                    j[s] = base0 + 4ll * (s * TK_THREADS + threadIdx.x);
+                    x[s] = load4(u, j[s], L, vec_ok);
+                }
+                uint32_t cnt = 0;
+#pragma unroll
+                for (int s = 0; s < TK_SLOTS; ++s)
+                    cnt += (j[s] < L && x[s].x >= floor_bits) + (j[s] + 1 < L && x[s].y >= floor_bits) +
+                           (j[s] + 2 < L && x[s].z >= floor_bits) + (j[s] + 3 < L && x[s].w >= floor_bits);
+                keep(x, j, TK_SLOTS, cnt);
+            }
         }
         __syncthreads();
         MAGE_PROBE_AT(3);
         const uint32_t nc = n_cand;
-        if (nc <= TK_CAND) {
+        if (!overflow && nc <= TK_CAND) {
             // exact k-th value among the candidates (radix select in LDS) and the number of
             // candidates equal to it that belong to the set (the ones with the smallest positions)
             uint32_t thr = 0, want = (uint32_t)k;
@@ -359,9 +447,10 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, lo
     }
 }
 
-hipError_t launch_topk(const float *alpha, int Hkv, long long L, int k, int32_t *idx_out, hipStream_t stream)
+// group_max: nullptr, or [Hkv][ceil(L / kGroupKeys)] maxima of alpha over groups of kGroupKeys consecutive positions
+hipError_t launch_topk(const float *alpha, const float *group_max, int Hkv, long long L, int k, int32_t *idx_out, hipStream_t stream)
 {
-    hipLaunchKernelGGL(topk_kernel, dim3(Hkv), dim3(TK_THREADS), 0, stream, alpha, L, k, idx_out);
+    hipLaunchKernelGGL(topk_kernel, dim3(Hkv), dim3(TK_THREADS), 0, stream, alpha, group_max, L, k, idx_out);
     return hipGetLastError();
 }
 
