@@ -150,6 +150,30 @@ def test_select_ties_and_uniform_on_gpu(oracle_mod):
     check_index_sets(idx, ref["idx"], ref["alpha32"], L)
 
 
+def test_select_long_rows_and_group_overflow(oracle_mod):
+    """Top-k filter fed with group maxima: more groups than the LDS copy holds (L > 131072), and a
+    row where every group reaches the bound (uniform alpha), which must leave by the radix route."""
+    from gpu_util import Problem, check_alpha, check_index_sets
+    from paper_2602_14209_amd.workloads import bf16_to_f32, round_to_bf16
+    rng = np.random.default_rng(17)
+    B, Hq, Hkv, d, L, k = 8, 2, 1, 64, 140001, 96
+    q = bf16_to_f32(round_to_bf16(rng.standard_normal((B, Hq, d)).astype(np.float32)))
+    K = bf16_to_f32(round_to_bf16(rng.standard_normal((L, Hkv, d)).astype(np.float32)))
+    ref = oracle_mod.select(q, K, k)
+    p = Problem(q, K, K, None, None, k, "bf16")
+    idx, alpha = p.select()
+    check_alpha(alpha, ref["alpha"])
+    check_index_sets(idx, ref["idx"], ref["alpha32"], L)
+    # all keys equal: 80000 / 16 = 5000 groups at the bound, more than the candidate list holds
+    L2 = 80000
+    K2 = np.broadcast_to(K[:1], (L2, Hkv, d)).copy()
+    p = Problem(q, K2, K2, None, None, k, "bf16")
+    idx, alpha = p.select()
+    assert np.array_equal(idx, np.tile(np.arange(k, dtype=np.int32), (Hkv, 1)))
+    np.testing.assert_allclose(alpha, 1.0 / L2, rtol=1e-5)
+
+
+
 def test_c4_full_size_headline_shape(oracle_mod):
     """The benchmark's shape and launch configuration (L=131072, Hq=32, Hkv=8, k=512): selection
     checked in full, exact attention on sampled block positions, one sparse step in full."""
