@@ -77,7 +77,7 @@ int run_attention(const mage_shape *shape, const SplitPlan &p, bool gather,
                   const void *q, const void *k_cache, const void *v_cache, const int32_t *idx,
                   const void *k_blk, const void *v_blk, float *out, float *lse_out,
                   void *workspace, size_t workspace_bytes, void *hip_stream,
-                  float *stat_m = nullptr, float *stat_l = nullptr)
+                  float *stat_m = nullptr, float *stat_l = nullptr, float *lse2_out = nullptr)
 {
     if (!q || !k_cache || !v_cache || !out || (gather && !idx)) return MAGE_ERR_NULL;
     if ((k_blk == nullptr) != (v_blk == nullptr)) return MAGE_ERR_NULL;
@@ -100,6 +100,7 @@ int run_attention(const mage_shape *shape, const SplitPlan &p, bool gather,
     a.lse_out = lse_out;
     a.stat_m = stat_m;
     a.stat_l = stat_l;
+    a.lse2_out = p.n_split > 1 ? lse2_out : nullptr;
     if (p.n_split > 1) carve_partials(*shape, p, workspace, a);
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -262,16 +263,18 @@ int mage_step1(const mage_shape *shape, const void *q1, const void *k_cache, con
     if (!workspace || workspace_bytes < lay.bytes) return MAGE_ERR_WORKSPACE;
     char *w = static_cast<char *>(workspace);
     float *stat_m = reinterpret_cast<float *>(w + lay.stat_m), *stat_l = reinterpret_cast<float *>(w + lay.stat_l);
+    float *lse2 = reinterpret_cast<float *>(w + lay.lse2);
     rc = run_attention(shape, pa, false, q1, k_cache, v_cache, nullptr, k_blk, v_blk, out, lse_out,
-                       w + lay.partials, lay.stat_m - lay.partials, hip_stream, stat_m, stat_l);
+                       w + lay.partials, lay.stat_m - lay.partials, hip_stream, stat_m, stat_l, lse2);
     if (rc != MAGE_OK) return rc;
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    float *lse2 = reinterpret_cast<float *>(w + lay.lse2);
-    KernelArgs r = base_args(*shape, pa);            // merge the attention splits' prefix statistics
-    r.part_m = stat_m;
-    r.part_l = stat_l;
-    if (launch_lse(r, lse2, stream) != hipSuccess) return MAGE_ERR_HIP;
+    if (pa.n_split == 1) {                           // unsplit keys: no combine pass ran, merge the one statistics set here
+        KernelArgs r = base_args(*shape, pa);
+        r.part_m = stat_m;
+        r.part_l = stat_l;
+        if (launch_lse(r, lse2, stream) != hipSuccess) return MAGE_ERR_HIP;
+    }
     KernelArgs a = base_args(*shape, ps);            // column sums on selection's own, finer split
     a.q = q1;
     a.kc = k_cache;

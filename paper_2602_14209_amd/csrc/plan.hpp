@@ -172,6 +172,7 @@ struct KernelArgs {
     float *part_o, *part_m, *part_l;
     float *stat_m, *stat_l;  // exact attention, optional: prefix-only (cache keys) statistics per split, as part_m/part_l
     const float *lse2;       // column-sum pass: per-row log2-domain log-sum-exp [Hkv][rpad]
+    float *lse2_out;         // combine, optional: the same, merged from stat_m / stat_l
     float *alpha;            // column-sum pass: [Hkv][L]
     float *gmax;             // column-sum pass, optional: [Hkv][ceil(L / kGroupKeys)] maxima of alpha over groups of consecutive keys
     int B, Hq, Hkv, G, R, rpad;

@@ -1,5 +1,6 @@
 // Small kernels around the attention passes (gfx950):
 //   combine_kernel   merges the split-key partials of an attention call into out / lse
+//                    (and, for the fused step 1, the prefix statistics into selection's lse)
 //   lse_kernel       merges the statistics partials of selection into one log2-domain
 //                    log-sum-exp per query row
 #include <hip/hip_runtime.h>
@@ -23,6 +24,24 @@ __global__ __launch_bounds__(256) void combine_kernel(const KernelArgs a)
     const int row = blockIdx.x, h = blockIdx.y;
     const int c4 = threadIdx.x % TPR, sg = threadIdx.x / TPR;
     const long long base = (long long)h * a.n_split * a.rpad + row;
+
+    // fused step 1: the last wavefront also merges the prefix-only statistics of this row into the
+    // log-sum-exp that the column sums need (as lse_kernel would)
+    if (a.lse2_out != nullptr && (threadIdx.x >> 6) == 3) {
+        const int lane = threadIdx.x & 63;
+        float Mp = -INFINITY;
+        for (int s = lane; s < a.n_split; s += 64) Mp = fmaxf(Mp, a.stat_m[base + (long long)s * a.rpad]);
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) Mp = fmaxf(Mp, __shfl_xor(Mp, d));
+        double lp = 0.0;
+        for (int s = lane; s < a.n_split; s += 64) {
+            const long long pi = base + (long long)s * a.rpad;
+            lp += (double)a.stat_l[pi] * (double)exp2f(a.stat_m[pi] - Mp);
+        }
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) lp += __shfl_xor(lp, d);
+        if (lane == 0) a.lse2_out[(long long)h * a.rpad + row] = Mp + (float)log2(lp);
+    }
 
     float M = -INFINITY;
     for (int s = threadIdx.x; s < a.n_split; s += 256) M = fmaxf(M, a.part_m[base + (long long)s * a.rpad]);
