@@ -23,7 +23,7 @@
  *   - T is not an argument: the caller invokes mage_sparse_attn once per denoising step
  *     2..T with the index set that mage_select produced at step 1 (Alg. 1, Phase 2).
  *   - Supported: d in {64, 128}; Hq % Hkv == 0; 1 <= k <= L <= 2^30; B*G <= 256 for
- *     mage_select with MAGE_BF16.
+ *     mage_select and mage_step1 with MAGE_BF16; mage_sparse_attn_batched with MAGE_BF16 only.
  */
 #ifndef MAGE_H
 #define MAGE_H
