@@ -47,6 +47,7 @@ enum { MODE_ATTN = 0, MODE_STATS = 1 };
 
 #define MAGE_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 #define MAGE_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
+#define MAGE_LDS_ADDR(a) ((__attribute__((address_space(3))) void *)(uintptr_t)(a))
 
 __device__ __forceinline__ bf16x8_t as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8_t, v); }
 
@@ -89,34 +90,33 @@ __device__ __forceinline__ void issue_tile(const u16 *kbase, const u16 *vbase, l
     }
 }
 
-// The same for a full tile of contiguous cache rows: `kptr[n]` is this lane's source address for
-// load n at the first tile of the split (computed once); tile t lies t * 64 rows further on.
+// The same for a full tile of contiguous cache rows, written so that the per-tile part of every
+// address is wavefront-uniform (scalar registers): `kbase` points at (first row of the tile, this KV
+// head, channel 0), `off[n]` is this lane's byte offset inside a tile for load n (constant over the
+// tiles), `lds_tile` the LDS byte address of the tile buffer plus this wavefront's 1 KB share.
 template <int D, int NW, bool WITH_V>
-__device__ __forceinline__ void issue_tile_stream(const u16 *const (&kptr)[TileGeom<D>::LOADS / NW], long long tile_elems,
-                                                  long long v_minus_k, int t, unsigned char *buf)
+__device__ __forceinline__ void issue_tile_stream(const unsigned char *kbase, long long v_minus_k_bytes,
+                                                  const unsigned (&off)[TileGeom<D>::LOADS / NW], unsigned lds_tile)
 {
     using G = TileGeom<D>;
-    const int wave = threadIdx.x >> 6;
 #pragma unroll
     for (int n = 0; n < G::LOADS / NW; ++n) {
-        const int unit = n * NW + wave;
-        const u16 *src = kptr[n] + t * tile_elems;
-        __builtin_amdgcn_global_load_lds(MAGE_GLOBAL_PTR(src), MAGE_LDS_PTR(buf + unit * 1024), 16, 0, 0);
+        const unsigned dst = lds_tile + n * NW * 1024;
+        __builtin_amdgcn_global_load_lds(MAGE_GLOBAL_PTR(kbase + off[n]), MAGE_LDS_ADDR(dst), 16, 0, 0);
         if (WITH_V)
-            __builtin_amdgcn_global_load_lds(MAGE_GLOBAL_PTR(src + v_minus_k), MAGE_LDS_PTR(buf + G::MAT_BYTES + unit * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(MAGE_GLOBAL_PTR(kbase + v_minus_k_bytes + off[n]), MAGE_LDS_ADDR(dst + G::MAT_BYTES), 16, 0, 0);
     }
 }
 
 template <int D, int NW>
-__device__ __forceinline__ void stream_pointers(const u16 *kc, long long c0, long long row_stride,
-                                                const u16 *(&kptr)[TileGeom<D>::LOADS / NW])
+__device__ __forceinline__ void stream_offsets(long long row_stride, unsigned (&off)[TileGeom<D>::LOADS / NW])
 {
     using G = TileGeom<D>;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
     for (int n = 0; n < G::LOADS / NW; ++n) {
         const int r = (n * NW + wave) * G::RPI + lane / G::CH;
-        kptr[n] = kc + (c0 + r) * row_stride + ((lane % G::CH) ^ swz<D>(r)) * 8;
+        off[n] = (unsigned)(r * row_stride * 2 + ((lane % G::CH) ^ swz<D>(r)) * 16);
     }
 }
 
@@ -317,6 +317,9 @@ struct SplitRange {
     int cache_tiles, blk_tiles;
 };
 
+// The tile counts steer every branch of the tile loop; they are the same for all lanes, and
+// readfirstlane tells the compiler so (the 64-bit division would otherwise leave them in vector
+// registers and turn the loop's control flow into lane masks).
 __device__ __forceinline__ SplitRange split_range(const KernelArgs &a, int s)
 {
     SplitRange r;
@@ -324,8 +327,8 @@ __device__ __forceinline__ SplitRange split_range(const KernelArgs &a, int s)
     r.first = (long long)s * kBf16Tile;
     r.step = (long long)a.n_cyc * kBf16Tile;
     r.nc = a.nc;
-    r.cache_tiles = (s < a.n_cyc && total > s) ? (int)((total - s + a.n_cyc - 1) / a.n_cyc) : 0;
-    r.blk_tiles = (s == a.blk_split) ? (a.n_blk + kBf16Tile - 1) / kBf16Tile : 0;
+    r.cache_tiles = __builtin_amdgcn_readfirstlane((s < a.n_cyc && total > s) ? (int)((total - s + a.n_cyc - 1) / a.n_cyc) : 0);
+    r.blk_tiles = __builtin_amdgcn_readfirstlane((s == a.blk_split) ? (a.n_blk + kBf16Tile - 1) / kBf16Tile : 0);
     return r;
 }
 
@@ -360,11 +363,13 @@ void attn_bf16_kernel(const KernelArgs a)
     constexpr int KS = D / 16;     // MFMA k-steps over the head dimension
     constexpr int DT = D / 32;     // 32-row tiles of O^T
     constexpr int HALF = 32 * G::ROW_BYTES;
-    constexpr int OST = D + 4;     // floats per staged output row
-    constexpr int MERGE_FLOATS = 4 * DT * 16 * 64;      // O^T accumulators of the four upper-half wavefronts
-    constexpr int MERGE_BYTES = ((WITH_V ? MERGE_FLOATS : 0) + 4 * 4 * 64) * 4;
-    constexpr int SMEM_BYTES = NBUF * BUF_BYTES > MERGE_BYTES ? NBUF * BUF_BYTES : MERGE_BYTES;
-    static_assert(SMEM_BYTES >= 2 * 32 * OST * 4, "output staging must fit in the tile buffers");
+    constexpr int HDT = WITH_V ? DT / 2 : 0;            // O^T tiles each wavefront of a pair finishes
+    constexpr int XCH_FLOATS = HDT * 16 * 64;           // accumulators a wavefront hands to its partner
+    constexpr int HOST = D / 2 + 4;                     // floats per staged half row
+    constexpr int XCH_BYTES = (NW * XCH_FLOATS + NW * 4 * 64) * 4;
+    constexpr int STAGE_BYTES = WITH_V ? NW * 32 * HOST * 4 : 0;
+    constexpr int TAIL_BYTES = XCH_BYTES > STAGE_BYTES ? XCH_BYTES : STAGE_BYTES;
+    constexpr int SMEM_BYTES = NBUF * BUF_BYTES > TAIL_BYTES ? NBUF * BUF_BYTES : TAIL_BYTES;
     static_assert((NBUF - 2) * LPT < 64, "outstanding loads must fit the counter");
 
     // tile buffers; after the key loop the same memory carries the merge and the output transposition
@@ -403,20 +408,40 @@ void attn_bf16_kernel(const KernelArgs a)
         const int left = a.n_blk - (t - sr.cache_tiles) * kBf16Tile;
         return left < kBf16Tile ? left : kBf16Tile;
     };
-    const u16 *kptr[G::LOADS / NW];
-    if (!GATHER) stream_pointers<D, NW>(kc, sr.first, cache_stride, kptr);
-    const long long tile_elems = sr.step * cache_stride;
-    const long long v_minus_k = vc - kc;
+    unsigned soff[G::LOADS / NW];      // this lane's byte offsets inside a streamed tile
+    stream_offsets<D, NW>(cache_stride, soff);
+    const long long v_minus_k_bytes = reinterpret_cast<const unsigned char *>(vc) - reinterpret_cast<const unsigned char *>(kc);
+    const unsigned lds_wave = __builtin_amdgcn_readfirstlane(lds_addr(smem) + wave * 1024);
+    // Gathered rows: the index entries of the next kIdxTiles tiles wait in LDS, fetched ahead in
+    // one go.  An index loaded into a register right before its row would sit behind every tile
+    // load in flight (loads retire in order), i.e. drain the ring at every tile.
+    constexpr int kIdxTiles = 16;
+    __shared__ int32_t idx_lds[GATHER ? kIdxTiles * kBf16Tile : 1];
+    const unsigned idx_addr = lds_addr(idx_lds);
+    int idx_t0 = 0;                    // first tile whose entries idx_lds holds
+    auto load_idx = [&](int tc0) {
+        for (int e = threadIdx.x; e < kIdxTiles * kBf16Tile; e += NW * 64) {
+            const int tt = tc0 + e / kBf16Tile;
+            long long pos = sr.first + tt * sr.step + (e % kBf16Tile);
+            if (pos >= sr.nc) pos = sr.nc - 1;              // padding positions re-read the last key (masked below)
+            idx_lds[e] = tt < sr.cache_tiles ? idx[pos] : 0;
+        }
+    };
     auto issue = [&](int t) {
         const int valid = tile_valid(t);
         unsigned char *buf = smem + (t % NBUF) * BUF_BYTES;
         if (!GATHER && t < sr.cache_tiles && valid == kBf16Tile) {
-            issue_tile_stream<D, NW, WITH_V>(kptr, tile_elems, v_minus_k, t, buf);
+            issue_tile_stream<D, NW, WITH_V>(reinterpret_cast<const unsigned char *>(kc + (sr.first + t * sr.step) * cache_stride),
+                                             v_minus_k_bytes, soff, lds_wave + (t % NBUF) * BUF_BYTES);
         } else if (t < sr.cache_tiles) {
             const long long base = sr.first + t * sr.step;
             issue_tile<D, NW, WITH_V>(kc, vc, cache_stride, buf, [&](int r) -> long long {
-                const long long pos = base + (r < valid ? r : valid - 1);
-                return GATHER ? (long long)idx[pos] : pos;
+                if (GATHER) {
+                    float v = lds_read_f32<0>(idx_addr + ((t - idx_t0) * kBf16Tile + r) * 4);
+                    lds_wait<0>(v);
+                    return (long long)__builtin_bit_cast(int, v);
+                }
+                return base + (r < valid ? r : valid - 1);
             });
         } else {
             const int base = (t - sr.cache_tiles) * kBf16Tile;
@@ -424,12 +449,16 @@ void attn_bf16_kernel(const KernelArgs a)
         }
     };
 
-#pragma unroll
-    for (int t = 0; t < NBUF - 1; ++t)
-        if (t < ntiles) issue(t);      // first: the longest dependent chain (index -> row)
-
+    // queries first: waiting for them later (loads retire in order) must not mean waiting for tiles
     bf16x8_t qf[KS];
     load_q_frag<D>(a, static_cast<const u16 *>(a.q) + z * a.seq_q, h, row, qf);
+    if (GATHER) {
+        load_idx(0);
+        __syncthreads();
+    }
+#pragma unroll
+    for (int t = 0; t < NBUF - 1; ++t)
+        if (t < ntiles) issue(t);
     FragAddr fa = frag_addr<D>(lane);
     fa.k += kh * HALF;                 // this wavefront's half of every tile
     fa.v[0] += kh * HALF;
@@ -444,11 +473,24 @@ void attn_bf16_kernel(const KernelArgs a)
     float m_run = -INFINITY, l_run = 0.f;     // running max (log2 domain) and this lane's share of the normaliser
     float m_pre = -INFINITY, l_pre = 0.f;     // the same after the last cache tile (prefix-only statistics)
 
+    // the query fragments must have arrived before the loop: a wait for them inside it would be a
+    // wait for every tile load in flight, once per tile
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" ::"v"(qf[ks]));
+
     for (int t = 0; t < ntiles; ++t) {
         // tile t landed (NBUF-2 younger tiles may still be in flight); everyone is done with tile t-1
         if (t + NBUF - 2 < ntiles) tile_barrier<(NBUF - 2) * LPT>();
         else tile_barrier<0>();
         if (t == 0) MAGE_PROBE_AT(1);
+        if (GATHER) {
+            const int tn = t + NBUF - 1;
+            if (tn < sr.cache_tiles && tn >= idx_t0 + kIdxTiles) {   // uniform; every wavefront is past its reads of the old entries
+                load_idx(tn);
+                idx_t0 = tn;
+                __syncthreads();
+            }
+        }
         if (t + NBUF - 1 < ntiles) issue(t + NBUF - 1);
         const int valid = tile_valid(t);
         const unsigned tile_addr = smem_addr + (t % NBUF) * BUF_BYTES;
@@ -528,48 +570,64 @@ void attn_bf16_kernel(const KernelArgs a)
     }
     MAGE_PROBE_AT(2);
 
-    // Merge the upper key half into the lower one.  O^T travels as 16-byte lane-contiguous pieces.
-    float *mrg = reinterpret_cast<float *>(smem);
-    float *mrg_stat = mrg + (WITH_V ? MERGE_FLOATS : 0) + rgw * 4 * 64 + lane;
+    // Merge of the two key halves.  Both wavefronts of a row group end up with the merged
+    // statistics, and each finishes one half of the channels: it hands the other half of its
+    // accumulators to its partner through LDS (16-byte lane-contiguous pieces).
+    float *xch = reinterpret_cast<float *>(smem);                      // [wave][HDT * 4][64] x 4 floats
+    float *xstat = xch + NW * XCH_FLOATS;                              // [wave][4][64]
+    auto hand_over = [&](auto FOREIGN) {                               // FOREIGN: first O^T tile of the half to give away
+        constexpr int f0 = decltype(FOREIGN)::value;
+#pragma unroll
+        for (int i = 0; i < HDT; ++i)
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4) {
+                const f32x4_t val = {o[f0 + i][4 * v4], o[f0 + i][4 * v4 + 1], o[f0 + i][4 * v4 + 2], o[f0 + i][4 * v4 + 3]};
+                *reinterpret_cast<f32x4_t *>(xch + (((wave * HDT + i) * 4 + v4) * 64 + lane) * 4) = val;
+            }
+    };
+    float fa_ = 1.f, fb_ = 1.f;
+    auto take_over = [&](auto OWN) {
+        constexpr int o0 = decltype(OWN)::value;
+        const int partner = wave ^ 4;
+#pragma unroll
+        for (int i = 0; i < HDT; ++i)
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4) {
+                const f32x4_t ob = *reinterpret_cast<const f32x4_t *>(xch + (((partner * HDT + i) * 4 + v4) * 64 + lane) * 4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[o0 + i][4 * v4 + e] = o[o0 + i][4 * v4 + e] * fa_ + ob[e] * fb_;
+            }
+    };
     __syncthreads();                    // every wavefront is done reading the last tile
-    if (kh == 1 && wave_active) {
+    if (wave_active) {
         if constexpr (WITH_V) {
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int v4 = 0; v4 < 4; ++v4) {
-                    const f32x4_t val = {o[dt][4 * v4], o[dt][4 * v4 + 1], o[dt][4 * v4 + 2], o[dt][4 * v4 + 3]};
-                    *reinterpret_cast<f32x4_t *>(mrg + (((rgw * DT + dt) * 4 + v4) * 64 + lane) * 4) = val;
-                }
+            if (kh == 0) hand_over(std::integral_constant<int, HDT>{});
+            else hand_over(std::integral_constant<int, 0>{});
         }
-        mrg_stat[0] = m_run;
-        mrg_stat[64] = l_tot;
-        mrg_stat[128] = m_pre;
-        mrg_stat[192] = lp_tot;
+        float *st = xstat + wave * 4 * 64 + lane;
+        st[0] = m_run;
+        st[64] = l_tot;
+        st[128] = m_pre;
+        st[192] = lp_tot;
     }
     __syncthreads();
-    if (kh == 0 && wave_active) {
-        const float m_b = mrg_stat[0], l_b = mrg_stat[64], mp_b = mrg_stat[128], lp_b = mrg_stat[192];
+    if (wave_active) {
+        const float *st = xstat + (wave ^ 4) * 4 * 64 + lane;
+        const float m_b = st[0], l_b = st[64], mp_b = st[128], lp_b = st[192];
         const float m = fmaxf(m_run, m_b);
-        const float fa_ = m_run == m ? 1.f : __builtin_amdgcn_exp2f(m_run - m);
-        const float fb_ = m_b == m ? 1.f : __builtin_amdgcn_exp2f(m_b - m);
+        fa_ = m_run == m ? 1.f : __builtin_amdgcn_exp2f(m_run - m);
+        fb_ = m_b == m ? 1.f : __builtin_amdgcn_exp2f(m_b - m);
         l_tot = l_tot * fa_ + l_b * fb_;
         m_run = m;
         const float mp = fmaxf(m_pre, mp_b);
         lp_tot = lp_tot * (m_pre == mp ? 1.f : __builtin_amdgcn_exp2f(m_pre - mp)) + lp_b * (mp_b == mp ? 1.f : __builtin_amdgcn_exp2f(mp_b - mp));
         m_pre = mp;
         if constexpr (WITH_V) {
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int v4 = 0; v4 < 4; ++v4) {
-                    const f32x4_t ob = *reinterpret_cast<const f32x4_t *>(mrg + (((rgw * DT + dt) * 4 + v4) * 64 + lane) * 4);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) o[dt][4 * v4 + e] = o[dt][4 * v4 + e] * fa_ + ob[e] * fb_;
-                }
+            if (kh == 0) take_over(std::integral_constant<int, 0>{});
+            else take_over(std::integral_constant<int, HDT>{});
         }
     }
-    const bool owner = kh == 0 && wave_active;
+    const bool owner = kh == 0 && wave_active;      // writes the per-row scalars
 
     if (WITH_V && a.stat_m != nullptr) {
         if (owner && row < a.R && lg == 0) {
@@ -588,42 +646,44 @@ void attn_bf16_kernel(const KernelArgs a)
         return;
     }
 
-    // Epilogue.  O^T register (dt, v) holds channel d = dt*32 + 8*(v/4) + 4*lg + v%4 of query row
-    // `row`.  Two wavefronts at a time transpose their 32 x D block through LDS and write whole
-    // rows (16 bytes per lane, consecutive lanes on consecutive addresses).
-    constexpr int LPR = D / 4;          // lanes per output row
+    // Output.  O^T register (dt, v) holds channel d = dt*32 + 8*(v/4) + 4*lg + v%4 of query row
+    // `row`.  Every wavefront transposes its 32 rows x D/2 channels through a private LDS region
+    // and writes whole half rows (16 bytes per lane, consecutive lanes on consecutive addresses).
+    constexpr int LPR = D / 8;          // lanes per half row
     constexpr int RPS = 64 / LPR;       // rows per store instruction
     const bool direct = a.n_split == 1;
     const float inv = direct ? 1.f / l_tot : 1.f;
-    float *stage = reinterpret_cast<float *>(smem) + (rgw & 1) * 32 * OST;
-    __syncthreads();                    // the merge area has been read
-    for (int round = 0; round < 2; ++round) {
-        if ((rgw >> 1) == round && owner) {
+    float *stage = reinterpret_cast<float *>(smem) + wave * 32 * HOST;
+    auto put_out = [&](auto OWN) {
+        constexpr int o0 = decltype(OWN)::value;
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
+        for (int i = 0; i < HDT; ++i)
 #pragma unroll
-                for (int v4 = 0; v4 < 4; ++v4) {
-                    f32x4_t val = {o[dt][4 * v4] * inv, o[dt][4 * v4 + 1] * inv, o[dt][4 * v4 + 2] * inv, o[dt][4 * v4 + 3] * inv};
-                    *reinterpret_cast<f32x4_t *>(stage + l32 * OST + dt * 32 + 8 * v4 + 4 * lg) = val;
+            for (int v4 = 0; v4 < 4; ++v4) {
+                const f32x4_t val = {o[o0 + i][4 * v4] * inv, o[o0 + i][4 * v4 + 1] * inv, o[o0 + i][4 * v4 + 2] * inv, o[o0 + i][4 * v4 + 3] * inv};
+                *reinterpret_cast<f32x4_t *>(stage + l32 * HOST + i * 32 + 8 * v4 + 4 * lg) = val;
+            }
+#pragma unroll
+        for (int it = 0; it < 32 / RPS; ++it) {
+            const int rr = it * RPS + lane / LPR, col = (lane % LPR) * 4;
+            const f32x4_t val = *reinterpret_cast<const f32x4_t *>(stage + rr * HOST + col);
+            const int orow = row0 + rr;
+            if (orow < a.R) {
+                float *dst;
+                if (direct) {
+                    const int gl = orow / a.B, qi = orow - gl * a.B;
+                    dst = a.out + z * a.seq_out + ((long long)qi * a.Hq + (long long)h * a.G + gl) * D;
+                } else {
+                    dst = a.part_o + (((long long)h * a.n_split + split) * a.rpad + orow) * D;
                 }
-#pragma unroll
-            for (int it = 0; it < 32 / RPS; ++it) {
-                const int rr = it * RPS + lane / LPR, col = (lane % LPR) * 4;
-                const f32x4_t val = *reinterpret_cast<const f32x4_t *>(stage + rr * OST + col);
-                const int orow = row0 + rr;
-                if (orow < a.R) {
-                    float *dst;
-                    if (direct) {
-                        const int gl = orow / a.B, qi = orow - gl * a.B;
-                        dst = a.out + z * a.seq_out + ((long long)qi * a.Hq + (long long)h * a.G + gl) * D;
-                    } else {
-                        dst = a.part_o + (((long long)h * a.n_split + split) * a.rpad + orow) * D;
-                    }
-                    *reinterpret_cast<f32x4_t *>(dst + col) = val;
-                }
+                *reinterpret_cast<f32x4_t *>(dst + o0 * 32 + col) = val;
             }
         }
-        __syncthreads();
+    };
+    __syncthreads();                    // the exchange area has been read
+    if (wave_active) {
+        if (kh == 0) put_out(std::integral_constant<int, 0>{});
+        else put_out(std::integral_constant<int, HDT>{});
     }
     MAGE_PROBE_AT(3);
     MAGE_PROBE_FLUSH();
@@ -671,14 +731,15 @@ __global__ __launch_bounds__(NW * 64) void colsum_bf16_kernel(const KernelArgs a
         const long long left = sr.nc - tile_key(t);
         return left < kBf16Tile ? (int)left : kBf16Tile;
     };
-    const u16 *kptr[G::LOADS / NW];
-    stream_pointers<D, NW>(kc, sr.first, cache_stride, kptr);
-    const long long tile_elems = sr.step * cache_stride;
+    unsigned soff[G::LOADS / NW];
+    stream_offsets<D, NW>(cache_stride, soff);
+    const unsigned lds_wave = __builtin_amdgcn_readfirstlane(lds_addr(smem) + wave * 1024);
     auto issue = [&](int t) {
         const int valid = tile_valid(t);
         unsigned char *buf = smem + (t % NBUF) * BUF_BYTES;
         if (valid == kBf16Tile) {
-            issue_tile_stream<D, NW, false>(kptr, tile_elems, 0, t, buf);
+            issue_tile_stream<D, NW, false>(reinterpret_cast<const unsigned char *>(kc + tile_key(t) * cache_stride), 0, soff,
+                                            lds_wave + (t % NBUF) * BUF_BYTES);
         } else {
             const long long base = tile_key(t);
             issue_tile<D, NW, false>(kc, kc, cache_stride, buf, [&](int r) -> long long { return base + (r < valid ? r : valid - 1); });
