@@ -27,8 +27,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include <utility>
-
+#include "lds_asm.hpp"
 #include "plan.hpp"
 #include "probe.hpp"
 
@@ -40,14 +39,9 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x8_t __attribute__((ext_vector_type(8)));
 typedef unsigned short u16;
-typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
-typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
 
 enum { MODE_ATTN = 0, MODE_STATS = 1 };
 
-#define MAGE_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
-#define MAGE_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
-#define MAGE_LDS_ADDR(a) ((__attribute__((address_space(3))) void *)(uintptr_t)(a))
 
 __device__ __forceinline__ bf16x8_t as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8_t, v); }
 
@@ -158,69 +152,6 @@ __device__ __forceinline__ FragAddr frag_addr(int lane)
         f.v[b] = (unsigned)(key * ROW) | (unsigned)((low ^ swz<D>(key)) << 4) | (unsigned)(8 * (q & 1));
     }
     return f;
-}
-
-// The LDS reads of the tile loop are inline assembly.  The compiler orders every LDS access it
-// knows of behind ALL outstanding direct-to-LDS loads (it cannot tell the ring buffers apart), which
-// would put the whole HBM latency of the prefetch of tile t+1 in front of the arithmetic of tile t.
-// The price is that the waits are ours: lds_wait<N> holds the named registers until at most N
-// younger LDS operations of this wavefront are outstanding (LDS returns data in issue order).
-template <int OFF>
-__device__ __forceinline__ u32x4_t lds_read_b128(unsigned addr)
-{
-    u32x4_t r;
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
-    return r;
-}
-
-// Transposing read: within each 16-lane block, lane i' addresses 4 channels of one key; lane i
-// receives channel i of 4 keys.
-template <int OFF>
-__device__ __forceinline__ u32x2_t lds_read_tr16_b64(unsigned addr)
-{
-    u32x2_t r;
-    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
-    return r;
-}
-
-template <int N>
-__device__ __forceinline__ void lds_wait(u32x4_t &r)
-{
-    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(r) : "n"(N));
-}
-
-template <int N>
-__device__ __forceinline__ void lds_wait(u32x2_t &a, u32x2_t &b)
-{
-    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
-}
-
-template <int OFF>
-__device__ __forceinline__ float lds_read_f32(unsigned addr)
-{
-    float r;
-    asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
-    return r;
-}
-
-template <int N>
-__device__ __forceinline__ void lds_wait(float &r)
-{
-    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(r) : "n"(N));
-}
-
-__device__ __forceinline__ unsigned lds_addr(const void *p) { return (unsigned)(uintptr_t)MAGE_LDS_PTR(p); }
-
-template <int... I, class F>
-__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F &&f)
-{
-    (f(std::integral_constant<int, I>{}), ...);
-}
-
-template <int N, class F>
-__device__ __forceinline__ void static_for(F &&f)
-{
-    static_for_impl(std::make_integer_sequence<int, N>{}, f);
 }
 
 // Scores of one 64-key tile against the wavefront's 32 query rows: two 32-key halves, K fragments

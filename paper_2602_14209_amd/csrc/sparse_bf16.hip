@@ -19,6 +19,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "lds_asm.hpp"
 #include "plan.hpp"
 #include "probe.hpp"
 
@@ -79,16 +80,16 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
     const u16 *vb = static_cast<const u16 *>(a.vblk) + z * a.seq_blk + (long long)h * D;
     const int32_t *idx = COMPACT ? nullptr : a.idx + z * a.seq_idx + (long long)h * a.nc;
 
-    // query fragment: row l16 of this row tile, channels 32*ks + 8*lg4 .. +7
+    // query fragment: row l16 of this row tile, channels 32*ks + 8*lg4 .. +7.  Branch-free (rows
+    // past R re-read the last row and are never stored): a branch here would end in a wait for
+    // these loads before the index entries are even requested.
     bf16x8_t qf[KS];
-    if (row < a.R) {
-        const int gl = row / a.B, qi = row - gl * a.B;
+    {
+        const int rq = row < a.R ? row : a.R - 1;
+        const int gl = rq / a.B, qi = rq - gl * a.B;
         const u16 *src = static_cast<const u16 *>(a.q) + z * a.seq_q + ((long long)qi * a.Hq + (long long)h * a.G + gl) * D + 8 * lg4;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) qf[ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(src + ks * 32));
-    } else {
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) qf[ks] = __builtin_bit_cast(bf16x8_t, make_uint4(0, 0, 0, 0));
     }
 
     f32x4_t o[DT];
@@ -121,12 +122,16 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
         // but a load in that pattern touches 64 separate 16-byte pieces per instruction.  Load
         // coalesced instead -- lane 4*r + c fetches that same piece, so each lane quad reads 64
         // contiguous bytes of one row -- and move the pieces to their MFMA lanes with a lane permute.
-        uint4 kraw[SP_TPW][KS];
+        // The loads are inline assembly so that the waits can be ours: behind the conditional last
+        // slot the compiler's own bookkeeping would wait for every outstanding load, V included.
+        u32x4_t kraw[SP_TPW][KS];
         auto load_k = [&](int j) {
             const int e = __shfl(enc[j], lane >> 2);
-            const u16 *src = e >= 0 ? kc + (long long)e * stride : kb + (long long)(-1 - e) * stride;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) kraw[j][ks] = *reinterpret_cast<const uint4 *>(src + ks * 32 + 8 * (lane & 3));
+            const u16 *src = (e >= 0 ? kc + (long long)e * stride : kb + (long long)(-1 - e) * stride) + 8 * (lane & 3);
+            static_for<KS>([&](auto S) {
+                constexpr int ks = decltype(S)::value;
+                kraw[j][ks] = global_load_b128<ks * 64>(src);
+            });
         };
         auto load_v = [&](int j) {
             unsigned char *dst = vlds + (j * SP_WAVES + wave) * TILE_BYTES;
@@ -146,27 +151,32 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
 #pragma unroll
         for (int j = 0; j < SP_TPW - 1; ++j) load_k(j);
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) kraw[SP_TPW - 1][ks] = make_uint4(0, 0, 0, 0);
+        for (int ks = 0; ks < KS; ++ks) kraw[SP_TPW - 1][ks] = u32x4_t{0u, 0u, 0u, 0u};
         if (my_tiles == SP_TPW) load_k(SP_TPW - 1);
 #pragma unroll
         for (int j = 0; j < SP_TPW - 1; ++j) load_v(j);
         if (my_tiles == SP_TPW) load_v(SP_TPW - 1);
 
         __builtin_amdgcn_sched_barrier(0);     // keep every load ahead of the first MFMA (and its wait)
+        // K tile j has landed when at most this many younger loads are outstanding.  The counts assume
+        // that the conditional last slot was not issued; with it they only wait a little longer.
         bf16x8_t kf[SP_TPW][KS];
         {
             const int from = 4 * (4 * l16 + lg4);            // byte address of the source lane for ds_bpermute
-#pragma unroll
-            for (int j = 0; j < SP_TPW; ++j)
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    uint4 t;
+            static_for<SP_TPW>([&](auto J) {
+                constexpr int j = decltype(J)::value;
+                constexpr int younger = (j < SP_TPW - 1 ? (SP_TPW - 2 - j) * KS : 0) + (SP_TPW - 1) * VLOADS;
+                static_for<KS>([&](auto S) {
+                    constexpr int ks = decltype(S)::value;
+                    vm_wait<younger + (j < SP_TPW - 1 ? KS - 1 - ks : 0)>(kraw[j][ks]);
+                    u32x4_t t;
                     t.x = __builtin_amdgcn_ds_bpermute(from, kraw[j][ks].x);
                     t.y = __builtin_amdgcn_ds_bpermute(from, kraw[j][ks].y);
                     t.z = __builtin_amdgcn_ds_bpermute(from, kraw[j][ks].z);
                     t.w = __builtin_amdgcn_ds_bpermute(from, kraw[j][ks].w);
                     kf[j][ks] = __builtin_bit_cast(bf16x8_t, t);
-                }
+                });
+            });
         }
         MAGE_PROBE_AT(1);
         // ---- scores: sc[j][v] = S^T(key 4*lg4 + v of tile j, query row l16) ----
@@ -206,13 +216,24 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
 
         MAGE_PROBE_AT(2);
         // ---- O^T += V^T P^T, 32 key positions (two tiles) per MFMA ----
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // this wavefront's V tiles are in LDS
+        // V tiles are consumed as they land: before the MFMAs of tiles 2s and 2s+1 the wavefront
+        // waits only until its direct loads of those tiles are done (loads retire in issue order).
         MAGE_PROBE_AT(3);
+        // V^T fragments by transposing LDS reads (inline assembly, see lds_asm.hpp), kPre O^T tiles
+        // ahead of the MFMA that consumes them.  The swizzle and the O^T tile both act on address
+        // bits 4..7 only: address = (lane constant + compile-time slot offset) ^ (dt << 5).
         const int jj = l16 >> 2, q = l16 & 3;
         const int vr = 4 * lg4 + jj;                          // tile row this lane addresses in a transposing read
-#pragma unroll
-        for (int s = 0; s < (SP_TPW + 1) / 2; ++s) {
-            if (2 * s < my_tiles) {   // uniform; after the only wait of the pass
+        const unsigned vbase = (lds_addr(vlds) + wave * TILE_BYTES + vr * ROW_BYTES + 8 * (q & 1)) |
+                               ((((q >> 1) ^ sp_swz(vr)) & (CH - 1)) << 4);
+        constexpr int kPre = DT < 4 ? DT : 4;
+        auto pv = [&](auto SLOTS) {     // SLOTS: tile slots this wavefront issued V loads for
+          constexpr int issued = decltype(SLOTS)::value * VLOADS;
+          static_for<(SP_TPW + 1) / 2>([&](auto SI) {
+            constexpr int s = decltype(SI)::value;
+            if (2 * s < my_tiles) {   // uniform
+                constexpr int need = (2 * s + 2) * VLOADS < issued ? (2 * s + 2) * VLOADS : issued;
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"(issued - need) : "memory");
                 bf16x8_t pf;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -220,19 +241,31 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
                     pf[4 + e] = (2 * s + 1 < SP_TPW) ? (__bf16)sc[2 * s + 1 < SP_TPW ? 2 * s + 1 : 0][e] : (__bf16)0.f;
                 }
                 // a missing second tile contributes zeros through P; its slot repeats a real tile
-                const int ja = 2 * s, jb = (2 * s + 1 < SP_TPW) ? 2 * s + 1 : 2 * s;   // constants after unrolling
-                const unsigned char *ta = vlds + (ja * SP_WAVES + wave) * TILE_BYTES + vr * ROW_BYTES + 8 * (q & 1);
-                const unsigned char *tb = vlds + (jb * SP_WAVES + wave) * TILE_BYTES + vr * ROW_BYTES + 8 * (q & 1);
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt) {
-                    const int chunk = ((2 * dt + (q >> 1)) ^ sp_swz(vr)) & (CH - 1);
-                    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t *)(ta + chunk * 16));
-                    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t *)(tb + chunk * 16));
-                    const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                constexpr int ja = 2 * s, jb = (2 * s + 1 < SP_TPW) ? 2 * s + 1 : 2 * s;
+                constexpr int offa = ja * SP_WAVES * TILE_BYTES, offb = jb * SP_WAVES * TILE_BYTES;
+                u32x2_t lo[DT], hi[DT];
+                static_for<kPre>([&](auto T) {
+                    constexpr int dt = decltype(T)::value;
+                    lo[dt] = lds_read_tr16_b64<0>((vbase + offa) ^ (unsigned)(dt << 5));
+                    hi[dt] = lds_read_tr16_b64<0>((vbase + offb) ^ (unsigned)(dt << 5));
+                });
+                static_for<DT>([&](auto T) {
+                    constexpr int dt = decltype(T)::value;
+                    // younger reads outstanding behind this pair: the pairs dt+1 .. min(dt+kPre, DT)-1
+                    constexpr int younger = ((dt + kPre < DT ? dt + kPre : DT) - dt - 1) * 2;
+                    lds_wait<younger>(lo[dt], hi[dt]);
+                    const u32x4_t both = {lo[dt][0], lo[dt][1], hi[dt][0], hi[dt][1]};
                     o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, both), pf, o[dt], 0, 0, 0);
-                }
+                    if constexpr (dt + kPre < DT) {
+                        lo[dt + kPre] = lds_read_tr16_b64<0>((vbase + offa) ^ (unsigned)((dt + kPre) << 5));
+                        hi[dt + kPre] = lds_read_tr16_b64<0>((vbase + offb) ^ (unsigned)((dt + kPre) << 5));
+                    }
+                });
             }
-        }
+          });
+        };
+        pv(std::integral_constant<int, SP_TPW - 1>{});       // counts without the conditional last slot: never too lax
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // slots past this wavefront's last tile were loaded too
     }
 
     MAGE_PROBE_AT(4);
