@@ -125,8 +125,18 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
         // The loads are inline assembly so that the waits can be ours: behind the conditional last
         // slot the compiler's own bookkeeping would wait for every outstanding load, V included.
         u32x4_t kraw[SP_TPW][KS];
+        // every lane permute of the issue phase first, in one batch: interleaved with the loads, each
+        // load would wait for its own permute (a dependent LDS round trip per load)
+        int ek[SP_TPW], ev[SP_TPW][VLOADS];
+#pragma unroll
+        for (int j = 0; j < SP_TPW; ++j) {
+            ek[j] = __shfl(enc[j], lane >> 2);
+#pragma unroll
+            for (int n = 0; n < VLOADS; ++n) ev[j][n] = __shfl(enc[j], n * RPL + lane / CH);
+        }
+        __builtin_amdgcn_sched_barrier(0);
         auto load_k = [&](int j) {
-            const int e = __shfl(enc[j], lane >> 2);
+            const int e = ek[j];
             const u16 *src = (e >= 0 ? kc + (long long)e * stride : kb + (long long)(-1 - e) * stride) + 8 * (lane & 3);
             static_for<KS>([&](auto S) {
                 constexpr int ks = decltype(S)::value;
@@ -138,7 +148,7 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
 #pragma unroll
             for (int n = 0; n < VLOADS; ++n) {
                 const int r = n * RPL + lane / CH;                           // tile row this lane fetches
-                const int e = __shfl(enc[j], r);
+                const int e = ev[j][n];
                 const u16 *src = e >= 0 ? vc + (long long)e * stride : vb + (long long)(-1 - e) * stride;
                 const int chunk = (lane % CH) ^ (sp_swz(r) & (CH - 1));
                 __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + chunk * 8),
