@@ -62,6 +62,13 @@ def test_c0_tiny_fp32(oracle_mod):
     ("s8", "f32", 8, 1, 64, 129, 16, 129),          # 128 rows: two fp32 row groups, k = L
     ("s9", "f32", 2, 2, 64, 31, 1, 5),
     ("s10", "bf16", 16, 2, 128, 2048, 48, 512),     # G*B = 384 > 256: row groups (no select)
+    ("s11", "bf16", 4, 2, 128, 1, 32, 1),           # one cached key
+    ("s12", "bf16", 4, 2, 128, 64, 32, 64),         # exactly one tile
+    ("s13", "bf16", 4, 2, 128, 65, 32, 7),          # second tile holds one key: its upper half is all padding
+    ("s14", "bf16", 8, 2, 64, 97, 16, 33),          # second tile holds 33 keys: one key in the upper half
+    ("s15", "bf16", 1, 1, 128, 300, 1, 10),         # a single query row
+    ("s16", "bf16", 12, 2, 128, 5000, 32, 300),     # G*B = 192: two row groups in attention, 8 wavefronts in the column sums
+    ("s17", "bf16", 8, 8, 64, 20000, 32, 1500),     # k + B > 640 key positions: several passes of the sparse kernel
 ])
 def test_small_shapes(oracle_mod, case):
     name, dtype, Hq, Hkv, d, L, B, k = case
