@@ -107,16 +107,24 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
         // ---- issue every load of the pass, branch-free (a branch would make the compiler wait
         // for all outstanding loads at its join).  A tile slot j >= my_tiles repeats the last
         // real tile's rows into its own (unused) LDS slot; its scores are masked below. ----
-        // enc: source row of key position tile*16 + l16 (cache row >= 0, block row r as -1-r)
-        int tile_of[SP_TPW], enc[SP_TPW];
-#pragma unroll
-        for (int j = 0; j < SP_TPW; ++j) {
-            tile_of[j] = first + SP_WAVES * (j < my_tiles ? j : my_tiles - 1);
-            int p = tile_of[j] * SP_KT + l16;
+        // src_row(tile row): source of key position tile*16 + row (cache row >= 0, block row r as
+        // -1-r).  Every lane reads the index entries of exactly the rows it will fetch -- row
+        // (lane / 4) for its K pieces, rows n*RPL + lane / CH for its V loads -- with all those small
+        // loads in flight at once; they hit the same few cache lines.
+        int tile_of[SP_TPW], ek[SP_TPW], ev[SP_TPW][VLOADS];
+        auto src_row = [&](int tile, int r) {
+            int p = tile * SP_KT + r;
             p = p < n_keys ? p : n_keys - 1;                // padding positions re-read the last key (masked below)
             const int pc = p < (int)a.nc ? p : (int)a.nc - 1;
             const int ci = COMPACT ? pc : idx[pc];
-            enc[j] = p < (int)a.nc ? ci : -1 - (p - (int)a.nc);
+            return p < (int)a.nc ? ci : -1 - (p - (int)a.nc);
+        };
+#pragma unroll
+        for (int j = 0; j < SP_TPW; ++j) {
+            tile_of[j] = first + SP_WAVES * (j < my_tiles ? j : my_tiles - 1);
+            ek[j] = src_row(tile_of[j], lane >> 2);
+#pragma unroll
+            for (int n = 0; n < VLOADS; ++n) ev[j][n] = src_row(tile_of[j], n * RPL + lane / CH);
         }
         // K fragments.  The MFMA wants lane (16*c + r) to hold channels [32*ks + 8*c, +8) of tile row r,
         // but a load in that pattern touches 64 separate 16-byte pieces per instruction.  Load
@@ -125,16 +133,7 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
         // The loads are inline assembly so that the waits can be ours: behind the conditional last
         // slot the compiler's own bookkeeping would wait for every outstanding load, V included.
         u32x4_t kraw[SP_TPW][KS];
-        // every lane permute of the issue phase first, in one batch: interleaved with the loads, each
-        // load would wait for its own permute (a dependent LDS round trip per load)
-        int ek[SP_TPW], ev[SP_TPW][VLOADS];
-#pragma unroll
-        for (int j = 0; j < SP_TPW; ++j) {
-            ek[j] = __shfl(enc[j], lane >> 2);
-#pragma unroll
-            for (int n = 0; n < VLOADS; ++n) ev[j][n] = __shfl(enc[j], n * RPL + lane / CH);
-        }
-        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_sched_barrier(0);     // every index entry is requested before the first row
         auto load_k = [&](int j) {
             const int e = ek[j];
             const u16 *src = (e >= 0 ? kc + (long long)e * stride : kb + (long long)(-1 - e) * stride) + 8 * (lane & 3);
