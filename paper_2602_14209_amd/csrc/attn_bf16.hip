@@ -578,40 +578,30 @@ void attn_bf16_kernel(const KernelArgs a)
     }
 
     // Output.  O^T register (dt, v) holds channel d = dt*32 + 8*(v/4) + 4*lg + v%4 of query row
-    // `row`.  Every wavefront transposes its 32 rows x D/2 channels through a private LDS region
-    // and writes whole half rows (16 bytes per lane, consecutive lanes on consecutive addresses).
-    constexpr int LPR = D / 8;          // lanes per half row
-    constexpr int RPS = 64 / LPR;       // rows per store instruction
+    // `row`: every lane owns runs of 4 consecutive channels (16 bytes), and the two lane halves
+    // of a row together 32 consecutive bytes, which the L2 merges into full lines.  Written straight
+    // from the registers: a transposition through LDS into whole rows costs more time (two more LDS
+    // passes and a barrier at the end of every workgroup) than the narrower stores do.
     const bool direct = a.n_split == 1;
     const float inv = direct ? 1.f / l_tot : 1.f;
-    float *stage = reinterpret_cast<float *>(smem) + wave * 32 * HOST;
     auto put_out = [&](auto OWN) {
         constexpr int o0 = decltype(OWN)::value;
+        if (row >= a.R) return;
+        float *dst;
+        if (direct) {
+            const int gl = row / a.B, qi = row - gl * a.B;
+            dst = a.out + z * a.seq_out + ((long long)qi * a.Hq + (long long)h * a.G + gl) * D;
+        } else {
+            dst = a.part_o + (((long long)h * a.n_split + split) * a.rpad + row) * D;
+        }
 #pragma unroll
         for (int i = 0; i < HDT; ++i)
 #pragma unroll
             for (int v4 = 0; v4 < 4; ++v4) {
                 const f32x4_t val = {o[o0 + i][4 * v4] * inv, o[o0 + i][4 * v4 + 1] * inv, o[o0 + i][4 * v4 + 2] * inv, o[o0 + i][4 * v4 + 3] * inv};
-                *reinterpret_cast<f32x4_t *>(stage + l32 * HOST + i * 32 + 8 * v4 + 4 * lg) = val;
+                *reinterpret_cast<f32x4_t *>(dst + (o0 + i) * 32 + 8 * v4 + 4 * lg) = val;
             }
-#pragma unroll
-        for (int it = 0; it < 32 / RPS; ++it) {
-            const int rr = it * RPS + lane / LPR, col = (lane % LPR) * 4;
-            const f32x4_t val = *reinterpret_cast<const f32x4_t *>(stage + rr * HOST + col);
-            const int orow = row0 + rr;
-            if (orow < a.R) {
-                float *dst;
-                if (direct) {
-                    const int gl = orow / a.B, qi = orow - gl * a.B;
-                    dst = a.out + z * a.seq_out + ((long long)qi * a.Hq + (long long)h * a.G + gl) * D;
-                } else {
-                    dst = a.part_o + (((long long)h * a.n_split + split) * a.rpad + orow) * D;
-                }
-                *reinterpret_cast<f32x4_t *>(dst + o0 * 32 + col) = val;
-            }
-        }
     };
-    __syncthreads();                    // the exchange area has been read
     if (wave_active) {
         if (kh == 0) put_out(std::integral_constant<int, 0>{});
         else put_out(std::integral_constant<int, HDT>{});
