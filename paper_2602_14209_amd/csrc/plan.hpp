@@ -18,8 +18,8 @@ constexpr int kF32Tile = 32;    // keys per LDS tile, fp32 vector path
 constexpr int kF32Rows = 64;    // query rows per workgroup, fp32 vector path
 constexpr int kTargetWorkgroups = 512;   // fp32 vector path: 2 per CU on 256 CUs
 constexpr int kBf16Workgroups = 256;     // MFMA path: one 8-wavefront workgroup per CU (its tile ring fills the LDS)
-constexpr int kStatsWorkgroups = 512;    // MFMA row-statistics pass: two workgroups per CU
-constexpr int kSelectWorkgroups = 2048;  // column-sum pass (and both fp32 selection passes): 8 per CU
+constexpr int kStatsWorkgroups = 512;    // MFMA selection passes (row statistics, column sums): two per CU
+constexpr int kSelectWorkgroups = 2048;  // fp32 selection passes: 8 per CU
 
 struct SplitPlan {
     int R;            // query rows sharing one KV head: G*B
@@ -81,20 +81,13 @@ inline SplitPlan plan_stats(const mage_shape &s)
 }
 
 // Selection, second pass (column sums).  The MFMA kernel parks the sums of up to kColsumTiles tiles
-// in LDS and writes them out together, so its splits are at most that long.
+// in LDS and writes them out together.  Like the statistics pass it wants long splits (every
+// workgroup pays a pipeline fill) and a power-of-two number of them.
 constexpr int kColsumTiles = 8;
 constexpr int kGroupKeys = 16;           // keys per group maximum handed from the column sums to the top-k filter
 inline SplitPlan plan_colsum(const mage_shape &s)
 {
-    SplitPlan p = plan_dense(s, kSelectWorkgroups);
-    if (s.dtype == MAGE_BF16 && p.kps > kColsumTiles * p.tile) {
-        const int64_t tiles = (s.L + p.tile - 1) / p.tile;
-        p.kps = kColsumTiles * p.tile;
-        p.n_split = (int)((tiles + kColsumTiles - 1) / kColsumTiles);
-        p.n_cyc = p.n_split;
-        p.blk_split = p.n_split - 1;
-    }
-    return p;
+    return plan_dense(s, s.dtype == MAGE_BF16 ? kStatsWorkgroups : kSelectWorkgroups);
 }
 
 // Sparse step: k gathered cache keys, in-block keys in a split of their own when k is large
