@@ -12,4 +12,8 @@ from .mage_oracle import (  # noqa: F401
     exact_attn,
     sparse_attn,
     compact,
+    page_summary,
+    quest_probs,
+    quest_select,
+    overlap,
 )

@@ -298,3 +298,157 @@ int mage_oracle_compact(int Hkv, int d, int64_t L, int k, const float *src, cons
         }
     return 0;
 }
+
+/* ------------------------------------------------------------------------------------------
+ * Second workload: a Quest-style page estimator under per-block selection, and the two
+ * set-overlap metrics the paper measures estimators with.
+ *
+ * Readings taken here (the paper describes Quest in one sentence and never says how its page
+ * scores enter Eq. 2):
+ *   - a page is a run of p consecutive cache positions of one KV head (the last page may be
+ *     shorter); its summary is the per-channel maximum and minimum of its key rows
+ *     (Sec. 2, "Methods for AR LLMs");
+ *   - the page score of a query is the sign-aware upper bound on q.k over the page,
+ *     sum_c max(q_c Kmax_c, q_c Kmin_c) (same passage);
+ *   - the estimated score of position j is what the exact score becomes when every logit is
+ *     replaced by the bound of its page: softmax over the L prefix positions of
+ *     bound(page(j)) / sqrt(d).  Eq. 2 (per-block form) then averages these over the G heads and
+ *     B tokens and takes Top-k exactly as for the exact scores, so with p = 1 the estimator IS
+ *     the oracle;
+ *   - ties (all positions of a page tie) go to the smaller index, as everywhere else.
+ * ------------------------------------------------------------------------------------------ */
+
+/*
+ * Page summaries (Sec. 2, Quest): kmax[P,h,c] = max_j K[j,h,c], kmin likewise, j over page P =
+ * [P*p, min((P+1)*p, L)).  kc [L,Hkv,d]; kmax, kmin [ceil(L/p),Hkv,d].
+ */
+int mage_oracle_page_summary(int Hkv, int d, int64_t L, int p, const float *kc, float *kmax, float *kmin)
+{
+    if (Hkv <= 0 || d <= 0 || L <= 0 || p <= 0 || !kc || !kmax || !kmin)
+        return -1;
+    const int64_t np = (L + p - 1) / p;
+    for (int64_t P = 0; P < np; ++P)
+        for (int h = 0; h < Hkv; ++h)
+            for (int c = 0; c < d; ++c) {
+                float mx = -INFINITY, mn = INFINITY;
+                for (int64_t j = P * p; j < (P + 1) * p && j < L; ++j) {
+                    const float v = kc[((size_t)j * Hkv + h) * d + c];
+                    if (v > mx) mx = v;
+                    if (v < mn) mn = v;
+                }
+                kmax[((size_t)P * Hkv + h) * d + c] = mx;
+                kmin[((size_t)P * Hkv + h) * d + c] = mn;
+            }
+    return 0;
+}
+
+/* sign-aware upper bound of q.k over a page: sum_c max(q_c Kmax_c, q_c Kmin_c) (Sec. 2, Quest) */
+static double page_bound(const float *qrow, const float *mx, const float *mn, int d)
+{
+    double acc = 0.0;
+    for (int c = 0; c < d; ++c) {
+        const double a = (double)qrow[c] * (double)mx[c], b = (double)qrow[c] * (double)mn[c];
+        acc += a > b ? a : b;
+    }
+    return acc;
+}
+
+/*
+ * Estimated per-block scores (Eq. 2, per-block form, with the exact score replaced by the
+ * estimator's):  s[g,q,j] = softmax_j( bound[g,q,page(j)] / sqrt(d) ),  j in [0,L);
+ * est[h,j] = 1/(GB) sum_{g in group(h)} sum_q s[g,q,j].
+ * q [B,Hq,d]; kmax, kmin [ceil(L/p),Hkv,d]; est [Hkv,L] fp64.
+ */
+int mage_oracle_quest_probs(int B, int Hq, int Hkv, int d, int64_t L, int p,
+                            const float *q, const float *kmax, const float *kmin, double *est)
+{
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || d <= 0 || L <= 0 || p <= 0 || Hq % Hkv != 0 || !q || !kmax || !kmin || !est)
+        return -1;
+    const int G = Hq / Hkv;
+    const int64_t np = (L + p - 1) / p;
+    for (size_t i = 0; i < (size_t)Hkv * (size_t)L; ++i)
+        est[i] = 0.0;
+    int fail = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int h = 0; h < Hkv; ++h) {
+        double *s = (double *)malloc(sizeof(double) * (size_t)L);
+        if (!s) {
+#pragma omp atomic write
+            fail = 1;
+            continue;
+        }
+        double *row = est + (size_t)h * (size_t)L;
+        for (int g = h * G; g < (h + 1) * G; ++g)
+            for (int qi = 0; qi < B; ++qi) {
+                const float *qrow = q + ((size_t)qi * Hq + g) * d;
+                double m = -INFINITY;
+                for (int64_t P = 0; P < np; ++P) {
+                    const double b = page_bound(qrow, kmax + ((size_t)P * Hkv + h) * d, kmin + ((size_t)P * Hkv + h) * d, d) /
+                                     sqrt((double)d);
+                    for (int64_t j = P * p; j < (P + 1) * p && j < L; ++j)
+                        s[j] = b;
+                    if (b > m) m = b;
+                }
+                double Z = 0.0;
+                for (int64_t j = 0; j < L; ++j)
+                    Z += exp(s[j] - m);
+                for (int64_t j = 0; j < L; ++j)
+                    row[j] += exp(s[j] - m) / Z;
+            }
+        for (int64_t j = 0; j < L; ++j)
+            row[j] /= (double)G * (double)B;
+        free(s);
+    }
+    return fail ? -1 : 0;
+}
+
+/*
+ * Estimated per-block KV subset (Eq. 2 with the estimator's scores): page summaries of kc ->
+ * quest_probs -> round to fp32 -> per-KV-head Top-k over the L positions.
+ * idx_out [Hkv,k]; est32_out [Hkv,L] (nullable).
+ */
+int mage_oracle_quest_select(int B, int Hq, int Hkv, int d, int64_t L, int p, int k,
+                             const float *q, const float *kc, int32_t *idx_out, float *est32_out)
+{
+    if (k <= 0 || (int64_t)k > L || !idx_out || Hkv <= 0 || d <= 0 || L <= 0 || p <= 0)
+        return -1;
+    const int64_t np = (L + p - 1) / p;
+    float *mx = (float *)malloc(sizeof(float) * (size_t)np * Hkv * d);
+    float *mn = (float *)malloc(sizeof(float) * (size_t)np * Hkv * d);
+    double *est = (double *)malloc(sizeof(double) * (size_t)Hkv * (size_t)L);
+    float *e32 = est32_out ? est32_out : (float *)malloc(sizeof(float) * (size_t)Hkv * (size_t)L);
+    int rc = (mx && mn && est && e32) ? mage_oracle_page_summary(Hkv, d, L, p, kc, mx, mn) : -1;
+    if (rc == 0)
+        rc = mage_oracle_quest_probs(B, Hq, Hkv, d, L, p, q, mx, mn, est);
+    if (rc == 0) {
+        for (size_t i = 0; i < (size_t)Hkv * (size_t)L; ++i)
+            e32[i] = (float)est[i];
+        for (int h = 0; h < Hkv && rc == 0; ++h)
+            rc = mage_oracle_topk(e32 + (size_t)h * (size_t)L, L, k, idx_out + (size_t)h * k);
+    }
+    free(mx);
+    free(mn);
+    free(est);
+    if (!est32_out) free(e32);
+    return rc;
+}
+
+/*
+ * |A intersect B| / k for two index sets of k distinct entries each, in any order: the ratio of
+ * Eq. 1 (estimation accuracy: evaluated subset against an oracle subset) and of Eq. 3 (recall of the
+ * step-1 oracle subset at a later noise level).  By direct comparison of every pair.
+ */
+double mage_oracle_overlap(int k, const int32_t *a, const int32_t *b)
+{
+    if (k <= 0 || !a || !b)
+        return -1.0;
+    int64_t common = 0;
+    for (int i = 0; i < k; ++i)
+        for (int j = 0; j < k; ++j)
+            if (a[i] == b[j]) {
+                ++common;
+                break;
+            }
+    return (double)common / (double)k;
+}
+

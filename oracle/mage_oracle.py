@@ -53,6 +53,16 @@ def _load():
             _f32p, _f32p, _f32p, _i32p, ctypes.c_int, _f32p, _f32p, ctypes.c_int, _f32p, _f32p]
         lib.mage_oracle_compact.restype = ctypes.c_int
         lib.mage_oracle_compact.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int, _f32p, _i32p, _f32p]
+        lib.mage_oracle_page_summary.restype = ctypes.c_int
+        lib.mage_oracle_page_summary.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int, _f32p, _f32p, _f32p]
+        lib.mage_oracle_quest_probs.restype = ctypes.c_int
+        lib.mage_oracle_quest_probs.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int64,
+                                                ctypes.c_int, _f32p, _f32p, _f32p, _f64p]
+        lib.mage_oracle_quest_select.restype = ctypes.c_int
+        lib.mage_oracle_quest_select.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int64,
+                                                 ctypes.c_int, ctypes.c_int, _f32p, _f32p, _i32p, _f32p]
+        lib.mage_oracle_overlap.restype = ctypes.c_double
+        lib.mage_oracle_overlap.argtypes = [ctypes.c_int, _i32p, _i32p]
         _lib = lib
     return _lib
 
@@ -171,3 +181,57 @@ def compact(cache, idx):
     if rc:
         raise RuntimeError("mage_oracle_compact failed")
     return out
+
+
+def page_summary(k_cache, p):
+    """Quest page summaries (Sec. 2): per-channel (max, min) of every run of p cache rows -> two [ceil(L/p),Hkv,d] arrays."""
+    k_cache = _f32(k_cache)
+    L, Hkv, d = k_cache.shape
+    n_pages = (L + p - 1) // p
+    kmax = np.empty((n_pages, Hkv, d), np.float32)
+    kmin = np.empty((n_pages, Hkv, d), np.float32)
+    rc = _load().mage_oracle_page_summary(Hkv, d, L, p, _ptr(k_cache, _f32p), _ptr(kmax, _f32p), _ptr(kmin, _f32p))
+    if rc:
+        raise RuntimeError("mage_oracle_page_summary failed")
+    return kmax, kmin
+
+
+def quest_probs(q, kmax, kmin, L, p):
+    """Per-block averaged estimated scores est[Hkv,L] (fp64): Eq. 2 with every logit replaced by its page's bound."""
+    q, kmax, kmin = _f32(q), _f32(kmax), _f32(kmin)
+    B, Hq, d = q.shape
+    n_pages, Hkv, d2 = kmax.shape
+    if d2 != d or kmin.shape != kmax.shape or n_pages != (L + p - 1) // p:
+        raise ValueError("page summary shape mismatch")
+    est = np.empty((Hkv, L), np.float64)
+    rc = _load().mage_oracle_quest_probs(B, Hq, Hkv, d, L, p, _ptr(q, _f32p), _ptr(kmax, _f32p), _ptr(kmin, _f32p),
+                                         _ptr(est, _f64p))
+    if rc:
+        raise RuntimeError("mage_oracle_quest_probs failed")
+    return est
+
+
+def quest_select(q, k_cache, p, k):
+    """Estimated per-block KV subset.  Returns dict(idx[Hkv,k] int32 ascending, est32[Hkv,L])."""
+    q, k_cache = _f32(q), _f32(k_cache)
+    B, Hq, Hkv, d, L = _dims(q, k_cache)
+    idx = np.empty((Hkv, k), np.int32)
+    e32 = np.empty((Hkv, L), np.float32)
+    rc = _load().mage_oracle_quest_select(B, Hq, Hkv, d, L, p, k, _ptr(q, _f32p), _ptr(k_cache, _f32p),
+                                          _ptr(idx, _i32p), _ptr(e32, _f32p))
+    if rc:
+        raise RuntimeError("mage_oracle_quest_select failed")
+    return {"idx": idx, "est32": e32}
+
+
+def overlap(a, b):
+    """|A intersect B| / k for two index sets of equal size k (Eq. 1, Eq. 3)."""
+    a = np.ascontiguousarray(a, dtype=np.int32).ravel()
+    b = np.ascontiguousarray(b, dtype=np.int32).ravel()
+    if a.shape != b.shape:
+        raise ValueError("sets must have the same size")
+    r = _load().mage_oracle_overlap(a.shape[0], _ptr(a, _i32p), _ptr(b, _i32p))
+    if r < 0:
+        raise RuntimeError("mage_oracle_overlap failed")
+    return float(r)
+

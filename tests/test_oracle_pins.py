@@ -343,3 +343,100 @@ def test_compact_is_fancy_indexing_and_commutes_with_attention(oracle_mod):
     assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
     with pytest.raises(RuntimeError):
         oracle_mod.compact(kc, np.full((Hkv, 2), L, np.int32))
+
+
+# --------------------------------------------------------------------------- page estimator (Sec. 2, Quest) and overlap metrics (Eq. 1, Eq. 3)
+def test_page_summary_is_blockwise_max_min(oracle_mod):
+    rng = _rng(40)
+    for L, p in ((48, 16), (50, 16), (7, 3), (5, 8), (33, 1)):
+        K = rng.standard_normal((L, 3, 8)).astype(np.float32)
+        kmax, kmin = oracle_mod.page_summary(K, p)
+        n_pages = -(-L // p)
+        assert kmax.shape == kmin.shape == (n_pages, 3, 8)
+        for P in range(n_pages):
+            rows = K[P * p:(P + 1) * p]
+            assert np.array_equal(kmax[P], rows.max(axis=0)) and np.array_equal(kmin[P], rows.min(axis=0)), (L, p, P)
+
+
+def test_quest_page_size_one_is_the_oracle_selection(oracle_mod):
+    """With one position per page the bound is q.k itself, so the estimator must be the exact selection, bit for bit."""
+    rng = _rng(41)
+    q = rng.standard_normal((5, 6, 16)).astype(np.float32)
+    K = rng.standard_normal((70, 2, 16)).astype(np.float32)
+    est = oracle_mod.quest_select(q, K, 1, 9)
+    ref = oracle_mod.select(q, K, 9)
+    assert np.array_equal(est["idx"], ref["idx"])
+    assert np.array_equal(est["est32"], ref["alpha32"])
+
+
+def test_quest_bound_is_exact_on_pages_of_identical_rows(oracle_mod):
+    """If all rows of a page are equal, max = min = the row and the bound equals q.k: the estimated
+    scores must be the exact averaged probabilities of the expanded cache (Eq. 2)."""
+    rng = _rng(42)
+    p, n_pages, Hkv, d = 4, 9, 2, 8
+    q = rng.standard_normal((3, 4, d)).astype(np.float32)
+    reps = rng.standard_normal((n_pages, Hkv, d)).astype(np.float32)
+    K = np.repeat(reps, p, axis=0)
+    kmax, kmin = oracle_mod.page_summary(K, p)
+    assert np.array_equal(kmax, reps) and np.array_equal(kmin, reps)
+    est = oracle_mod.quest_probs(q, kmax, kmin, n_pages * p, p)
+    _, alpha = oracle_mod.block_probs(q, K)
+    np.testing.assert_allclose(est, alpha, rtol=1e-12, atol=0)
+
+
+def test_quest_bound_is_sign_aware_closed_form(oracle_mod):
+    """d = 2, q = (1, -2); page A holds keys (3,5) and (-1,7): max = (3,7), min = (-1,5), so the bound is
+    max(3,-1) + max(-14,-10) = -7 (a bound from the maxima alone would give -11).  Page B holds (0,0) twice:
+    bound 0.  One query, one head: est(A) / est(B) = exp((-7 - 0) / sqrt(2))."""
+    q = np.array([[[1.0, -2.0]]], np.float32)
+    K = np.array([[[3.0, 5.0]], [[-1.0, 7.0]], [[0.0, 0.0]], [[0.0, 0.0]]], np.float32)
+    kmax, kmin = oracle_mod.page_summary(K, 2)
+    est = oracle_mod.quest_probs(q, kmax, kmin, 4, 2)[0]
+    assert est[0] == est[1] and est[2] == est[3]
+    np.testing.assert_allclose(est[0] / est[2], np.exp(-7.0 / np.sqrt(2.0)), rtol=1e-12)
+    np.testing.assert_allclose(est.sum(), 1.0, rtol=1e-12)
+
+
+def test_quest_bound_dominates_every_key_of_its_page(oracle_mod):
+    """The page score is an upper bound of q.k over the page: with one query and one head the estimated
+    probability of a position is >= Z_exact / Z_est times its exact probability, i.e. est * Z_est >= exp(logit)."""
+    rng = _rng(43)
+    L, p, d = 60, 6, 8
+    q = rng.standard_normal((1, 1, d)).astype(np.float32)
+    K = rng.standard_normal((L, 1, d)).astype(np.float32)
+    kmax, kmin = oracle_mod.page_summary(K, p)
+    est = oracle_mod.quest_probs(q, kmax, kmin, L, p)[0]
+    logits = (K[:, 0, :].astype(np.float64) @ q[0, 0].astype(np.float64)) / np.sqrt(d)
+    bounds = np.log(est) - np.log(est).max()                 # bound / sqrt(d) up to one additive constant ...
+    page_max = logits.reshape(-1, p).max(axis=1)
+    # ... which the page holding the largest bound fixes: there bound >= its own maximum logit
+    shift = np.maximum(q[0, 0] * kmax[:, 0, :], q[0, 0] * kmin[:, 0, :]).astype(np.float64).sum(axis=1).max() / np.sqrt(d)
+    assert np.all(bounds.reshape(-1, p)[:, 0] + shift >= page_max - 1e-9)
+    assert np.all(np.abs(est.reshape(-1, p) - est.reshape(-1, p)[:, :1]) == 0)      # one score per page
+
+
+def test_quest_select_takes_whole_pages_and_sums_to_one(oracle_mod):
+    rng = _rng(44)
+    L, p, k = 96, 8, 24
+    q = rng.standard_normal((4, 4, 16)).astype(np.float32)
+    K = rng.standard_normal((L, 2, 16)).astype(np.float32)
+    r = oracle_mod.quest_select(q, K, p, k)
+    np.testing.assert_allclose(r["est32"].sum(axis=1, dtype=np.float64), 1.0, atol=1e-5)
+    for h in range(2):
+        pages = np.unique(r["idx"][h] // p)
+        assert len(pages) == k // p
+        assert np.array_equal(r["idx"][h], (pages[:, None] * p + np.arange(p)[None, :]).ravel())
+        page_score = r["est32"][h].reshape(-1, p)[:, 0]
+        assert set(pages) == set(_brute_topk(page_score, k // p))
+
+
+def test_overlap_is_set_intersection_over_k(oracle_mod):
+    rng = _rng(45)
+    for k in (1, 5, 64):
+        a = rng.choice(300, k, replace=False).astype(np.int32)
+        b = rng.choice(300, k, replace=False).astype(np.int32)
+        want = len(set(a.tolist()) & set(b.tolist())) / k
+        assert oracle_mod.overlap(a, b) == want
+        assert oracle_mod.overlap(b, a) == want
+        assert oracle_mod.overlap(a, a[::-1].copy()) == 1.0
+        assert oracle_mod.overlap(a, (a + 1000).astype(np.int32)) == 0.0
