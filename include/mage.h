@@ -155,6 +155,51 @@ int mage_sparse_attn_batched(const mage_shape *shape, int n_seq, const void *q, 
                              const void *v_cache, const int32_t *idx, const void *k_blk, const void *v_blk,
                              float *out, float *lse_out, void *hip_stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Second workload: the lightweight estimator the paper compares against, under the same per-block
+ * selection (Sec. 2 "Methods for AR LLMs": Quest; Sec. 3.1, Eq. 2 per-block form), and the overlap
+ * ratio both of its accuracy measures are (Eq. 1, Eq. 3).
+ * ------------------------------------------------------------------------------------------- */
+
+/*
+ * Page summaries (Sec. 2, Quest): the cache of every KV head is cut into pages of p consecutive
+ * positions (the last one may be shorter) and each page is summarised by its per-channel maximum
+ * and minimum key:  summary[P,h,0,:] = max_j k_cache[j,h,:],  summary[P,h,1,:] = min_j,  j in page P.
+ * In:  k_cache [L,Hkv,d].  Out: summary [ceil(L/p),Hkv,2,d], same element type.  shape->k and
+ * shape->B are not used.  p >= 1.  No workspace.
+ */
+int mage_page_summary(const mage_shape *shape, int p, const void *k_cache, void *summary, void *hip_stream);
+
+/* Bytes of workspace mage_quest_select needs for `shape` and page size p (0 if invalid). */
+size_t mage_quest_workspace_bytes(const mage_shape *shape, int p);
+
+/*
+ * Estimated per-block KV subset (Eq. 2, per-block form, with the estimator's scores in place of the
+ * exact ones).  The page score of a query is the sign-aware upper bound on q.k over the page,
+ *   bound[g,q,P] = sum_c max(q[q,g,c] * Kmax[P,g/G,c], q[q,g,c] * Kmin[P,g/G,c]);
+ * the estimated score of position j is softmax over the L positions of bound[g,q,page(j)] / sqrt(d)
+ * (the exact score with every logit replaced by its page's bound; the paper does not spell this
+ * step out), averaged over the G heads of the group and the B tokens; the subset is its Top-k,
+ * equal scores to the smaller position -- i.e. the k/p best pages, whole.
+ * In:  q [B,Hq,d]; summary from mage_page_summary with the same p.
+ * Out: idx_out [Hkv,k] int32 ascending; est_out [Hkv,L/p] fp32, nullable (the averaged estimated
+ *      score of one position of each page).
+ * Needs MAGE_BF16, L % p == 0, k % p == 0 and B*G <= 256 (MAGE_ERR_UNSUPPORTED otherwise).
+ */
+int mage_quest_select(const mage_shape *shape, int p, const void *q, const void *summary,
+                      int32_t *idx_out, float *est_out,
+                      void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Overlap of index sets: out[i] = |A_(i mod a_rows) intersect B_i| / k for i in [0, n_rows).
+ * Eq. 1 (estimation accuracy of a subset against per-token oracle subsets: a = the evaluated
+ * subset [Hkv,k], a_rows = Hkv, b = oracle subsets [B,Hkv,k], n_rows = B*Hkv) and Eq. 3 (recall of
+ * the step-1 oracle subset at a later noise level: a_rows = n_rows = Hkv).
+ * In:  a [a_rows,k] int32, every row ascending and duplicate-free (as mage_select emits them);
+ *      b [n_rows,k] int32, rows duplicate-free, any order.  Out: out [n_rows] fp32.
+ */
+int mage_set_overlap(const int32_t *a, const int32_t *b, int n_rows, int k, int a_rows, float *out, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,8 @@ MAGE_OK = 0
 
 EXPORTS = ("mage_version", "mage_status_string", "mage_workspace_bytes",
            "mage_select", "mage_exact_attn", "mage_sparse_attn", "mage_step1",
-           "mage_compact", "mage_sparse_attn_compact", "mage_sparse_attn_batched")
+           "mage_compact", "mage_sparse_attn_compact", "mage_sparse_attn_batched",
+           "mage_page_summary", "mage_quest_workspace_bytes", "mage_quest_select", "mage_set_overlap")
 
 
 class mage_shape(ctypes.Structure):
@@ -70,6 +71,14 @@ def lib() -> ctypes.CDLL:
         L.mage_sparse_attn_batched.argtypes = [shp, ctypes.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.mage_step1.restype = ctypes.c_int
         L.mage_step1.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.mage_page_summary.restype = ctypes.c_int
+        L.mage_page_summary.argtypes = [shp, ctypes.c_int, vp, vp, vp]
+        L.mage_quest_workspace_bytes.restype = sz
+        L.mage_quest_workspace_bytes.argtypes = [shp, ctypes.c_int]
+        L.mage_quest_select.restype = ctypes.c_int
+        L.mage_quest_select.argtypes = [shp, ctypes.c_int, vp, vp, vp, vp, vp, sz, vp]
+        L.mage_set_overlap.restype = ctypes.c_int
+        L.mage_set_overlap.argtypes = [vp, vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp]
         _lib = L
     return _lib
 
@@ -160,6 +169,26 @@ def mage_sparse_attn_batched(shape: mage_shape, n_seq: int, q, k_cache, v_cache,
     return lib().mage_sparse_attn_batched(ctypes.byref(shape), int(n_seq), _ptr(q), _ptr(k_cache), _ptr(v_cache),
                                           _ptr(idx), _ptr(k_blk), _ptr(v_blk), _ptr(out), _ptr(lse_out),
                                           _stream(stream))
+
+
+def mage_page_summary(shape: mage_shape, p: int, k_cache, summary, stream=None) -> int:
+    """Per-page (max, min) key rows; see include/mage.h."""
+    return lib().mage_page_summary(ctypes.byref(shape), int(p), _ptr(k_cache), _ptr(summary), _stream(stream))
+
+
+def mage_quest_workspace_bytes(shape: mage_shape, p: int) -> int:
+    return int(lib().mage_quest_workspace_bytes(ctypes.byref(shape), int(p)))
+
+
+def mage_quest_select(shape: mage_shape, p: int, q, summary, idx_out, est_out, workspace, stream=None) -> int:
+    """Estimated per-block KV subset from page summaries; see include/mage.h."""
+    return lib().mage_quest_select(ctypes.byref(shape), int(p), _ptr(q), _ptr(summary), _ptr(idx_out), _ptr(est_out),
+                                   _ptr(workspace), _wsize(workspace), _stream(stream))
+
+
+def mage_set_overlap(a, b, n_rows: int, k: int, a_rows: int, out, stream=None) -> int:
+    """out[i] = |A_(i mod a_rows) & B_i| / k (Eq. 1, Eq. 3); see include/mage.h."""
+    return lib().mage_set_overlap(_ptr(a), _ptr(b), int(n_rows), int(k), int(a_rows), _ptr(out), _stream(stream))
 
 
 def check(status: int, where: str = "mage") -> None:

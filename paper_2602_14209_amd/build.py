@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmage.so")
-SOURCES = ["mage_api.hip", "attn_bf16.hip", "sparse_bf16.hip", "attn_f32.hip", "reduce.hip", "topk.hip"]
+SOURCES = ["mage_api.hip", "attn_bf16.hip", "sparse_bf16.hip", "attn_f32.hip", "reduce.hip", "topk.hip", "quest.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 VALU ops

@@ -51,6 +51,7 @@ __device__ __forceinline__ bf16x8_t as_bf16x8(uint4 v) { return __builtin_bit_ca
 template <int D>
 __device__ __forceinline__ int swz(int r)
 {
+    if (D == 256) return r & 15;      // K-only tiles (page-summary rows): any bijection of the low row bits will do
     return D == 128 ? (((r & 3) << 2) | ((r >> 2) & 3)) : ((((r >> 1) & 1) << 2) | ((r >> 2) & 3));
 }
 
@@ -154,6 +155,9 @@ __device__ __forceinline__ FragAddr frag_addr(int lane)
     return f;
 }
 
+template <int D, bool KEYS_AS_A>
+__device__ __forceinline__ void qk_half(unsigned ka, const bf16x8_t (&qf)[D / 16], f32x16_t &sc);
+
 // Scores of one 64-key tile against the wavefront's 32 query rows: two 32-key halves, K fragments
 // (key row kt*32 + l32, channels [16*ks + 8*lg, +8)) read KS deep ahead of the MFMA that uses them.
 // KEYS_AS_A: S^T = K Q^T (a lane holds 16 keys of one query row); otherwise S = Q K^T.
@@ -162,6 +166,11 @@ __device__ __forceinline__ void qk_tile(unsigned ka, const bf16x8_t (&qf)[D / 16
 {
     constexpr int KS = D / 16;
     constexpr int HALF = 32 * TileGeom<D>::ROW_BYTES;
+    if constexpr (KS > 8) {            // more fragments than the LDS counter can keep apart: one half after the other
+        qk_half<D, KEYS_AS_A>(ka, qf, sc[0]);
+        qk_half<D, KEYS_AS_A>(ka + HALF, qf, sc[1]);
+        return;
+    }
     u32x4_t k0[KS], k1[KS];
 #pragma unroll
     for (int v = 0; v < 16; ++v) sc[0][v] = sc[1][v] = 0.f;
@@ -186,24 +195,30 @@ __device__ __forceinline__ void qk_tile(unsigned ka, const bf16x8_t (&qf)[D / 16
     });
 }
 
-// The same for one 32-key half of a tile (key row l32 of the half that `ka` points at).
+// The same for one 32-key half of a tile (key row l32 of the half that `ka` points at), at most 8
+// fragment reads in flight at a time.
 template <int D, bool KEYS_AS_A>
 __device__ __forceinline__ void qk_half(unsigned ka, const bf16x8_t (&qf)[D / 16], f32x16_t &sc)
 {
     constexpr int KS = D / 16;
-    u32x4_t k0[KS];
+    constexpr int KB = KS < 8 ? KS : 8;
+    static_assert(KS % KB == 0, "k-steps come in whole batches");
 #pragma unroll
     for (int v = 0; v < 16; ++v) sc[v] = 0.f;
-    static_for<KS>([&](auto S) {
-        constexpr int ks = decltype(S)::value;
-        k0[ks] = lds_read_b128<0>(ka ^ (unsigned)(ks << 5));
-    });
-    static_for<KS>([&](auto S) {
-        constexpr int ks = decltype(S)::value;
-        lds_wait<KS - 1 - ks>(k0[ks]);
-        const bf16x8_t kf = __builtin_bit_cast(bf16x8_t, k0[ks]);
-        sc = KEYS_AS_A ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sc, 0, 0, 0)
-                       : __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[ks], kf, sc, 0, 0, 0);
+    static_for<KS / KB>([&](auto BI) {
+        constexpr int k0i = decltype(BI)::value * KB;
+        u32x4_t k0[KB];
+        static_for<KB>([&](auto S) {
+            constexpr int i = decltype(S)::value;
+            k0[i] = lds_read_b128<0>(ka ^ (unsigned)((k0i + i) << 5));
+        });
+        static_for<KB>([&](auto S) {
+            constexpr int i = decltype(S)::value;
+            lds_wait<KB - 1 - i>(k0[i]);
+            const bf16x8_t kf = __builtin_bit_cast(bf16x8_t, k0[i]);
+            sc = KEYS_AS_A ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[k0i + i], sc, 0, 0, 0)
+                           : __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[k0i + i], kf, sc, 0, 0, 0);
+        });
     });
 }
 
@@ -279,7 +294,7 @@ struct AttnGeom {
     // registers and runs two workgroups per CU with two tiles in flight each.
     static constexpr int NBUF = WITH_V ? 4 : 3;
     static constexpr int LPT = (TileGeom<D>::LOADS / kAttnWaves) * (WITH_V ? 2 : 1);            // loads one wavefront issues per tile
-    static constexpr int MAX_WAVES_PER_SIMD = WITH_V ? 2 : 4;
+    static constexpr int MAX_WAVES_PER_SIMD = (WITH_V || D > 128) ? 2 : 4;
 };
 
 template <int D, int MODE, bool GATHER>
@@ -810,6 +825,7 @@ hipError_t bf16_stats(const KernelArgs &a, int d, int row_groups, hipStream_t st
 {
     if (d == 128) return launch_attn<128, MODE_STATS, false>(a, row_groups, a.n_split, stream);
     if (d == 64) return launch_attn<64, MODE_STATS, false>(a, row_groups, a.n_split, stream);
+    if (d == 256) return launch_attn<256, MODE_STATS, false>(a, row_groups, a.n_split, stream);   // page-summary rows [max | min] of d = 128
     return hipErrorInvalidValue;
 }
 
@@ -819,6 +835,8 @@ hipError_t bf16_colsum(const KernelArgs &a, int d, int waves, hipStream_t stream
     if (d == 128 && waves == 8) return launch_colsum<128, 8>(a, stream);
     if (d == 64 && waves == 4) return launch_colsum<64, 4>(a, stream);
     if (d == 64 && waves == 8) return launch_colsum<64, 8>(a, stream);
+    if (d == 256 && waves == 4) return launch_colsum<256, 4>(a, stream);
+    if (d == 256 && waves == 8) return launch_colsum<256, 8>(a, stream);
     return hipErrorInvalidValue;
 }
 

@@ -19,6 +19,10 @@ hipError_t f32_stats(const KernelArgs &a, int d, int row_groups, hipStream_t str
 hipError_t f32_colsum(const KernelArgs &a, int d, hipStream_t stream);
 hipError_t launch_combine(const KernelArgs &a, int d, hipStream_t stream);
 hipError_t launch_lse(const KernelArgs &a, float *lse2_out, hipStream_t stream);
+hipError_t launch_page_summary(const void *kc, void *out, long long L, int Hkv, int d, int p, bool bf16, hipStream_t stream);
+hipError_t launch_quest_query(const void *q, void *q2, long long rows, int d, hipStream_t stream);
+hipError_t launch_expand_pages(const int32_t *pages, int32_t *idx, int Hkv, int k, int p, hipStream_t stream);
+hipError_t launch_overlap(const int32_t *a, const int32_t *b, int n_rows, int k, int a_rows, float *out, hipStream_t stream);
 hipError_t launch_topk(const float *alpha, const float *group_max, int Hkv, long long L, int k, int32_t *idx_out, hipStream_t stream);
 }  // namespace mage
 
@@ -160,6 +164,58 @@ int run_sparse_bf16(const mage_shape *shape, bool compact, int n_seq, const void
     return MAGE_OK;
 }
 
+// The selection pipeline (row statistics, log-sum-exp, column sums, top-k) on a validated
+// geometry.  `scale_log2` = log2(e) times the factor on the logit; `key_weight`: every key stands for
+// that many positions of equal score (its probability is shared among them); shape->d may be 256
+// here (page-summary rows).
+int select_impl(const mage_shape *shape, float scale_log2, int key_weight, const void *q1, const void *k_cache,
+                int32_t *idx_out, float *alpha_out,
+                void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!q1 || !k_cache || !idx_out) return MAGE_ERR_NULL;
+    const SplitPlan p = plan_stats(*shape), pc = plan_colsum(*shape);
+    if (shape->dtype == MAGE_BF16 && p.rpad > 256) return MAGE_ERR_UNSUPPORTED;   // the column-sum pass keeps all rows of a head in one workgroup
+    if (!aligned16(q1) || !aligned16(k_cache) || !aligned16(workspace) || !aligned16(alpha_out)) return MAGE_ERR_ALIGN;
+    const SelectLayout lay = select_layout(*shape, p);
+    if (!workspace || workspace_bytes < lay.bytes) return MAGE_ERR_WORKSPACE;
+
+    char *w = static_cast<char *>(workspace);
+    KernelArgs a = base_args(*shape, p);
+    a.scale_log2 = scale_log2;
+    a.inv_rows /= (float)key_weight;
+    a.q = q1;
+    a.kc = k_cache;
+    a.vc = k_cache;
+    a.kblk = k_cache;
+    a.vblk = k_cache;
+    a.n_blk = 0;
+    a.blk_split = -1;
+    a.nc = shape->L;
+    a.part_m = reinterpret_cast<float *>(w + lay.part_m);
+    a.part_l = reinterpret_cast<float *>(w + lay.part_l);
+    float *lse2 = reinterpret_cast<float *>(w + lay.lse2);
+    a.lse2 = lse2;
+    a.alpha = alpha_out ? alpha_out : reinterpret_cast<float *>(w + lay.alpha);
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const bool bf = shape->dtype == MAGE_BF16;
+    a.gmax = bf ? reinterpret_cast<float *>(w + lay.gmax) : nullptr;   // the MFMA column sums also leave group maxima for the top-k filter
+    hipError_t e = bf ? bf16_stats(a, shape->d, p.row_groups, stream) : f32_stats(a, shape->d, p.row_groups, stream);
+    if (e != hipSuccess) return MAGE_ERR_HIP;
+    e = launch_lse(a, lse2, stream);
+    if (e != hipSuccess) return MAGE_ERR_HIP;
+    KernelArgs c = a;                                // the column sums have their own split of the keys
+    c.kps = pc.kps;
+    c.n_split = pc.n_split;
+    c.n_cyc = pc.n_cyc;
+    e = bf ? bf16_colsum(c, shape->d, pc.waves, stream) : f32_colsum(c, shape->d, stream);
+    if (e != hipSuccess) return MAGE_ERR_HIP;
+    e = launch_topk(a.alpha, a.gmax, shape->Hkv, shape->L, shape->k, idx_out, stream);
+    if (e != hipSuccess) return MAGE_ERR_HIP;
+    return MAGE_OK;
+}
+
+
 }  // namespace
 
 extern "C" {
@@ -198,47 +254,10 @@ int mage_select(const mage_shape *shape, const void *q1, const void *k_cache,
                 int32_t *idx_out, float *alpha_out,
                 void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    int rc = check_shape(shape, true);
+    const int rc = check_shape(shape, true);
     if (rc != MAGE_OK) return rc;
-    if (!q1 || !k_cache || !idx_out) return MAGE_ERR_NULL;
-    const SplitPlan p = plan_stats(*shape), pc = plan_colsum(*shape);
-    if (shape->dtype == MAGE_BF16 && p.rpad > 256) return MAGE_ERR_UNSUPPORTED;   // the column-sum pass keeps all rows of a head in one workgroup
-    if (!aligned16(q1) || !aligned16(k_cache) || !aligned16(workspace) || !aligned16(alpha_out)) return MAGE_ERR_ALIGN;
-    const SelectLayout lay = select_layout(*shape, p);
-    if (!workspace || workspace_bytes < lay.bytes) return MAGE_ERR_WORKSPACE;
-
-    char *w = static_cast<char *>(workspace);
-    KernelArgs a = base_args(*shape, p);
-    a.q = q1;
-    a.kc = k_cache;
-    a.vc = k_cache;
-    a.kblk = k_cache;
-    a.vblk = k_cache;
-    a.n_blk = 0;
-    a.blk_split = -1;
-    a.nc = shape->L;
-    a.part_m = reinterpret_cast<float *>(w + lay.part_m);
-    a.part_l = reinterpret_cast<float *>(w + lay.part_l);
-    float *lse2 = reinterpret_cast<float *>(w + lay.lse2);
-    a.lse2 = lse2;
-    a.alpha = alpha_out ? alpha_out : reinterpret_cast<float *>(w + lay.alpha);
-
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const bool bf = shape->dtype == MAGE_BF16;
-    a.gmax = bf ? reinterpret_cast<float *>(w + lay.gmax) : nullptr;   // the MFMA column sums also leave group maxima for the top-k filter
-    hipError_t e = bf ? bf16_stats(a, shape->d, p.row_groups, stream) : f32_stats(a, shape->d, p.row_groups, stream);
-    if (e != hipSuccess) return MAGE_ERR_HIP;
-    e = launch_lse(a, lse2, stream);
-    if (e != hipSuccess) return MAGE_ERR_HIP;
-    KernelArgs c = a;                                // the column sums have their own split of the keys
-    c.kps = pc.kps;
-    c.n_split = pc.n_split;
-    c.n_cyc = pc.n_cyc;
-    e = bf ? bf16_colsum(c, shape->d, pc.waves, stream) : f32_colsum(c, shape->d, stream);
-    if (e != hipSuccess) return MAGE_ERR_HIP;
-    e = launch_topk(a.alpha, a.gmax, shape->Hkv, shape->L, shape->k, idx_out, stream);
-    if (e != hipSuccess) return MAGE_ERR_HIP;
-    return MAGE_OK;
+    return select_impl(shape, (float)(1.4426950408889634 / sqrt((double)shape->d)), 1, q1, k_cache, idx_out, alpha_out,
+                       workspace, workspace_bytes, hip_stream);
 }
 
 int mage_step1(const mage_shape *shape, const void *q1, const void *k_cache, const void *v_cache,
@@ -353,6 +372,91 @@ int mage_sparse_attn_batched(const mage_shape *shape, int n_seq, const void *q, 
     if (n_seq <= 0 || n_seq > 65535) return MAGE_ERR_SHAPE;
     if (shape->dtype != MAGE_BF16) return MAGE_ERR_UNSUPPORTED;
     return run_sparse_bf16(shape, false, n_seq, q, k_cache, v_cache, idx, k_blk, v_blk, out, lse_out, hip_stream);
+}
+
+// ---- second workload: page estimator and overlap ratio ----
+namespace {
+
+// geometry of the scoring passes: pages as keys, [max | min] rows of length 2d, k/p pages to select
+int quest_shape(const mage_shape *shape, int p, mage_shape &s2)
+{
+    const int rc = check_shape(shape, true);
+    if (rc != MAGE_OK) return rc;
+    if (p <= 0) return MAGE_ERR_SHAPE;
+    if (shape->dtype != MAGE_BF16 || shape->L % p != 0 || shape->k % p != 0) return MAGE_ERR_UNSUPPORTED;
+    s2 = *shape;
+    s2.d = 2 * shape->d;
+    s2.L = shape->L / p;
+    s2.k = shape->k / p;
+    return MAGE_OK;
+}
+
+struct QuestLayout {
+    size_t q2, select, pages, bytes;
+};
+
+QuestLayout quest_layout(const mage_shape &shape, const mage_shape &s2)
+{
+    QuestLayout l{};
+    size_t off = 0;
+    l.q2 = off;     off += align_up((size_t)shape.B * shape.Hq * s2.d * 2, 256);
+    l.select = off; off += align_up(select_layout(s2, plan_stats(s2)).bytes, 256);
+    l.pages = off;  off += align_up((size_t)shape.Hkv * s2.k * sizeof(int32_t), 256);
+    l.bytes = off;
+    return l;
+}
+
+}  // namespace
+
+int mage_page_summary(const mage_shape *shape, int p, const void *k_cache, void *summary, void *hip_stream)
+{
+    const int rc = check_shape(shape, false);
+    if (rc != MAGE_OK) return rc;
+    if (p <= 0) return MAGE_ERR_SHAPE;
+    if (!k_cache || !summary) return MAGE_ERR_NULL;
+    if (!aligned16(k_cache) || !aligned16(summary)) return MAGE_ERR_ALIGN;
+    const hipError_t e = launch_page_summary(k_cache, summary, shape->L, shape->Hkv, shape->d, p, shape->dtype == MAGE_BF16,
+                                             static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MAGE_OK : MAGE_ERR_HIP;
+}
+
+size_t mage_quest_workspace_bytes(const mage_shape *shape, int p)
+{
+    mage_shape s2;
+    if (quest_shape(shape, p, s2) != MAGE_OK) return 0;
+    return quest_layout(*shape, s2).bytes;
+}
+
+int mage_quest_select(const mage_shape *shape, int p, const void *q, const void *summary,
+                      int32_t *idx_out, float *est_out,
+                      void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    mage_shape s2;
+    const int rc = quest_shape(shape, p, s2);
+    if (rc != MAGE_OK) return rc;
+    if (!q || !summary || !idx_out) return MAGE_ERR_NULL;
+    if (!aligned16(q) || !aligned16(summary) || !aligned16(workspace) || !aligned16(est_out)) return MAGE_ERR_ALIGN;
+    const QuestLayout lay = quest_layout(*shape, s2);
+    if (!workspace || workspace_bytes < lay.bytes) return MAGE_ERR_WORKSPACE;
+    char *w = static_cast<char *>(workspace);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    void *q2 = w + lay.q2;
+    int32_t *pages = reinterpret_cast<int32_t *>(w + lay.pages);
+    if (launch_quest_query(q, q2, (long long)shape->B * shape->Hq, shape->d, stream) != hipSuccess) return MAGE_ERR_HIP;
+    // the bound is scaled like a logit of the original head dimension
+    const int rs = select_impl(&s2, (float)(1.4426950408889634 / sqrt((double)shape->d)), p, q2, summary, pages, est_out,
+                               w + lay.select, lay.pages - lay.select, hip_stream);
+    if (rs != MAGE_OK) return rs;
+    if (launch_expand_pages(pages, idx_out, shape->Hkv, shape->k, p, stream) != hipSuccess) return MAGE_ERR_HIP;
+    return MAGE_OK;
+}
+
+int mage_set_overlap(const int32_t *a, const int32_t *b, int n_rows, int k, int a_rows, float *out, void *hip_stream)
+{
+    if (!a || !b || !out) return MAGE_ERR_NULL;
+    if (n_rows <= 0 || k <= 0 || a_rows <= 0 || a_rows > n_rows || n_rows > (1 << 24)) return MAGE_ERR_SHAPE;
+    const hipError_t e = launch_overlap(a, b, n_rows, k, a_rows, out, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MAGE_OK : MAGE_ERR_HIP;
 }
 
 }  // extern "C"

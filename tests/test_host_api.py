@@ -94,3 +94,31 @@ def test_null_alignment_and_workspace_errors():
     sf = mb.make_shape(32, 32, 8, 128, 4096, 512, "f32")
     assert L.mage_sparse_attn(ctypes.byref(sf), fake, fake, fake, fake, fake, fake, fake, None, fake, 16, None) == -4
     assert L.mage_sparse_attn(ctypes.byref(s), fake, fake, odd, fake, fake, fake, fake, None, None, 0, None) == -6
+
+
+def test_second_workload_argument_validation():
+    """Page estimator and overlap ratio: every argument error is reported before anything is launched."""
+    L = mb.lib()
+    fake = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1004)
+    big = 1 << 40
+    s = mb.make_shape(32, 32, 8, 128, 4096, 512, "bf16")
+    assert L.mage_page_summary(ctypes.byref(s), 0, fake, fake, None) == -2
+    assert L.mage_page_summary(ctypes.byref(s), 16, None, fake, None) == -1
+    assert L.mage_page_summary(ctypes.byref(s), 16, fake, odd, None) == -6
+    assert L.mage_page_summary(None, 16, fake, fake, None) == -1
+    assert mb.mage_quest_workspace_bytes(s, 16) > 0
+    assert mb.mage_quest_workspace_bytes(s, 0) == 0
+    assert mb.mage_quest_workspace_bytes(s, 24) == 0                       # L % p != 0
+    assert mb.mage_quest_workspace_bytes(mb.make_shape(32, 32, 8, 128, 4096, 500, "bf16"), 16) == 0   # k % p != 0
+    assert mb.mage_quest_workspace_bytes(mb.make_shape(32, 32, 8, 128, 4096, 512, "f32"), 16) == 0
+    assert L.mage_quest_select(ctypes.byref(s), 16, None, fake, fake, None, fake, big, None) == -1
+    assert L.mage_quest_select(ctypes.byref(s), 16, fake, fake, None, None, fake, big, None) == -1
+    assert L.mage_quest_select(ctypes.byref(s), 16, odd, fake, fake, None, fake, big, None) == -6
+    assert L.mage_quest_select(ctypes.byref(s), 16, fake, fake, fake, None, fake, 16, None) == -4
+    assert L.mage_quest_select(ctypes.byref(s), 24, fake, fake, fake, None, fake, big, None) == -3
+    assert L.mage_quest_select(ctypes.byref(s), -1, fake, fake, fake, None, fake, big, None) == -2
+    assert L.mage_set_overlap(None, fake, 4, 8, 4, fake, None) == -1
+    assert L.mage_set_overlap(fake, fake, 0, 8, 1, fake, None) == -2
+    assert L.mage_set_overlap(fake, fake, 4, 0, 4, fake, None) == -2
+    assert L.mage_set_overlap(fake, fake, 4, 8, 5, fake, None) == -2          # more `a` rows than rows
