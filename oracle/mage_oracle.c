@@ -27,6 +27,9 @@
  * G=B=1 special case, torch scaled_dot_product_attention, brute-force sort
  * top-k, closed forms (Q=0, all-equal keys, one-hot values, planted spike),
  * sum-to-one invariants, shift/permutation invariances, k=L == exact.
+ * The second workload at the end of this file (page estimator, set overlap) is pinned on numpy
+ * block max/min, on page size 1 being the exact selection, on pages of identical rows (bound
+ * exact), on a hand-computed sign-aware bound, and on python set intersection.
  */
 #include <math.h>
 #include <stdint.h>
