@@ -301,6 +301,20 @@ def second_workload(w, k, p, shape, layers, idx, ws_main, main_s, capture, time_
             main_s.synchronize()
             reuse.append(float(frac[0].mean()))
             est.append(float(frac[1].mean()))
+    # Eq. 1 proper: against the per-token oracle subsets of the late step (one B = 1 selection per token)
+    shape1 = mb.make_shape(1, w.Hq, w.Hkv, w.d, w.L, k, w.dtype)
+    ws1 = mb.alloc_workspace(shape1)
+    tok = torch.zeros((w.B, w.Hkv, k), dtype=torch.int32, device=dev)
+    acc = torch.zeros((2, w.B * w.Hkv), dtype=torch.float32, device=dev)
+    with torch.cuda.stream(main_s):
+        x = layers[0]
+        for qi in range(w.B):
+            mb.check(mb.mage_select(shape1, x["q"][t_late][qi:qi + 1], x["k_cache"], tok[qi], None, ws1, main_s), "mage_select")
+        quest(0, t_late)
+        mb.check(mb.mage_set_overlap(idx[0], tok, w.B * w.Hkv, k, w.Hkv, acc[0], main_s), "mage_set_overlap")
+        mb.check(mb.mage_set_overlap(idx_q, tok, w.B * w.Hkv, k, w.Hkv, acc[1], main_s), "mage_set_overlap")
+        main_s.synchronize()
+    est_acc_reuse, est_acc_pages = float(acc[0].mean()), float(acc[1].mean())
     esz = 2
     sum_bytes = w.L * w.Hkv * w.d * esz + n_pages * w.Hkv * 2 * w.d * esz
     quest_bytes = 2 * n_pages * w.Hkv * 2 * w.d * esz + 2 * n_pages * w.Hkv * 4 + 2 * w.B * w.Hq * w.d * esz + w.Hkv * k * 4
@@ -312,7 +326,10 @@ def second_workload(w, k, p, shape, layers, idx, ws_main, main_s, capture, time_
             "late_step": int(t_late) + 1,
             "recall_of_step1_exact_subset_at_late_step": round(sum(reuse) / len(reuse), 4),
             "accuracy_of_page_estimate_at_late_step": round(sum(est) / len(est), 4),
-            "note": "Eq. 3 / Eq. 1-style overlap with the late step's own exact per-block subset; synthetic queries "
+            "est_acc_eq1_of_step1_exact_subset": round(est_acc_reuse, 4),
+            "est_acc_eq1_of_page_estimate": round(est_acc_pages, 4),
+            "note": "recall/accuracy: overlap with the late step's own exact per-block subset (Eq. 3 form); est_acc_eq1: "
+                    "Eq. 1, mean over tokens and heads against per-token oracle subsets of layer 0; synthetic queries "
                     "(Q_t = Q_1 + 0.3 N(0,1)), not the paper's models"}
 
 
