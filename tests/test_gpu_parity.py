@@ -276,3 +276,21 @@ def test_batched_sparse_step(oracle_mod):
     for s in range(n_seq):
         o_ref, l_ref = oracle_mod.sparse_attn(xs[s]["q"][1], xs[s]["k_cache"], xs[s]["v_cache"], idx[s], xs[s]["k_blk"][1], xs[s]["v_blk"][1])
         check_out(out[s].cpu().numpy(), o_ref, lse[s].cpu().numpy(), l_ref, "bf16")
+
+
+@pytest.mark.parametrize("seed", list(range(12)))
+def test_seeded_random_geometries(oracle_mod, seed):
+    """Whole path (select, exact, fused step 1, sparse steps) on seeded random geometries inside the
+    supported ranges: odd lengths, every group size, both head dimensions, both element types."""
+    rng = np.random.default_rng(9000 + seed)
+    dtype = "bf16" if seed % 4 else "f32"
+    d = int(rng.choice([64, 128]))
+    Hkv = int(rng.integers(1, 4))
+    G = int(rng.choice([1, 2, 3, 4, 7, 8]))
+    B = int(rng.choice([1, 4, 16, 32]))
+    while G * B > 256:
+        G = max(1, G // 2)
+    L = int(rng.integers(1, 1200 if dtype == "f32" else 6000))
+    k = int(rng.integers(1, min(L, 700) + 1))
+    w = Workload(f"rnd{seed}", dtype, Hq=Hkv * G, Hkv=Hkv, d=d, L=L, B=B, ks=(k,), T=2, heavy_frac=0.02, heavy_scale=3.0)
+    _run_workload(oracle_mod, w, seed=9000 + seed)
