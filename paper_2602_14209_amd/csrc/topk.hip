@@ -8,6 +8,10 @@
 //     disjoint groups of elements is a lower bound of the k-th largest element, so only the few
 //     elements at or above it can belong to the set; a radix select over those candidates in LDS
 //     finds the k-th value and the ties to keep, and a bitmap walk emits the positions in order.
+//     The whole route is one chain of short dependent phases on a single workgroup, so its time is
+//     the sum of their latencies: every radix step has its own pre-zeroed histogram and two
+//     barriers, prefix sums inside a wavefront use lane-shift moves, and wavefront-uniform values
+//     travel through scalar registers rather than the LDS crossbar.
 //     The group maxima either come with the row (the column-sum pass leaves one per kGroupKeys
 //     consecutive keys; only the groups at or above the bound are then read at all) or are
 //     taken here over 8192 strided groups in a first sweep of the row.
@@ -31,32 +35,114 @@ constexpr int TK_GROUPS = TK_THREADS * TK_SLOTS;     // 8192
 constexpr int TK_CAND = 4096;                        // candidate capacity of the filter route
 constexpr int TK_FILTER_MAX_K = 2048;
 
+// Inclusive prefix sum over the 64 lanes of a wavefront with data-parallel-primitive moves
+// (row shifts inside rows of 16 lanes, then the row broadcasts of the gfx9 family): eight
+// vector-ALU instructions instead of six trips through the LDS crossbar.
+__device__ __forceinline__ uint32_t wave_scan_incl(uint32_t x)
+{
+    constexpr int ROW_SHR = 0x110, ROW_BCAST15 = 0x142, ROW_BCAST31 = 0x143;
+    uint32_t v = x;
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, ROW_SHR + 1, 0xf, 0xf, true);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, ROW_SHR + 2, 0xf, 0xf, true);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, ROW_SHR + 3, 0xf, 0xf, true);      // x[l-3..l] inside the row
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, ROW_SHR + 4, 0xf, 0xe, true);      // lanes 4..15 of a row: 8 terms
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, ROW_SHR + 8, 0xf, 0xc, true);      // lanes 8..15: the whole row prefix
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, ROW_BCAST15, 0xa, 0xf, true);      // rows 1 and 3 take the row before
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, ROW_BCAST31, 0xc, 0xf, true);      // rows 2 and 3 take lane 31
+    return v;
+}
+
+// value of a wavefront-uniform lane
+__device__ __forceinline__ uint32_t lane_value(uint32_t v, int lane_uniform)
+{
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, __builtin_amdgcn_readfirstlane(lane_uniform));
+}
+
 // inclusive scan of one value per thread over the workgroup; returns this thread's inclusive
-// prefix and the workgroup total.  `tmp` holds TK_WAVES+1 entries.
+// prefix and the workgroup total.  `tmp` holds TK_WAVES entries.  Every wavefront adds up the
+// per-wavefront totals itself (TK_WAVES <= 64 lanes), so nothing runs on a single thread.
 __device__ __forceinline__ uint32_t block_scan_incl(uint32_t v, uint32_t *tmp, uint32_t &total)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    uint32_t x = v;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t y = __shfl_up(x, d);
-        if (lane >= d) x += y;
-    }
+    const uint32_t x = wave_scan_incl(v);
     __syncthreads();                      // tmp may still be read from a previous call
     if (lane == 63) tmp[wave] = x;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t run = 0;
-        for (int w = 0; w < TK_WAVES; ++w) {
-            const uint32_t t = tmp[w];
-            tmp[w] = run;
-            run += t;
+    const uint32_t w = lane < TK_WAVES ? tmp[lane] : 0u;
+    const uint32_t wi = wave_scan_incl(w);
+    total = lane_value(wi, TK_WAVES - 1);
+    return x + lane_value(wi - w, wave);
+}
+
+// Radix step over elements held in LDS or global memory, for a histogram that is already zero
+// and used once: histogram the BITS-wide digit at `shift` of every element whose higher bits
+// equal `prefix` (bin = number of larger digits, so bins run from the top digit downwards),
+// then find the digit in which the `want`-th largest element falls.  Two barriers: after the
+// histogram, and after every wavefront has published the running sums of its threads' bins;
+// from those every wavefront works out the answer itself.  On return prefix has the digit
+// appended, want is the rank inside the digit's bucket and bucket its size.
+// Requires: at least `want` elements match the prefix.
+template <int BITS>
+__device__ __forceinline__ void radix_step_once(const uint32_t *u, long long n, int shift, uint32_t &prefix, uint32_t &want,
+                                                uint32_t &bucket, uint32_t *hist, uint32_t *lscan, uint32_t *wtot)
+{
+    constexpr int NB = 1 << BITS;
+    constexpr int PER = NB > TK_THREADS ? NB / TK_THREADS : 1;       // bins per thread
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t hi_mask = (shift + BITS >= 32) ? 0u : (0xffffffffu << (shift + BITS));
+    constexpr int UNR = 8;      // independent loads in flight per thread
+    for (long long j0 = threadIdx.x; j0 < n; j0 += (long long)TK_THREADS * UNR) {
+        uint32_t x[UNR];
+#pragma unroll
+        for (int i = 0; i < UNR; ++i) {
+            const long long j = j0 + (long long)i * TK_THREADS;
+            x[i] = j < n ? u[j] : 0xffffffffu;
         }
-        tmp[TK_WAVES] = run;
+#pragma unroll
+        for (int i = 0; i < UNR; ++i) {
+            const long long j = j0 + (long long)i * TK_THREADS;
+            if (j < n && (x[i] & hi_mask) == prefix) atomicAdd(&hist[NB - 1 - ((x[i] >> shift) & (NB - 1))], 1u);
+        }
     }
     __syncthreads();
-    total = tmp[TK_WAVES];
-    return x + tmp[wave];
+    uint32_t mine = 0;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const int b = threadIdx.x * PER + i;
+        mine += b < NB ? hist[b] : 0u;
+    }
+    const uint32_t incl = wave_scan_incl(mine);
+    lscan[threadIdx.x] = incl;
+    if (lane == 63) wtot[wave] = incl;
+    __syncthreads();
+    // the wavefront, then the thread, in whose bins the running count reaches `want`
+    const uint32_t w = lane < TK_WAVES ? wtot[lane] : 0u;
+    const uint32_t wi = wave_scan_incl(w);
+    const unsigned long long wmask = __ballot(lane < TK_WAVES && wi >= want);
+    const int wsel = wmask ? __ffsll((long long)wmask) - 1 : TK_WAVES - 1;      // (never empty when the requirement holds)
+    const uint32_t wbase = lane_value(wi - w, wsel);                       // elements in the wavefronts before it
+    const uint32_t v = lscan[wsel * 64 + lane];
+    const unsigned long long lmask = __ballot(wbase + v >= want);
+    const int lsel = lmask ? __ffsll((long long)lmask) - 1 : 63;
+    const int tsel = wsel * 64 + lsel;
+    uint32_t run = wbase + (lsel > 0 ? lane_value(v, lsel > 0 ? lsel - 1 : 0) : 0u);   // elements in the bins before that thread's
+    uint32_t digit_bin = (uint32_t)(tsel * PER), cnt = 0;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const int b = tsel * PER + i;
+        const uint32_t c = b < NB ? hist[b] : 0u;
+        if (cnt == 0) {
+            if (run < want && want <= run + c) {
+                digit_bin = (uint32_t)b;
+                cnt = c;
+            } else {
+                run += c;
+            }
+        }
+    }
+    prefix |= (uint32_t)(NB - 1 - digit_bin) << shift;
+    want -= run;
+    bucket = cnt;
 }
 
 // One radix step over n elements of u (global or LDS): histogram the `bits`-wide digit at
@@ -164,7 +250,13 @@ __device__ __forceinline__ int pow2_at_least(int n)
 
 __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, const float *group_max, long long L, int k, int32_t *idx_out)
 {
-    __shared__ uint32_t hist[TK_BINS];
+    // one histogram per radix step of the filter route, zeroed together at the start; the radix
+    // route reuses the first TK_BINS entries
+    constexpr int H_G1 = 0, H_G2 = H_G1 + 4096, H_C1 = H_G2 + 256, H_C2 = H_C1 + 4096, H_C3 = H_C2 + 1024, H_ALL = H_C3 + 1024;
+    __shared__ uint32_t hists[H_ALL];
+    static_assert(H_ALL >= TK_BINS, "the radix route histograms 12-bit digits in the same array");
+    uint32_t *hist = hists;
+    __shared__ uint32_t lscan[TK_THREADS];
     __shared__ uint32_t tmp[TK_WAVES + 1];
     __shared__ uint32_t tmp2[TK_WAVES + 1];
     __shared__ uint32_t bcast[3];                        // chosen digit, rank inside its bucket, bucket size
@@ -187,6 +279,7 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
         const long long ng = (L + kGroupKeys - 1) / kGroupKeys;       // handed-in group maxima
         const uint32_t *gsrc = gmax;                                   // where the maxima are ranked from
         long long gcount = TK_GROUPS;
+        for (int i = threadIdx.x; i < H_ALL; i += TK_THREADS) hists[i] = 0u;
         if (group_max != nullptr) {
             const uint32_t *gg = reinterpret_cast<const uint32_t *>(group_max) + (long long)h * ng;
             if (ng <= TK_GROUPS) {
@@ -223,24 +316,30 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
         MAGE_PROBE_AT(1);
         // a lower bound of the k-th largest group maximum (its top 20 bits), hence of the k-th
         // largest element: at least k elements are >= floor_bits
-        uint32_t floor_bits = 0, rank = (uint32_t)k;
-        radix_step(gsrc, gcount, 20, 12, floor_bits, rank, hist, tmp, bcast);
-        radix_step(gsrc, gcount, 12, 8, floor_bits, rank, hist, tmp, bcast);
+        uint32_t floor_bits = 0, rank = (uint32_t)k, bucket;
+        radix_step_once<12>(gsrc, gcount, 20, floor_bits, rank, bucket, hists + H_G1, lscan, tmp);
+        MAGE_PROBE_AT(5);
+        radix_step_once<8>(gsrc, gcount, 12, floor_bits, rank, bucket, hists + H_G2, lscan, tmp2);
+        // the maxima buffer turns into the position bitmap / index sort buffer of the last phase
+        const bool bitmap = L <= (long long)TK_GROUPS * 32;
+        uint32_t *bits = gmax;
+        int32_t *sidx = reinterpret_cast<int32_t *>(gmax);
+        const int words = (int)((L + 31) >> 5);
+        const int P2 = pow2_at_least(k);
+        auto clear_last_phase = [&]() {
+            if (bitmap) for (int i = threadIdx.x; i < words; i += TK_THREADS) bits[i] = 0u;
+            else for (int i = threadIdx.x; i < P2; i += TK_THREADS) sidx[i] = 0x7fffffff;
+        };
 
         MAGE_PROBE_AT(2);
         // appends this thread's `cnt` keepers among x[0..NX) (positions j[i] .. j[i]+3) to the candidates
         auto keep = [&](const uint4 *x, const long long *j, int nx, uint32_t cnt) {
-            uint32_t incl = cnt;
-#pragma unroll
-            for (int d = 1; d < 64; d <<= 1) {
-                const uint32_t y = __shfl_up(incl, d);
-                if (lane >= d) incl += y;
-            }
-            const uint32_t wave_total = __shfl(incl, 63);
+            const uint32_t incl = wave_scan_incl(cnt);
+            const uint32_t wave_total = lane_value(incl, 63);
             if (wave_total == 0) return;                   // uniform per wavefront
             uint32_t base = 0;
             if (lane == 0) base = atomicAdd(&n_cand, wave_total);
-            uint32_t pos = __shfl(base, 0) + incl - cnt;
+            uint32_t pos = lane_value(base, 0) + incl - cnt;
             if (cnt) {
                 for (int s = 0; s < nx; ++s) {
                     const uint32_t xs[4] = {x[s].x, x[s].y, x[s].z, x[s].w};
@@ -272,17 +371,12 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
                     const long long g = g0 + (long long)s * TK_THREADS + threadIdx.x;
                     cnt += (g < ng && gv[s] >= floor_bits);
                 }
-                uint32_t incl = cnt;
-#pragma unroll
-                for (int d = 1; d < 64; d <<= 1) {
-                    const uint32_t y = __shfl_up(incl, d);
-                    if (lane >= d) incl += y;
-                }
-                const uint32_t wave_total = __shfl(incl, 63);
+                const uint32_t incl = wave_scan_incl(cnt);
+                const uint32_t wave_total = lane_value(incl, 63);
                 if (wave_total == 0) continue;
                 uint32_t base = 0;
                 if (lane == 0) base = atomicAdd(&n_hit, wave_total);
-                uint32_t pos = __shfl(base, 0) + incl - cnt;
+                uint32_t pos = lane_value(base, 0) + incl - cnt;
 #pragma unroll
                 for (int s = 0; s < TK_SLOTS; ++s) {
                     const long long g = g0 + (long long)s * TK_THREADS + threadIdx.x;
@@ -295,6 +389,8 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
             __syncthreads();
             const uint32_t nh = n_hit;
             overflow = nh > TK_CAND;
+            clear_last_phase();                              // every read of the maxima is behind the barrier
+            MAGE_PROBE_AT(6);
             if (!overflow) {
                 constexpr int QPG = kGroupKeys / 4;            // 16-byte pieces per group
                 constexpr int NX = 4;                           // pieces in flight per thread
@@ -319,6 +415,8 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
             }
         } else {
             // ---- sweep 2: keep the elements at or above the bound ----
+            __syncthreads();                                 // every wavefront has left the radix steps over the maxima
+            clear_last_phase();
             for (long long base0 = 0; base0 < L; base0 += 4ll * TK_GROUPS) {      // uniform trip count
                 uint4 x[TK_SLOTS];
                 long long j[TK_SLOTS];
@@ -341,21 +439,17 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
         if (!overflow && nc <= TK_CAND) {
             // exact k-th value among the candidates (radix select in LDS) and the number of
             // candidates equal to it that belong to the set (the ones with the smallest positions)
-            uint32_t thr = 0, want = (uint32_t)k;
-            radix_step(cval, nc, 20, 12, thr, want, hist, tmp, bcast);
-            radix_step(cval, nc, 10, 10, thr, want, hist, tmp, bcast);
-            radix_step(cval, nc, 0, 10, thr, want, hist, tmp, bcast);
-            const uint32_t n_equal = bcast[2];
-            __syncthreads();
-            const bool bitmap = L <= (long long)TK_GROUPS * 32;
-            uint32_t *bits = gmax;                           // reuses the group-maxima buffer
-            int32_t *sidx = reinterpret_cast<int32_t *>(gmax);
-            const int words = (int)((L + 31) >> 5);
-            const int P2 = pow2_at_least(k);
-            if (bitmap) for (int i = threadIdx.x; i < words; i += TK_THREADS) bits[i] = 0u;
-            else for (int i = threadIdx.x; i < P2; i += TK_THREADS) sidx[i] = 0x7fffffff;
-            if (threadIdx.x == 0) n_cand = 0;                // now counts the winners (index-sort route)
-            __syncthreads();
+            uint32_t thr = 0, want = (uint32_t)k, n_equal;
+            radix_step_once<12>(cval, nc, 20, thr, want, n_equal, hists + H_C1, lscan, tmp);
+            radix_step_once<10>(cval, nc, 10, thr, want, n_equal, hists + H_C2, lscan, tmp2);
+            radix_step_once<10>(cval, nc, 0, thr, want, n_equal, hists + H_C3, lscan, tmp);
+            MAGE_PROBE_AT(7);
+            // n_cand now counts the winners (index-sort route); every thread read nc before the
+            // barriers of the radix steps
+            if (!bitmap) {
+                if (threadIdx.x == 0) n_cand = 0;
+                __syncthreads();
+            }
             for (uint32_t i = threadIdx.x; i < nc; i += TK_THREADS) {
                 const uint32_t v = cval[i], j = cidx[i];
                 bool take = v > thr;
@@ -389,7 +483,8 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
                         uint32_t b = bits[wi];
                         while (b) {
                             const int bit = __ffs(b) - 1;
-                            out[pos++] = (int32_t)(wi * 32 + bit);
+                            if (pos < (uint32_t)k) out[pos] = (int32_t)(wi * 32 + bit);
+                            ++pos;
                             b &= b - 1;
                         }
                     }
