@@ -83,13 +83,16 @@ __device__ __forceinline__ uint32_t block_scan_incl(uint32_t v, uint32_t *tmp, u
 // appended, want is the rank inside the digit's bucket and bucket its size.
 // Requires: at least `want` elements match the prefix.
 template <int BITS>
-__device__ __forceinline__ void radix_step_once(const uint32_t *u, long long n, int shift, uint32_t &prefix, uint32_t &want,
-                                                uint32_t &bucket, uint32_t *hist, uint32_t *lscan, uint32_t *wtot)
+__device__ __forceinline__ void radix_count(uint32_t x, bool in, int shift, uint32_t prefix, uint32_t *hist)
 {
     constexpr int NB = 1 << BITS;
-    constexpr int PER = NB > TK_THREADS ? NB / TK_THREADS : 1;       // bins per thread
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint32_t hi_mask = (shift + BITS >= 32) ? 0u : (0xffffffffu << (shift + BITS));
+    if (in && (x & hi_mask) == prefix) atomicAdd(&hist[NB - 1 - ((x >> shift) & (NB - 1))], 1u);
+}
+
+template <int BITS>
+__device__ __forceinline__ void radix_hist_mem(const uint32_t *u, long long n, int shift, uint32_t prefix, uint32_t *hist)
+{
     constexpr int UNR = 8;      // independent loads in flight per thread
     for (long long j0 = threadIdx.x; j0 < n; j0 += (long long)TK_THREADS * UNR) {
         uint32_t x[UNR];
@@ -99,11 +102,25 @@ __device__ __forceinline__ void radix_step_once(const uint32_t *u, long long n, 
             x[i] = j < n ? u[j] : 0xffffffffu;
         }
 #pragma unroll
-        for (int i = 0; i < UNR; ++i) {
-            const long long j = j0 + (long long)i * TK_THREADS;
-            if (j < n && (x[i] & hi_mask) == prefix) atomicAdd(&hist[NB - 1 - ((x[i] >> shift) & (NB - 1))], 1u);
-        }
+        for (int i = 0; i < UNR; ++i) radix_count<BITS>(x[i], j0 + (long long)i * TK_THREADS < n, shift, prefix, hist);
     }
+}
+
+// the same over TK_SLOTS elements per thread that already sit in registers
+template <int BITS>
+__device__ __forceinline__ void radix_hist_regs(const uint32_t (&x)[TK_SLOTS], int shift, uint32_t prefix, uint32_t *hist)
+{
+#pragma unroll
+    for (int i = 0; i < TK_SLOTS; ++i) radix_count<BITS>(x[i], true, shift, prefix, hist);
+}
+
+template <int BITS>
+__device__ __forceinline__ void radix_pick(int shift, uint32_t &prefix, uint32_t &want, uint32_t &bucket,
+                                           const uint32_t *hist, uint32_t *lscan, uint32_t *wtot)
+{
+    constexpr int NB = 1 << BITS;
+    constexpr int PER = NB > TK_THREADS ? NB / TK_THREADS : 1;       // bins per thread
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     __syncthreads();
     uint32_t mine = 0;
 #pragma unroll
@@ -143,6 +160,14 @@ __device__ __forceinline__ void radix_step_once(const uint32_t *u, long long n, 
     prefix |= (uint32_t)(NB - 1 - digit_bin) << shift;
     want -= run;
     bucket = cnt;
+}
+
+template <int BITS>
+__device__ __forceinline__ void radix_step_once(const uint32_t *u, long long n, int shift, uint32_t &prefix, uint32_t &want,
+                                                uint32_t &bucket, uint32_t *hist, uint32_t *lscan, uint32_t *wtot)
+{
+    radix_hist_mem<BITS>(u, n, shift, prefix, hist);
+    radix_pick<BITS>(shift, prefix, want, bucket, hist, lscan, wtot);
 }
 
 // One radix step over n elements of u (global or LDS): histogram the `bits`-wide digit at
@@ -277,23 +302,31 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
         const bool vec_ok = (L & 3) == 0 && (reinterpret_cast<uintptr_t>(u) & 15) == 0;
         const int lane = threadIdx.x & 63;
         const long long ng = (L + kGroupKeys - 1) / kGroupKeys;       // handed-in group maxima
-        const uint32_t *gsrc = gmax;                                   // where the maxima are ranked from
-        long long gcount = TK_GROUPS;
-        for (int i = threadIdx.x; i < H_ALL; i += TK_THREADS) hists[i] = 0u;
-        if (group_max != nullptr) {
-            const uint32_t *gg = reinterpret_cast<const uint32_t *>(group_max) + (long long)h * ng;
-            if (ng <= TK_GROUPS) {
-                for (int i = threadIdx.x; i < TK_GROUPS; i += TK_THREADS) gmax[i] = i < ng ? gg[i] : 0u;
-            } else {
-                gsrc = gg;
-            }
-            gcount = ng <= TK_GROUPS ? TK_GROUPS : ng;
-        } else {
-            // ---- sweep 1: strided group maxima (group = slot * 1024 + thread); each thread takes 4
-            // consecutive elements per slot (one 16-byte load when the row is aligned)
-            uint32_t gm[TK_SLOTS];
+        // the maxima buffer serves the last phase only (position bitmap / index sort buffer)
+        const bool bitmap = L <= (long long)TK_GROUPS * 32;
+        uint32_t *bits = gmax;
+        int32_t *sidx = reinterpret_cast<int32_t *>(gmax);
+        const int words = (int)((L + 31) >> 5);
+        const int P2 = pow2_at_least(k);
+        // This thread's group maxima, group = slot * 1024 + thread: handed in (if they fit: up to
+        // TK_GROUPS of them, the rest reads as zero) or taken here; ranked and compared from
+        // registers.  More handed-in maxima than that are ranked from global memory.
+        uint32_t gv[TK_SLOTS];
+        const uint32_t *gg = group_max ? reinterpret_cast<const uint32_t *>(group_max) + (long long)h * ng : nullptr;
+        const bool in_regs = group_max == nullptr || ng <= TK_GROUPS;
 #pragma unroll
-            for (int s = 0; s < TK_SLOTS; ++s) gm[s] = 0u;
+        for (int s = 0; s < TK_SLOTS; ++s) gv[s] = 0u;
+        if (group_max != nullptr) {
+            if (in_regs) {
+#pragma unroll
+                for (int s = 0; s < TK_SLOTS; ++s) {
+                    const int g = s * TK_THREADS + threadIdx.x;
+                    if (g < ng) gv[s] = gg[g];
+                }
+            }
+        } else {
+            // ---- sweep 1: strided group maxima; each thread takes 4 consecutive elements per slot
+            // (one 16-byte load when the row is aligned)
             for (long long base0 = 0; base0 < L; base0 += 4ll * TK_GROUPS) {
                 uint4 x[TK_SLOTS];
 #pragma unroll
@@ -302,12 +335,14 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
                 for (int s = 0; s < TK_SLOTS; ++s) {
                     const uint32_t a = x[s].x > x[s].y ? x[s].x : x[s].y, b = x[s].z > x[s].w ? x[s].z : x[s].w;
                     const uint32_t c = a > b ? a : b;
-                    gm[s] = c > gm[s] ? c : gm[s];
+                    gv[s] = c > gv[s] ? c : gv[s];
                 }
             }
-#pragma unroll
-            for (int s = 0; s < TK_SLOTS; ++s) gmax[s * TK_THREADS + threadIdx.x] = gm[s];
         }
+        // while the loads travel: every histogram and the buffer of the last phase start at zero
+        for (int i = threadIdx.x; i < H_ALL; i += TK_THREADS) hists[i] = 0u;
+        if (bitmap) for (int i = threadIdx.x; i < words; i += TK_THREADS) bits[i] = 0u;
+        else for (int i = threadIdx.x; i < P2; i += TK_THREADS) sidx[i] = 0x7fffffff;
         if (threadIdx.x == 0) {
             n_cand = 0;
             n_hit = 0;
@@ -317,19 +352,13 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
         // a lower bound of the k-th largest group maximum (its top 20 bits), hence of the k-th
         // largest element: at least k elements are >= floor_bits
         uint32_t floor_bits = 0, rank = (uint32_t)k, bucket;
-        radix_step_once<12>(gsrc, gcount, 20, floor_bits, rank, bucket, hists + H_G1, lscan, tmp);
+        if (in_regs) radix_hist_regs<12>(gv, 20, floor_bits, hists + H_G1);
+        else radix_hist_mem<12>(gg, ng, 20, floor_bits, hists + H_G1);
+        radix_pick<12>(20, floor_bits, rank, bucket, hists + H_G1, lscan, tmp);
         MAGE_PROBE_AT(5);
-        radix_step_once<8>(gsrc, gcount, 12, floor_bits, rank, bucket, hists + H_G2, lscan, tmp2);
-        // the maxima buffer turns into the position bitmap / index sort buffer of the last phase
-        const bool bitmap = L <= (long long)TK_GROUPS * 32;
-        uint32_t *bits = gmax;
-        int32_t *sidx = reinterpret_cast<int32_t *>(gmax);
-        const int words = (int)((L + 31) >> 5);
-        const int P2 = pow2_at_least(k);
-        auto clear_last_phase = [&]() {
-            if (bitmap) for (int i = threadIdx.x; i < words; i += TK_THREADS) bits[i] = 0u;
-            else for (int i = threadIdx.x; i < P2; i += TK_THREADS) sidx[i] = 0x7fffffff;
-        };
+        if (in_regs) radix_hist_regs<8>(gv, 12, floor_bits, hists + H_G2);
+        else radix_hist_mem<8>(gg, ng, 12, floor_bits, hists + H_G2);
+        radix_pick<8>(12, floor_bits, rank, bucket, hists + H_G2, lscan, tmp2);
 
         MAGE_PROBE_AT(2);
         // appends this thread's `cnt` keepers among x[0..NX) (positions j[i] .. j[i]+3) to the candidates
@@ -358,12 +387,13 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
         bool overflow = false;
         if (group_max != nullptr) {
             // ---- the groups at or above the bound, then only their elements ----
-            for (long long g0 = 0; g0 < ng; g0 += (long long)TK_THREADS * TK_SLOTS) {     // uniform trip count
-                uint32_t gv[TK_SLOTS];
+            for (long long g0 = 0; g0 < ng; g0 += (long long)TK_THREADS * TK_SLOTS) {     // uniform trip count (one if in_regs)
+                if (!in_regs) {
 #pragma unroll
-                for (int s = 0; s < TK_SLOTS; ++s) {
-                    const long long g = g0 + (long long)s * TK_THREADS + threadIdx.x;
-                    gv[s] = g < ng ? gsrc[g] : 0u;
+                    for (int s = 0; s < TK_SLOTS; ++s) {
+                        const long long g = g0 + (long long)s * TK_THREADS + threadIdx.x;
+                        gv[s] = g < ng ? gg[g] : 0u;
+                    }
                 }
                 uint32_t cnt = 0;
 #pragma unroll
@@ -389,7 +419,6 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
             __syncthreads();
             const uint32_t nh = n_hit;
             overflow = nh > TK_CAND;
-            clear_last_phase();                              // every read of the maxima is behind the barrier
             MAGE_PROBE_AT(6);
             if (!overflow) {
                 constexpr int QPG = kGroupKeys / 4;            // 16-byte pieces per group
@@ -415,8 +444,6 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
             }
         } else {
             // ---- sweep 2: keep the elements at or above the bound ----
-            __syncthreads();                                 // every wavefront has left the radix steps over the maxima
-            clear_last_phase();
             for (long long base0 = 0; base0 < L; base0 += 4ll * TK_GROUPS) {      // uniform trip count
                 uint4 x[TK_SLOTS];
                 long long j[TK_SLOTS];
