@@ -85,6 +85,31 @@ __device__ __forceinline__ void issue_tile(const u16 *kbase, const u16 *vbase, l
     }
 }
 
+// One matrix of a tile through per-lane element offsets: `rows_to_offsets` works them out from the
+// source rows (and keeps them), `issue_offsets` requests the loads.  K and V of a tile share the
+// offsets: the V request reuses what the K request of the same tile left behind.
+template <int D, int NW, class RowOf>
+__device__ __forceinline__ void rows_to_offsets(long long row_stride, RowOf row_of, long long (&off)[TileGeom<D>::LOADS / NW])
+{
+    using G = TileGeom<D>;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int n = 0; n < G::LOADS / NW; ++n) {
+        const int r = (n * NW + wave) * G::RPI + lane / G::CH;
+        off[n] = row_of(r) * row_stride + ((lane % G::CH) ^ swz<D>(r)) * 8;
+    }
+}
+
+template <int D, int NW>
+__device__ __forceinline__ void issue_offsets(const u16 *base, const long long (&off)[TileGeom<D>::LOADS / NW], unsigned char *buf)
+{
+    using G = TileGeom<D>;
+    const int wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int n = 0; n < G::LOADS / NW; ++n)
+        __builtin_amdgcn_global_load_lds(MAGE_GLOBAL_PTR(base + off[n]), MAGE_LDS_PTR(buf + (n * NW + wave) * 1024), 16, 0, 0);
+}
+
 // The same for a full tile of contiguous cache rows, written so that the per-tile part of every
 // address is wavefront-uniform (scalar registers): `kbase` points at (first row of the tile, this KV
 // head, channel 0), `off[n]` is this lane's byte offset inside a tile for load n (constant over the
@@ -288,11 +313,13 @@ constexpr int kAttnRows = 128;   // query rows per workgroup (4 row groups of 32
 template <int D, int MODE>
 struct AttnGeom {
     static constexpr bool WITH_V = (MODE == MODE_ATTN);
-    static constexpr int BUF_BYTES = TileGeom<D>::MAT_BYTES * (WITH_V ? 2 : 1);
-    // LDS tile buffers = prefetch distance + 1.  Attention is register-bound to one workgroup per
-    // CU and hides its arithmetic best with three tiles in flight; the K-only pass is lighter on
-    // registers and runs two workgroups per CU with two tiles in flight each.
+    // LDS: a ring of NBUF K tiles, then (attention) a ring of NBUF V tiles.  While tile t is
+    // consumed, K(t+1) is resident too (its scores are computed one tile ahead) and the next
+    // NBUF-1 K tiles / V tiles are in flight.  Attention is register-bound to one workgroup per CU;
+    // the K-only pass is lighter on registers and runs two workgroups per CU.
     static constexpr int NBUF = WITH_V ? 4 : 3;
+    static constexpr int RING_BYTES = NBUF * TileGeom<D>::MAT_BYTES;
+    static constexpr int TILE_LDS_BYTES = RING_BYTES * (WITH_V ? 2 : 1);
     static constexpr int LPT = (TileGeom<D>::LOADS / kAttnWaves) * (WITH_V ? 2 : 1);            // loads one wavefront issues per tile
     static constexpr int MAX_WAVES_PER_SIMD = (WITH_V || D > 128) ? 2 : 4;
 };
@@ -305,7 +332,7 @@ void attn_bf16_kernel(const KernelArgs a)
     using AG = AttnGeom<D, MODE>;
     constexpr int NW = kAttnWaves;
     constexpr bool WITH_V = AG::WITH_V;
-    constexpr int NBUF = AG::NBUF, LPT = AG::LPT, BUF_BYTES = AG::BUF_BYTES;
+    constexpr int NBUF = AG::NBUF, LPT = AG::LPT, VRING = AG::RING_BYTES;
     constexpr int KS = D / 16;     // MFMA k-steps over the head dimension
     constexpr int DT = D / 32;     // 32-row tiles of O^T
     constexpr int HALF = 32 * G::ROW_BYTES;
@@ -315,8 +342,8 @@ void attn_bf16_kernel(const KernelArgs a)
     constexpr int XCH_BYTES = (NW * XCH_FLOATS + NW * 4 * 64) * 4;
     constexpr int STAGE_BYTES = WITH_V ? NW * 32 * HOST * 4 : 0;
     constexpr int TAIL_BYTES = XCH_BYTES > STAGE_BYTES ? XCH_BYTES : STAGE_BYTES;
-    constexpr int SMEM_BYTES = NBUF * BUF_BYTES > TAIL_BYTES ? NBUF * BUF_BYTES : TAIL_BYTES;
-    static_assert((NBUF - 2) * LPT < 64, "outstanding loads must fit the counter");
+    constexpr int SMEM_BYTES = AG::TILE_LDS_BYTES > TAIL_BYTES ? AG::TILE_LDS_BYTES : TAIL_BYTES;
+    static_assert((NBUF - 1) * LPT < 64, "outstanding loads must fit the counter");
 
     // tile buffers; after the key loop the same memory carries the merge and the output transposition
     __shared__ __attribute__((aligned(1024))) unsigned char smem[SMEM_BYTES];
@@ -356,7 +383,6 @@ void attn_bf16_kernel(const KernelArgs a)
     };
     unsigned soff[G::LOADS / NW];      // this lane's byte offsets inside a streamed tile
     stream_offsets<D, NW>(cache_stride, soff);
-    const long long v_minus_k_bytes = reinterpret_cast<const unsigned char *>(vc) - reinterpret_cast<const unsigned char *>(kc);
     const unsigned lds_wave = __builtin_amdgcn_readfirstlane(lds_addr(smem) + wave * 1024);
     // Gathered rows: the index entries of the next kIdxTiles tiles wait in LDS, fetched ahead in
     // one go.  An index loaded into a register right before its row would sit behind every tile
@@ -373,27 +399,44 @@ void attn_bf16_kernel(const KernelArgs a)
             idx_lds[e] = tt < sr.cache_tiles ? idx[pos] : 0;
         }
     };
-    auto issue = [&](int t) {
-        const int valid = tile_valid(t);
-        unsigned char *buf = smem + (t % NBUF) * BUF_BYTES;
-        if (!GATHER && t < sr.cache_tiles && valid == kBf16Tile) {
-            issue_tile_stream<D, NW, WITH_V>(reinterpret_cast<const unsigned char *>(kc + (sr.first + t * sr.step) * cache_stride),
-                                             v_minus_k_bytes, soff, lds_wave + (t % NBUF) * BUF_BYTES);
-        } else if (t < sr.cache_tiles) {
-            const long long base = sr.first + t * sr.step;
-            issue_tile<D, NW, WITH_V>(kc, vc, cache_stride, buf, [&](int r) -> long long {
-                if (GATHER) {
-                    float v = lds_read_f32<0>(idx_addr + ((t - idx_t0) * kBf16Tile + r) * 4);
-                    lds_wait<0>(v);
-                    return (long long)__builtin_bit_cast(int, v);
-                }
-                return base + (r < valid ? r : valid - 1);
-            });
-        } else {
-            const int base = (t - sr.cache_tiles) * kBf16Tile;
-            issue_tile<D, NW, WITH_V>(kb, vb, cache_stride, buf, [&](int r) -> long long { return base + (r < valid ? r : valid - 1); });
+    // Tiles 0 .. n_full-1 are whole tiles of contiguous cache rows: the common case takes one
+    // comparison per tile; everything else (a ragged last tile, gathered rows, in-block keys) goes
+    // through the general path.
+    const int n_full = GATHER ? 0 : sr.cache_tiles - ((sr.cache_tiles > 0 && tile_valid(sr.cache_tiles - 1) < kBf16Tile) ? 1 : 0);
+    // one matrix (K: IS_V = false, V: true) of tile t into its ring slot; outside the common case
+    // the V request of a tile reuses the offsets of its K request, which must be the latest one
+    long long goff[G::LOADS / NW];
+    auto issue = [&](int t, auto IS_V) {
+        constexpr bool is_v = decltype(IS_V)::value;
+        const unsigned slot = (is_v ? VRING : 0) + (t % NBUF) * G::MAT_BYTES;
+        const u16 *cache = is_v ? vc : kc, *blk = is_v ? vb : kb;
+        if (t < n_full) {
+            issue_tile_stream<D, NW, false>(reinterpret_cast<const unsigned char *>(cache + (sr.first + t * sr.step) * cache_stride),
+                                            0, soff, lds_wave + slot);
+            return;
         }
+        if (t >= ntiles) return;
+        if constexpr (!is_v) {
+            const int valid = tile_valid(t);
+            if (t < sr.cache_tiles) {
+                const long long base = sr.first + t * sr.step;
+                rows_to_offsets<D, NW>(cache_stride, [&](int r) -> long long {
+                    if (GATHER) {
+                        float v = lds_read_f32<0>(idx_addr + ((t - idx_t0) * kBf16Tile + r) * 4);
+                        lds_wait<0>(v);
+                        return (long long)__builtin_bit_cast(int, v);
+                    }
+                    return base + (r < valid ? r : valid - 1);
+                }, goff);
+            } else {
+                const int base = (t - sr.cache_tiles) * kBf16Tile;
+                rows_to_offsets<D, NW>(cache_stride, [&](int r) -> long long { return base + (r < valid ? r : valid - 1); }, goff);
+            }
+        }
+        issue_offsets<D, NW>(t < sr.cache_tiles ? cache : blk, goff, smem + slot);
     };
+    auto issue_k = [&](int t) { issue(t, std::false_type{}); };
+    auto issue_v = [&](int t) { if (WITH_V) issue(t, std::true_type{}); };
 
     // queries first: waiting for them later (loads retire in order) must not mean waiting for tiles
     bf16x8_t qf[KS];
@@ -402,9 +445,13 @@ void attn_bf16_kernel(const KernelArgs a)
         load_idx(0);
         __syncthreads();
     }
+    // load order: K(0), then pairs [V(j), K(j+1)]; loads retire in this order
+    issue_k(0);
 #pragma unroll
-    for (int t = 0; t < NBUF - 1; ++t)
-        if (t < ntiles) issue(t);
+    for (int j = 0; j < NBUF - 1; ++j) {
+        issue_v(j);
+        issue_k(j + 1);
+    }
     FragAddr fa = frag_addr<D>(lane);
     fa.k += kh * HALF;                 // this wavefront's half of every tile
     fa.v[0] += kh * HALF;
@@ -416,30 +463,45 @@ void attn_bf16_kernel(const KernelArgs a)
     for (int i = 0; i < (WITH_V ? DT : 1); ++i)
 #pragma unroll
         for (int v = 0; v < 16; ++v) o[i][v] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;     // running max (log2 domain) and this lane's share of the normaliser
-    float m_pre = -INFINITY, l_pre = 0.f;     // the same after the last cache tile (prefix-only statistics)
+    // Online softmax with a lazily raised reference: probabilities are taken against m_run (log2
+    // domain), which follows the row maximum only when that has run ahead by more than kLazy, so
+    // the accumulators are rescaled on few tiles instead of on almost every one (any reference
+    // gives the same ratios; fp32 sums and bf16 probabilities have the exponent range to spare).
+    // The reference starts at a finite floor: rows that have seen padding keys only keep it and
+    // a zero sum, without any inf - inf.
+    constexpr float kLazy = 8.f, kFloor = -3.0e38f;
+    float m_run = kFloor, l_run = 0.f;        // reference and this lane's share of the normaliser
+    float m_pre = kFloor, l_pre = 0.f;        // the same after the last cache tile (prefix-only statistics)
 
     // the query fragments must have arrived before the loop: a wait for them inside it would be a
     // wait for every tile load in flight, once per tile
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) asm volatile("" ::"v"(qf[ks]));
 
+    // Scores run one tile ahead of the softmax: S^T(t+1) is accumulated by the matrix cores while
+    // the vector ALU exponentiates S^T(t), the two interleaved instruction by instruction.
+    // sc[v] = score of query row l32 against key kh*32 + 8*(v/4) + 4*lg + v%4
+    f32x16_t sc_cur, sc_nxt;
+    if (ntiles >= NBUF) tile_barrier<(NBUF - 1) * LPT>();       // K(0) landed
+    else tile_barrier<0>();
+    if (wave_active) qk_half<D, true>(smem_addr + fa.k, qf, sc_cur);
+
     for (int t = 0; t < ntiles; ++t) {
-        // tile t landed (NBUF-2 younger tiles may still be in flight); everyone is done with tile t-1
-        if (t + NBUF - 2 < ntiles) tile_barrier<(NBUF - 2) * LPT>();
+        // V(t) and K(t+1) landed (NBUF-2 younger pairs may still be in flight); everyone is done
+        // with K(t) and V(t-1)
+        if (t + NBUF - 1 < ntiles) tile_barrier<(NBUF - 2) * LPT>();
         else tile_barrier<0>();
         if (t == 0) MAGE_PROBE_AT(1);
         if (GATHER) {
-            const int tn = t + NBUF - 1;
+            const int tn = t + NBUF;               // the K tile about to be requested (V requests read no entries)
             if (tn < sr.cache_tiles && tn >= idx_t0 + kIdxTiles) {   // uniform; every wavefront is past its reads of the old entries
                 load_idx(tn);
                 idx_t0 = tn;
                 __syncthreads();
             }
         }
-        if (t + NBUF - 1 < ntiles) issue(t + NBUF - 1);
-        const int valid = tile_valid(t);
-        const unsigned tile_addr = smem_addr + (t % NBUF) * BUF_BYTES;
+        issue_v(t + NBUF - 1);
+        issue_k(t + NBUF);
         // keep the per-read address arithmetic inside the loop: hoisted, it would pin dozens of registers
         asm volatile("" : "+v"(fa.k), "+v"(fa.v[0]), "+v"(fa.v[1]));
         if (WITH_V && t == sr.cache_tiles) {   // first in-block tile: freeze the prefix statistics
@@ -452,50 +514,87 @@ void attn_bf16_kernel(const KernelArgs a)
 #else
         if (wave_active) {
 #endif
-            // S^T: sc[v] = score of query row l32 against key kh*32 + 8*(v/4) + 4*lg + v%4
-            f32x16_t sc;
-            qk_half<D, true>(tile_addr + fa.k, qf, sc);
-            // the first V^T fragments travel while the softmax runs
-            const unsigned va[2] = {tile_addr + G::MAT_BYTES + fa.v[0], tile_addr + G::MAT_BYTES + fa.v[1]};
-            u32x2_t vf[2][WITH_V ? DT : 1][2];
-            if constexpr (WITH_V) issue_vt_group<D, 0>(va, vf[0]);
-            if (valid < kBf16Tile) {           // uniform: only the last tile of a slice has padding keys
+            // K fragments of the next tile (its ring slot holds stale data after the last tile: the
+            // scores computed from it are never used)
+            const unsigned ka = smem_addr + ((t + 1) % NBUF) * G::MAT_BYTES + fa.k;
+            constexpr int KI = KS <= 8 ? KS : 1;        // k-steps interleaved with the softmax
+            u32x4_t kf[KI];
+            if constexpr (KS <= 8) {
+                static_for<KS>([&](auto S) {
+                    constexpr int i = decltype(S)::value;
+                    kf[i] = lds_read_b128<0>(ka ^ (unsigned)(i << 5));
+                });
+            }
+            const unsigned vt = smem_addr + VRING + (t % NBUF) * G::MAT_BYTES;
+            const unsigned va[2] = {vt + fa.v[0], vt + fa.v[1]};
+            u32x2_t vf[2][DT][2];
+
+            if (t >= n_full) {                 // uniform: only the last tile of a slice can have padding keys
+                const int valid = tile_valid(t);
 #pragma unroll
                 for (int v = 0; v < 16; ++v)
-                    if (kh * 32 + 8 * (v >> 2) + 4 * lg + (v & 3) >= valid) sc[v] = -INFINITY;
+                    if (kh * 32 + 8 * (v >> 2) + 4 * lg + (v & 3) >= valid) sc_cur[v] = -INFINITY;
             }
-            float mx = sc[0];
+            float mx = sc_cur[0];
 #pragma unroll
-            for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sc[v]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32)) * a.scale_log2;
-            // finite floor: a half tile of padding keys must not turn the running maximum into -inf - -inf
-            const float m_new = fmaxf(fmaxf(m_run, mx), -3.0e38f);
-            const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
-            const bool grew = m_new > m_run;
-            m_run = m_new;
-            float psum = 0.f;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const float p = __builtin_amdgcn_exp2f(fmaf(sc[v], a.scale_log2, -m_new));
-                sc[v] = p;
-                psum += p;
+            for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sc_cur[v]);
+            {   // the other 16 keys of this row sit in the other half of the wavefront
+                const unsigned mi = __builtin_bit_cast(unsigned, mx);
+                const auto sw = __builtin_amdgcn_permlane32_swap(mi, mi, false, false);
+                mx = fmaxf(__builtin_bit_cast(float, sw[0]), __builtin_bit_cast(float, sw[1])) * a.scale_log2;
             }
-            l_run = l_run * corr + psum;
-
-            if constexpr (WITH_V) {
-                if (__any(grew)) {             // rescale only when some row's maximum moved
+            if (__any(mx > m_run + kLazy)) {      // uniform: some row's maximum has run ahead of its reference
+                const float m_new = fmaxf(m_run, mx);
+                const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
+                m_run = m_new;
+                l_run *= corr;
+                if constexpr (WITH_V) {
 #pragma unroll
                     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
                         for (int v = 0; v < 16; ++v) o[dt][v] *= corr;
                 }
-                // key group g (16 keys): P^T fragment from sc[8*g ..]; the V^T fragments of group 1
+            }
+            const float m_new = m_run;
+            float psum = 0.f;
+            if constexpr (KS <= 8) {
+                constexpr int VPS = 16 / KS;      // scores exponentiated per MFMA k-step
+#pragma unroll
+                for (int v = 0; v < 16; ++v) sc_nxt[v] = 0.f;
+                static_for<KS>([&](auto S) {
+                    constexpr int i = decltype(S)::value;
+                    constexpr int VR = (WITH_V && i >= 1) ? 2 * DT : 0;     // V^T reads requested behind the K fragments
+                    lds_wait<KS - 1 - i + VR>(kf[i]);
+                    sc_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[i]), qf[i], sc_nxt, 0, 0, 0);
+                    if constexpr (WITH_V && i == 0) issue_vt_group<D, 0>(va, vf[0]);
+#pragma unroll
+                    for (int e = 0; e < VPS; ++e) {
+                        float p = __builtin_amdgcn_exp2f(fmaf(sc_cur[i * VPS + e], a.scale_log2, -m_new));
+                        asm volatile("" : "+v"(p));        // computed here, between two MFMAs, not wherever it is first used
+                        sc_cur[i * VPS + e] = p;
+                        psum += p;
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                });
+            } else {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const float p = __builtin_amdgcn_exp2f(fmaf(sc_cur[v], a.scale_log2, -m_new));
+                    sc_cur[v] = p;
+                    psum += p;
+                }
+                qk_half<D, true>(ka, qf, sc_nxt);
+            }
+            l_run += psum;
+
+            if constexpr (WITH_V) {
+                // key group g (16 keys): P^T fragment from sc_cur[8*g ..]; the V^T fragments of group 1
                 // are requested before group 0 is consumed
                 static_for<2>([&](auto GI) {
                     constexpr int g = decltype(GI)::value;
                     bf16x8_t pf;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) pf[e] = (__bf16)sc[8 * g + e];
+                    for (int e = 0; e < 8; ++e) pf[e] = (__bf16)sc_cur[8 * g + e];
                     if constexpr (g == 0) issue_vt_group<D, 1>(va, vf[1]);
                     static_for<DT>([&](auto T) {
                         constexpr int dt = decltype(T)::value;
@@ -505,6 +604,7 @@ void attn_bf16_kernel(const KernelArgs a)
                     });
                 });
             }
+            sc_cur = sc_nxt;
         }
     }
 

@@ -90,10 +90,11 @@ __device__ __forceinline__ void radix_count(uint32_t x, bool in, int shift, uint
     if (in && (x & hi_mask) == prefix) atomicAdd(&hist[NB - 1 - ((x >> shift) & (NB - 1))], 1u);
 }
 
-template <int BITS>
+// UNR: independent loads in flight per thread (8 for rows in global memory; 1 for the few
+// candidates in LDS, where the instructions of the unused slots would cost more than the latency)
+template <int BITS, int UNR = 8>
 __device__ __forceinline__ void radix_hist_mem(const uint32_t *u, long long n, int shift, uint32_t prefix, uint32_t *hist)
 {
-    constexpr int UNR = 8;      // independent loads in flight per thread
     for (long long j0 = threadIdx.x; j0 < n; j0 += (long long)TK_THREADS * UNR) {
         uint32_t x[UNR];
 #pragma unroll
@@ -163,10 +164,10 @@ __device__ __forceinline__ void radix_pick(int shift, uint32_t &prefix, uint32_t
 }
 
 template <int BITS>
-__device__ __forceinline__ void radix_step_once(const uint32_t *u, long long n, int shift, uint32_t &prefix, uint32_t &want,
+__device__ __forceinline__ void radix_step_once(const uint32_t *u, uint32_t n, int shift, uint32_t &prefix, uint32_t &want,
                                                 uint32_t &bucket, uint32_t *hist, uint32_t *lscan, uint32_t *wtot)
 {
-    radix_hist_mem<BITS>(u, n, shift, prefix, hist);
+    for (uint32_t j = threadIdx.x; j < n; j += TK_THREADS) radix_count<BITS>(u[j], true, shift, prefix, hist);
     radix_pick<BITS>(shift, prefix, want, bucket, hist, lscan, wtot);
 }
 
