@@ -319,12 +319,14 @@ struct AttnGeom {
     // the K-only pass is lighter on registers and runs two workgroups per CU.
     static constexpr int NBUF = WITH_V ? 4 : 3;
     static constexpr int RING_BYTES = NBUF * TileGeom<D>::MAT_BYTES;
+    // the same LDS as NBUF joint K|V tile buffers when scores do not run ahead
+    static constexpr int BUF_BYTES = TileGeom<D>::MAT_BYTES * (WITH_V ? 2 : 1);
     static constexpr int TILE_LDS_BYTES = RING_BYTES * (WITH_V ? 2 : 1);
     static constexpr int LPT = (TileGeom<D>::LOADS / kAttnWaves) * (WITH_V ? 2 : 1);            // loads one wavefront issues per tile
     static constexpr int MAX_WAVES_PER_SIMD = (WITH_V || D > 128) ? 2 : 4;
 };
 
-template <int D, int MODE, bool GATHER>
+template <int D, int MODE, bool GATHER, bool AHEAD>
 __global__ __launch_bounds__(kAttnWaves * 64) __attribute__((amdgpu_waves_per_eu(2, AttnGeom<D, MODE>::MAX_WAVES_PER_SIMD)))
 void attn_bf16_kernel(const KernelArgs a)
 {
@@ -332,7 +334,11 @@ void attn_bf16_kernel(const KernelArgs a)
     using AG = AttnGeom<D, MODE>;
     constexpr int NW = kAttnWaves;
     constexpr bool WITH_V = AG::WITH_V;
-    constexpr int NBUF = AG::NBUF, LPT = AG::LPT, VRING = AG::RING_BYTES;
+    constexpr int NBUF = AG::NBUF, LPT = AG::LPT;
+    // AHEAD: a ring of K tiles then a ring of V tiles (K runs one tile ahead of V); otherwise a
+    // ring of joint K|V buffers
+    constexpr int KPITCH = AHEAD ? G::MAT_BYTES : AG::BUF_BYTES;      // bytes between consecutive ring slots
+    constexpr int VRING = AHEAD ? AG::RING_BYTES : G::MAT_BYTES;       // where V slots start
     constexpr int KS = D / 16;     // MFMA k-steps over the head dimension
     constexpr int DT = D / 32;     // 32-row tiles of O^T
     constexpr int HALF = 32 * G::ROW_BYTES;
@@ -408,7 +414,7 @@ void attn_bf16_kernel(const KernelArgs a)
     long long goff[G::LOADS / NW];
     auto issue = [&](int t, auto IS_V) {
         constexpr bool is_v = decltype(IS_V)::value;
-        const unsigned slot = (is_v ? VRING : 0) + (t % NBUF) * G::MAT_BYTES;
+        const unsigned slot = (is_v ? VRING : 0) + (t % NBUF) * KPITCH;
         const u16 *cache = is_v ? vc : kc, *blk = is_v ? vb : kb;
         if (t < n_full) {
             issue_tile_stream<D, NW, false>(reinterpret_cast<const unsigned char *>(cache + (sr.first + t * sr.step) * cache_stride),
@@ -445,12 +451,18 @@ void attn_bf16_kernel(const KernelArgs a)
         load_idx(0);
         __syncthreads();
     }
-    // load order: K(0), then pairs [V(j), K(j+1)]; loads retire in this order
-    issue_k(0);
+    // load order (loads retire in it).  AHEAD: K(0), then pairs [V(j), K(j+1)].  Otherwise pairs
+    // [K(j), V(j)].  Either way the V request follows the K request of the same tile directly.
+    if constexpr (AHEAD) issue_k(0);
 #pragma unroll
     for (int j = 0; j < NBUF - 1; ++j) {
-        issue_v(j);
-        issue_k(j + 1);
+        if constexpr (AHEAD) {
+            issue_v(j);
+            issue_k(j + 1);
+        } else {
+            issue_k(j);
+            issue_v(j);
+        }
     }
     FragAddr fa = frag_addr<D>(lane);
     fa.k += kh * HALF;                 // this wavefront's half of every tile
@@ -478,30 +490,40 @@ void attn_bf16_kernel(const KernelArgs a)
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) asm volatile("" ::"v"(qf[ks]));
 
-    // Scores run one tile ahead of the softmax: S^T(t+1) is accumulated by the matrix cores while
-    // the vector ALU exponentiates S^T(t), the two interleaved instruction by instruction.
+    // AHEAD: scores run one tile ahead of the softmax: S^T(t+1) is accumulated by the matrix cores
+    // while the vector ALU exponentiates S^T(t), the two interleaved instruction by instruction.
+    // It pays where the loop is long and bound by memory (the tile requests go out earlier in the
+    // iteration); short loops and workgroups that share their tiles with a second row group run the
+    // plain order, which has fewer instructions per tile.
     // sc[v] = score of query row l32 against key kh*32 + 8*(v/4) + 4*lg + v%4
     f32x16_t sc_cur, sc_nxt;
-    if (ntiles >= NBUF) tile_barrier<(NBUF - 1) * LPT>();       // K(0) landed
-    else tile_barrier<0>();
-    if (wave_active) qk_half<D, true>(smem_addr + fa.k, qf, sc_cur);
+    if constexpr (AHEAD) {
+        if (ntiles >= NBUF) tile_barrier<(NBUF - 1) * LPT>();       // K(0) landed
+        else tile_barrier<0>();
+        if (wave_active) qk_half<D, true>(smem_addr + fa.k, qf, sc_cur);
+    }
 
     for (int t = 0; t < ntiles; ++t) {
-        // V(t) and K(t+1) landed (NBUF-2 younger pairs may still be in flight); everyone is done
-        // with K(t) and V(t-1)
-        if (t + NBUF - 1 < ntiles) tile_barrier<(NBUF - 2) * LPT>();
+        // AHEAD: V(t) and K(t+1) landed; otherwise K(t) and V(t).  NBUF-2 younger pairs may still be
+        // in flight; everyone is done with the tiles before.
+        if (t + NBUF - (AHEAD ? 1 : 2) < ntiles) tile_barrier<(NBUF - 2) * LPT>();
         else tile_barrier<0>();
         if (t == 0) MAGE_PROBE_AT(1);
         if (GATHER) {
-            const int tn = t + NBUF;               // the K tile about to be requested (V requests read no entries)
+            const int tn = t + NBUF - (AHEAD ? 0 : 1);   // the K tile about to be requested (V requests read no entries)
             if (tn < sr.cache_tiles && tn >= idx_t0 + kIdxTiles) {   // uniform; every wavefront is past its reads of the old entries
                 load_idx(tn);
                 idx_t0 = tn;
                 __syncthreads();
             }
         }
-        issue_v(t + NBUF - 1);
-        issue_k(t + NBUF);
+        if constexpr (AHEAD) {
+            issue_v(t + NBUF - 1);
+            issue_k(t + NBUF);
+        } else {
+            issue_k(t + NBUF - 1);
+            issue_v(t + NBUF - 1);
+        }
         // keep the per-read address arithmetic inside the loop: hoisted, it would pin dozens of registers
         asm volatile("" : "+v"(fa.k), "+v"(fa.v[0]), "+v"(fa.v[1]));
         if (WITH_V && t == sr.cache_tiles) {   // first in-block tile: freeze the prefix statistics
@@ -516,18 +538,21 @@ void attn_bf16_kernel(const KernelArgs a)
 #endif
             // K fragments of the next tile (its ring slot holds stale data after the last tile: the
             // scores computed from it are never used)
-            const unsigned ka = smem_addr + ((t + 1) % NBUF) * G::MAT_BYTES + fa.k;
-            constexpr int KI = KS <= 8 ? KS : 1;        // k-steps interleaved with the softmax
+            const unsigned ka = smem_addr + ((t + (AHEAD ? 1 : 0)) % NBUF) * KPITCH + fa.k;
+            constexpr bool INTERLEAVE = AHEAD && KS <= 8;    // k-steps of the next tile between the pieces of the softmax
+            constexpr int KI = INTERLEAVE ? KS : 1;
             u32x4_t kf[KI];
-            if constexpr (KS <= 8) {
+            if constexpr (!AHEAD) qk_half<D, true>(ka, qf, sc_cur);
+            if constexpr (INTERLEAVE) {
                 static_for<KS>([&](auto S) {
                     constexpr int i = decltype(S)::value;
                     kf[i] = lds_read_b128<0>(ka ^ (unsigned)(i << 5));
                 });
             }
-            const unsigned vt = smem_addr + VRING + (t % NBUF) * G::MAT_BYTES;
+            const unsigned vt = smem_addr + VRING + (t % NBUF) * KPITCH;
             const unsigned va[2] = {vt + fa.v[0], vt + fa.v[1]};
             u32x2_t vf[2][DT][2];
+            if constexpr (!AHEAD && WITH_V) issue_vt_group<D, 0>(va, vf[0]);      // the first V^T fragments travel while the softmax runs
 
             if (t >= n_full) {                 // uniform: only the last tile of a slice can have padding keys
                 const int valid = tile_valid(t);
@@ -557,7 +582,7 @@ void attn_bf16_kernel(const KernelArgs a)
             }
             const float m_new = m_run;
             float psum = 0.f;
-            if constexpr (KS <= 8) {
+            if constexpr (INTERLEAVE) {
                 constexpr int VPS = 16 / KS;      // scores exponentiated per MFMA k-step
 #pragma unroll
                 for (int v = 0; v < 16; ++v) sc_nxt[v] = 0.f;
@@ -583,7 +608,10 @@ void attn_bf16_kernel(const KernelArgs a)
                     sc_cur[v] = p;
                     psum += p;
                 }
-                qk_half<D, true>(ka, qf, sc_nxt);
+                if constexpr (AHEAD) {
+                    if constexpr (WITH_V) issue_vt_group<D, 0>(va, vf[0]);
+                    qk_half<D, true>(ka, qf, sc_nxt);
+                }
             }
             l_run += psum;
 
@@ -604,7 +632,7 @@ void attn_bf16_kernel(const KernelArgs a)
                     });
                 });
             }
-            sc_cur = sc_nxt;
+            if constexpr (AHEAD) sc_cur = sc_nxt;
         }
     }
 
@@ -888,11 +916,11 @@ __global__ __launch_bounds__(NW * 64) void colsum_bf16_kernel(const KernelArgs a
 }
 
 // ------------------------------------------------------------------------------ launchers
-template <int D, int MODE, bool GATHER>
+template <int D, int MODE, bool GATHER, bool AHEAD>
 static hipError_t launch_attn(const KernelArgs &a, int row_groups, int grid_x, hipStream_t stream)
 {
     dim3 grid(grid_x, a.Hkv, row_groups), block(kAttnWaves * 64);
-    hipLaunchKernelGGL((attn_bf16_kernel<D, MODE, GATHER>), grid, block, 0, stream, a);
+    hipLaunchKernelGGL((attn_bf16_kernel<D, MODE, GATHER, AHEAD>), grid, block, 0, stream, a);
     return hipGetLastError();
 }
 
@@ -904,10 +932,27 @@ static hipError_t launch_colsum(const KernelArgs &a, hipStream_t stream)
     return hipGetLastError();
 }
 
+// Scores one tile ahead (see the kernel) for long, memory-bound tile loops of workgroups that have
+// their tiles to themselves; measured on MI355X, the plain order is faster for shorter loops and
+// where two row groups stream the same tiles.
+static bool scores_ahead(const KernelArgs &a, int row_groups)
+{
+    const long long tiles = (a.nc + kBf16Tile - 1) / kBf16Tile;
+    return row_groups == 1 && tiles / (a.n_cyc > 0 ? a.n_cyc : 1) >= 24;
+}
+
+template <int D>
+static hipError_t launch_attn_any(const KernelArgs &a, int row_groups, bool gather, hipStream_t stream)
+{
+    if (gather) return launch_attn<D, MODE_ATTN, true, false>(a, row_groups, a.n_split, stream);
+    return scores_ahead(a, row_groups) ? launch_attn<D, MODE_ATTN, false, true>(a, row_groups, a.n_split, stream)
+                                       : launch_attn<D, MODE_ATTN, false, false>(a, row_groups, a.n_split, stream);
+}
+
 hipError_t bf16_attn(const KernelArgs &a, int d, int row_groups, bool gather, hipStream_t stream)
 {
-    if (d == 128) return gather ? launch_attn<128, MODE_ATTN, true>(a, row_groups, a.n_split, stream) : launch_attn<128, MODE_ATTN, false>(a, row_groups, a.n_split, stream);
-    if (d == 64) return gather ? launch_attn<64, MODE_ATTN, true>(a, row_groups, a.n_split, stream) : launch_attn<64, MODE_ATTN, false>(a, row_groups, a.n_split, stream);
+    if (d == 128) return launch_attn_any<128>(a, row_groups, gather, stream);
+    if (d == 64) return launch_attn_any<64>(a, row_groups, gather, stream);
     return hipErrorInvalidValue;
 }
 
@@ -916,16 +961,16 @@ hipError_t bf16_attn(const KernelArgs &a, int d, int row_groups, bool gather, hi
 // workgroup and nothing is merged across workgroups.
 hipError_t bf16_attn_batched(const KernelArgs &a, int d, int row_groups, int n_seq, hipStream_t stream)
 {
-    if (d == 128) return launch_attn<128, MODE_ATTN, true>(a, row_groups, n_seq, stream);
-    if (d == 64) return launch_attn<64, MODE_ATTN, true>(a, row_groups, n_seq, stream);
+    if (d == 128) return launch_attn<128, MODE_ATTN, true, false>(a, row_groups, n_seq, stream);
+    if (d == 64) return launch_attn<64, MODE_ATTN, true, false>(a, row_groups, n_seq, stream);
     return hipErrorInvalidValue;
 }
 
 hipError_t bf16_stats(const KernelArgs &a, int d, int row_groups, hipStream_t stream)
 {
-    if (d == 128) return launch_attn<128, MODE_STATS, false>(a, row_groups, a.n_split, stream);
-    if (d == 64) return launch_attn<64, MODE_STATS, false>(a, row_groups, a.n_split, stream);
-    if (d == 256) return launch_attn<256, MODE_STATS, false>(a, row_groups, a.n_split, stream);   // page-summary rows [max | min] of d = 128
+    if (d == 128) return launch_attn<128, MODE_STATS, false, true>(a, row_groups, a.n_split, stream);
+    if (d == 64) return launch_attn<64, MODE_STATS, false, true>(a, row_groups, a.n_split, stream);
+    if (d == 256) return launch_attn<256, MODE_STATS, false, true>(a, row_groups, a.n_split, stream);   // page-summary rows [max | min] of d = 128
     return hipErrorInvalidValue;
 }
 
