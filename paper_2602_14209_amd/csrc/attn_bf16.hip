@@ -564,9 +564,9 @@ void attn_bf16_kernel(const KernelArgs a)
 #pragma unroll
             for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sc_cur[v]);
             {   // the other 16 keys of this row sit in the other half of the wavefront
-                const unsigned mi = __builtin_bit_cast(unsigned, mx);
-                const auto sw = __builtin_amdgcn_permlane32_swap(mi, mi, false, false);
-                mx = fmaxf(__builtin_bit_cast(float, sw[0]), __builtin_bit_cast(float, sw[1])) * a.scale_log2;
+                float lo, hi;
+                lane_halves(mx, lo, hi);
+                mx = fmaxf(lo, hi) * a.scale_log2;
             }
             if (__any(mx > m_run + kLazy)) {      // uniform: some row's maximum has run ahead of its reference
                 const float m_new = fmaxf(m_run, mx);
@@ -798,15 +798,17 @@ __global__ __launch_bounds__(NW * 64) void colsum_bf16_kernel(const KernelArgs a
     unsigned soff[G::LOADS / NW];
     stream_offsets<D, NW>(cache_stride, soff);
     const unsigned lds_wave = __builtin_amdgcn_readfirstlane(lds_addr(smem) + wave * 1024);
+    // all tiles but possibly the last are whole: one comparison per tile in the common case
+    const int n_full = ntiles - ((ntiles > 0 && tile_valid(ntiles - 1) < kBf16Tile) ? 1 : 0);
     auto issue = [&](int t) {
-        const int valid = tile_valid(t);
-        unsigned char *buf = smem + (t % NBUF) * BUF_BYTES;
-        if (valid == kBf16Tile) {
+        if (t < n_full) {
             issue_tile_stream<D, NW, false>(reinterpret_cast<const unsigned char *>(kc + tile_key(t) * cache_stride), 0, soff,
                                             lds_wave + (t % NBUF) * BUF_BYTES);
         } else {
+            const int valid = tile_valid(t);
             const long long base = tile_key(t);
-            issue_tile<D, NW, false>(kc, kc, cache_stride, buf, [&](int r) -> long long { return base + (r < valid ? r : valid - 1); });
+            issue_tile<D, NW, false>(kc, kc, cache_stride, smem + (t % NBUF) * BUF_BYTES,
+                                     [&](int r) -> long long { return base + (r < valid ? r : valid - 1); });
         }
     };
 #pragma unroll
@@ -898,7 +900,11 @@ __global__ __launch_bounds__(NW * 64) void colsum_bf16_kernel(const KernelArgs a
             for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) col[kt] += __builtin_amdgcn_exp2f(fmaf(sc[kt][v], a.scale_log2, -lse2[v]));
-                col[kt] += __shfl_xor(col[kt], 32);
+                {   // the other 16 rows of this key sit in the other half of the wavefront
+                    float lo, hi;
+                    lane_halves(col[kt], lo, hi);
+                    col[kt] = lo + hi;
+                }
             }
         }
         if (lg == 0) {

@@ -81,6 +81,18 @@ __device__ __forceinline__ void vm_wait(u32x4_t &r)
     asm volatile("s_waitcnt vmcnt(%1)" : "+v"(r) : "n"(N));
 }
 
+// Both 32-lane halves of a value, for every lane: lo = x of lane (l % 32), hi = x of lane 32 + l % 32
+// (v_permlane32_swap exchanges the upper half of its first register with the lower half of its
+// second; started from two copies of x, the first ends up all-lower and the second all-upper).
+// Written as assembly: the builtin's two results were merged into one by the optimiser whenever
+// they met in a commutative operation.  The wait states cover a vector-ALU write of x right before.
+__device__ __forceinline__ void lane_halves(float x, float &lo, float &hi)
+{
+    lo = x;
+    hi = x;
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(lo), "+v"(hi));
+}
+
 __device__ __forceinline__ unsigned lds_addr(const void *p) { return (unsigned)(uintptr_t)MAGE_LDS_PTR(p); }
 
 template <int... I, class F>
