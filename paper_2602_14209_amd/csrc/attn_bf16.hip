@@ -974,9 +974,10 @@ hipError_t bf16_attn_batched(const KernelArgs &a, int d, int row_groups, int n_s
 
 hipError_t bf16_stats(const KernelArgs &a, int d, int row_groups, hipStream_t stream)
 {
-    if (d == 128) return launch_attn<128, MODE_STATS, false, true>(a, row_groups, a.n_split, stream);
-    if (d == 64) return launch_attn<64, MODE_STATS, false, true>(a, row_groups, a.n_split, stream);
-    if (d == 256) return launch_attn<256, MODE_STATS, false, true>(a, row_groups, a.n_split, stream);   // page-summary rows [max | min] of d = 128
+    // two workgroups per CU already overlap each other's phases: the plain order measured faster
+    if (d == 128) return launch_attn<128, MODE_STATS, false, false>(a, row_groups, a.n_split, stream);
+    if (d == 64) return launch_attn<64, MODE_STATS, false, false>(a, row_groups, a.n_split, stream);
+    if (d == 256) return launch_attn<256, MODE_STATS, false, false>(a, row_groups, a.n_split, stream);   // page-summary rows [max | min] of d = 128
     return hipErrorInvalidValue;
 }
 
