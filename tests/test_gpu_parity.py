@@ -294,3 +294,27 @@ def test_seeded_random_geometries(oracle_mod, seed):
     k = int(rng.integers(1, min(L, 700) + 1))
     w = Workload(f"rnd{seed}", dtype, Hq=Hkv * G, Hkv=Hkv, d=d, L=L, B=B, ks=(k,), T=2, heavy_frac=0.02, heavy_scale=3.0)
     _run_workload(oracle_mod, w, seed=9000 + seed)
+
+
+@pytest.mark.parametrize("case", [
+    # long single-row-group loops (the scores-one-tile-ahead order of the attention kernel) with a
+    # ragged last tile, for both head dimensions
+    ("a1", "bf16", 8, 8, 64, 49152 + 37, 32, 128),
+    ("a2", "bf16", 16, 8, 128, 65536 + 1, 32, 256),
+])
+def test_long_single_row_group_loops(oracle_mod, case):
+    from gpu_util import Problem, check_alpha, check_index_sets, check_out
+    name, dtype, Hq, Hkv, d, L, B, k = case
+    w = Workload(name, dtype, Hq=Hq, Hkv=Hkv, d=d, L=L, B=B, ks=(k,), T=2, heavy_frac=0.01, heavy_scale=4.0)
+    x = make_layer(w, 4100 + len(name) + d, steps=2)
+    print(f"[parity] {name} L={L} d={d}", flush=True)
+    p = Problem(x["q"][0], x["k_cache"], x["v_cache"], x["k_blk"][0], x["v_blk"][0], k, dtype)
+    o, l = p.exact()
+    o1, l1, idx, alpha = p.step1()
+    rows = [0, 7, 31]
+    o_ref, l_ref = oracle_mod.exact_attn(x["q"][0][rows], x["k_cache"], x["v_cache"], x["k_blk"][0], x["v_blk"][0])
+    check_out(o[rows], o_ref, l[rows], l_ref, dtype)
+    check_out(o1[rows], o_ref, l1[rows], l_ref, dtype)
+    ref = oracle_mod.select(x["q"][0], x["k_cache"], k)
+    check_alpha(alpha, ref["alpha32"])
+    check_index_sets(idx, ref["idx"], ref["alpha32"], L)
