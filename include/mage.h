@@ -83,6 +83,21 @@ int mage_select(const mage_shape *shape, const void *q1, const void *k_cache,
                 void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Block-averaged probabilities per QUERY head (Sec. 3, Eq. 2 written per head; the inner
+ * average of Eq. 5):
+ *   pbar[g,j] = 1/B * sum_q A[g,q,j],   A as in mage_select
+ * so every row of pbar sums to 1 over j, and the mean of the G rows of a KV head's group is
+ * mage_select's alpha.  A diagnostic output (which positions each head of the block looks at);
+ * the index set is taken per KV head by mage_select.
+ * In:  q1 [B,Hq,d], k_cache [L,Hkv,d]; shape as for mage_select (k is validated, not used).
+ * Out: pbar_out [Hq,L] fp32.
+ * Cost: the pass over K that mage_select makes, plus G further passes (one per head of a group).
+ * Same limits as mage_select (B*G <= 256 with MAGE_BF16); workspace as mage_workspace_bytes().
+ */
+int mage_block_probs(const mage_shape *shape, const void *q1, const void *k_cache, float *pbar_out,
+                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Exact attention of the block over the whole cache plus the block itself (Alg. 1 main
  * stream "Attn(Q,K,V,C)"; also the Exact baseline of Sec. 5):
  *   out[q,g,:] = softmax_j( [q.K_cache^T ; q.K_blk^T] / sqrt(d) ) . [V_cache ; V_blk]

@@ -22,7 +22,7 @@ MAGE_BF16 = 1
 MAGE_OK = 0
 
 EXPORTS = ("mage_version", "mage_status_string", "mage_workspace_bytes",
-           "mage_select", "mage_exact_attn", "mage_sparse_attn", "mage_step1",
+           "mage_select", "mage_block_probs", "mage_exact_attn", "mage_sparse_attn", "mage_step1",
            "mage_compact", "mage_sparse_attn_compact", "mage_sparse_attn_batched",
            "mage_page_summary", "mage_quest_workspace_bytes", "mage_quest_select", "mage_set_overlap")
 
@@ -59,6 +59,8 @@ def lib() -> ctypes.CDLL:
         L.mage_workspace_bytes.argtypes = [shp]
         L.mage_select.restype = ctypes.c_int
         L.mage_select.argtypes = [shp, vp, vp, vp, vp, vp, sz, vp]
+        L.mage_block_probs.restype = ctypes.c_int
+        L.mage_block_probs.argtypes = [shp, vp, vp, vp, vp, sz, vp]
         L.mage_exact_attn.restype = ctypes.c_int
         L.mage_exact_attn.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.mage_sparse_attn.restype = ctypes.c_int
@@ -125,6 +127,12 @@ def mage_select(shape: mage_shape, q1, k_cache, idx_out, alpha_out, workspace, s
     """Step-1 selection; see include/mage.h.  Returns the status code (0 = ok)."""
     return lib().mage_select(ctypes.byref(shape), _ptr(q1), _ptr(k_cache), _ptr(idx_out), _ptr(alpha_out),
                              _ptr(workspace), _wsize(workspace), _stream(stream))
+
+
+def mage_block_probs(shape: mage_shape, q1, k_cache, pbar_out, workspace, stream=None) -> int:
+    """Block-averaged probabilities per query head, pbar_out [Hq,L]; see include/mage.h."""
+    return lib().mage_block_probs(ctypes.byref(shape), _ptr(q1), _ptr(k_cache), _ptr(pbar_out),
+                                  _ptr(workspace), _wsize(workspace), _stream(stream))
 
 
 def mage_exact_attn(shape: mage_shape, q, k_cache, v_cache, k_blk, v_blk, out, lse_out, workspace, stream=None) -> int:

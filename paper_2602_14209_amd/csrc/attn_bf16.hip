@@ -779,11 +779,17 @@ __global__ __launch_bounds__(NW * 64) void colsum_bf16_kernel(const KernelArgs a
     __shared__ float ring[kColsumTiles][kBf16Tile];
     static_assert(kColsumTiles % NW == 0, "flush deals the ring slots to the wavefronts");
 
-    const int split = blockIdx.x, h = blockIdx.y;
+    // One grid row per KV head sums all G*B rows of the head (Eq. 5); with head_rows = B there is
+    // one grid row per query head, which sums the B rows of that head alone (Eq. 2 per head).
+    const int split = blockIdx.x, hy = blockIdx.y;
+    const bool per_head = a.head_rows > 0;
+    const int h = per_head ? hy / a.G : hy;                     // KV head whose keys are read
+    const int row_lo = per_head ? (hy % a.G) * a.B : 0;         // first row (of the KV head's row space) summed here
+    const int R = per_head ? a.head_rows : a.R;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, lg = lane >> 5;
     const int row0 = wave * 32;
-    const bool wave_active = row0 < a.R;
+    const bool wave_active = row0 < R;
 
     const SplitRange sr = split_range(a, split);
     const int ntiles = sr.cache_tiles;
@@ -816,16 +822,16 @@ __global__ __launch_bounds__(NW * 64) void colsum_bf16_kernel(const KernelArgs a
         if (t < ntiles) issue(t);
 
     bf16x8_t qf[KS];
-    load_q_frag<D>(a, static_cast<const u16 *>(a.q), h, row0 + l32, qf);
+    load_q_frag<D>(a, static_cast<const u16 *>(a.q), h, row_lo + row0 + l32, qf);
     FragAddr fa = frag_addr<D>(lane);
     const unsigned smem_addr = lds_addr(smem);
 
-    // per-register row statistics: register v is query row row0 + 8*(v/4) + 4*lg + v%4
+    // per-register row statistics: register v is query row row_lo + row0 + 8*(v/4) + 4*lg + v%4
     float lse2[16];
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
         const int r = row0 + 8 * (v >> 2) + 4 * lg + (v & 3);
-        lse2[v] = r < a.R ? a.lse2[(long long)h * a.rpad + r] : INFINITY;   // exp2(-inf) = 0 for padding rows
+        lse2[v] = r < R ? a.lse2[(long long)h * a.rpad + row_lo + r] : INFINITY;   // exp2(-inf) = 0 for rows outside the sum
     }
 
     // The cross-wavefront sum of tile t is finished after the barrier of tile t+1 (the `red`
@@ -866,14 +872,14 @@ __global__ __launch_bounds__(NW * 64) void colsum_bf16_kernel(const KernelArgs a
                 if (live) {
                     v = lds_read_f32<0>(ring_addr + ((t % kColsumTiles) * kBf16Tile + lane) * 4);
                     lds_wait<0>(v);
-                    a.alpha[(long long)h * a.L + tile_key(t) + lane] = v;
+                    a.alpha[(long long)hy * a.L + tile_key(t) + lane] = v;
                 }
                 if (a.gmax != nullptr) {                     // maxima of 16 consecutive keys, for the top-k filter
                     float g = v;
 #pragma unroll
                     for (int d = 1; d < kGroupKeys; d <<= 1) g = fmaxf(g, __shfl_xor(g, d));
                     if (live && (lane & (kGroupKeys - 1)) == 0)
-                        a.gmax[(long long)h * ((a.L + kGroupKeys - 1) / kGroupKeys) + (tile_key(t) + lane) / kGroupKeys] = g;
+                        a.gmax[(long long)hy * ((a.L + kGroupKeys - 1) / kGroupKeys) + (tile_key(t) + lane) / kGroupKeys] = g;
                 }
             }
         }
@@ -933,7 +939,7 @@ static hipError_t launch_attn(const KernelArgs &a, int row_groups, int grid_x, h
 template <int D, int NW>
 static hipError_t launch_colsum(const KernelArgs &a, hipStream_t stream)
 {
-    dim3 grid(a.n_split, a.Hkv), block(NW * 64);
+    dim3 grid(a.n_split, a.head_rows > 0 ? a.Hq : a.Hkv), block(NW * 64);
     hipLaunchKernelGGL((colsum_bf16_kernel<D, NW>), grid, block, 0, stream, a);
     return hipGetLastError();
 }

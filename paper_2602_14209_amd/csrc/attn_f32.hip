@@ -32,13 +32,13 @@ __device__ __forceinline__ F32Range f32_range(const KernelArgs &a, int s)
 
 // rows [row0, row0+64) of KV head h -> LDS, zero-filled past R
 template <int D>
-__device__ __forceinline__ void f32_load_q(const KernelArgs &a, int h, int row0, float (*qs)[D + 1])
+__device__ __forceinline__ void f32_load_q(const KernelArgs &a, int h, int row0, float (*qs)[D + 1], int row_end = 1 << 30)
 {
     const float *q = static_cast<const float *>(a.q);
     for (int e = threadIdx.x; e < kF32Rows * D; e += 256) {
         const int r = e / D, c = e - r * D, row = row0 + r;
         float v = 0.f;
-        if (row < a.R) {
+        if (row < a.R && row < row_end) {
             const int gl = row / a.B, qi = row - gl * a.B;
             v = q[((long long)qi * a.Hq + (long long)h * a.G + gl) * D + c];
         }
@@ -181,10 +181,15 @@ __global__ __launch_bounds__(256) void colsum_f32_kernel(const KernelArgs a)
     __shared__ float ps[kF32Rows][kF32Tile + 1];
     __shared__ float ls[kF32Rows];
 
-    const int h = blockIdx.x, split = blockIdx.y;
+    // one grid column per KV head (all G*B rows, Eq. 5), or with head_rows = B per QUERY head (its B rows, Eq. 2)
+    const int hy = blockIdx.x, split = blockIdx.y;
+    const bool per_head = a.head_rows > 0;
+    const int h = per_head ? hy / a.G : hy;
+    const int row_lo = per_head ? (hy % a.G) * a.B : 0;
+    const int row_end = per_head ? row_lo + a.head_rows : a.R;
     const int r = threadIdx.x >> 2, sub = threadIdx.x & 3;
     const F32Range sr = f32_range(a, split);
-    const int row_groups = a.rpad / kF32Rows;
+    const int row_groups = per_head ? (a.head_rows + kF32Rows - 1) / kF32Rows : a.rpad / kF32Rows;
     const long long stride = (long long)a.Hkv * D;
     const float *kc = static_cast<const float *>(a.kc) + (long long)h * D;
 
@@ -201,10 +206,10 @@ __global__ __launch_bounds__(256) void colsum_f32_kernel(const KernelArgs a)
         for (int rg = 0; rg < row_groups; ++rg) {
             if (rg > 0 || t == 0 || row_groups > 1) {
                 __syncthreads();
-                f32_load_q<D>(a, h, rg * kF32Rows, qs);
+                f32_load_q<D>(a, h, row_lo + rg * kF32Rows, qs, row_end);
                 if (threadIdx.x < kF32Rows) {
-                    const int row = rg * kF32Rows + threadIdx.x;
-                    ls[threadIdx.x] = row < a.R ? a.lse2[(long long)h * a.rpad + row] : INFINITY;
+                    const int row = row_lo + rg * kF32Rows + threadIdx.x;
+                    ls[threadIdx.x] = row < row_end ? a.lse2[(long long)h * a.rpad + row] : INFINITY;
                 }
             }
             __syncthreads();
@@ -221,7 +226,7 @@ __global__ __launch_bounds__(256) void colsum_f32_kernel(const KernelArgs a)
             if (threadIdx.x < kF32Tile)
                 for (int rr = 0; rr < kF32Rows; ++rr) col += ps[rr][threadIdx.x];
         }
-        if (threadIdx.x < kF32Tile && (int)threadIdx.x < valid) a.alpha[(long long)h * a.L + base + threadIdx.x] = col * a.inv_rows;
+        if (threadIdx.x < kF32Tile && (int)threadIdx.x < valid) a.alpha[(long long)hy * a.L + base + threadIdx.x] = col * a.inv_rows;
     }
 }
 
@@ -251,7 +256,7 @@ hipError_t f32_stats(const KernelArgs &a, int d, int row_groups, hipStream_t str
 
 hipError_t f32_colsum(const KernelArgs &a, int d, hipStream_t stream)
 {
-    dim3 grid(a.Hkv, a.n_split), block(256);
+    dim3 grid(a.head_rows > 0 ? a.Hq : a.Hkv, a.n_split), block(256);
     if (d == 128) hipLaunchKernelGGL((colsum_f32_kernel<128>), grid, block, 0, stream, a);
     else if (d == 64) hipLaunchKernelGGL((colsum_f32_kernel<64>), grid, block, 0, stream, a);
     else return hipErrorInvalidValue;

@@ -169,13 +169,13 @@ int run_sparse_bf16(const mage_shape *shape, bool compact, int n_seq, const void
 // that many positions of equal score (its probability is shared among them); shape->d may be 256
 // here (page-summary rows).
 int select_impl(const mage_shape *shape, float scale_log2, int key_weight, const void *q1, const void *k_cache,
-                int32_t *idx_out, float *alpha_out,
+                int32_t *idx_out, float *alpha_out, float *pbar_out,
                 void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    if (!q1 || !k_cache || !idx_out) return MAGE_ERR_NULL;
+    if (!q1 || !k_cache || (!idx_out && !pbar_out)) return MAGE_ERR_NULL;
     const SplitPlan p = plan_stats(*shape), pc = plan_colsum(*shape);
     if (shape->dtype == MAGE_BF16 && p.rpad > 256) return MAGE_ERR_UNSUPPORTED;   // the column-sum pass keeps all rows of a head in one workgroup
-    if (!aligned16(q1) || !aligned16(k_cache) || !aligned16(workspace) || !aligned16(alpha_out)) return MAGE_ERR_ALIGN;
+    if (!aligned16(q1) || !aligned16(k_cache) || !aligned16(workspace) || !aligned16(alpha_out) || !aligned16(pbar_out)) return MAGE_ERR_ALIGN;
     const SelectLayout lay = select_layout(*shape, p);
     if (!workspace || workspace_bytes < lay.bytes) return MAGE_ERR_WORKSPACE;
 
@@ -208,10 +208,20 @@ int select_impl(const mage_shape *shape, float scale_log2, int key_weight, const
     c.kps = pc.kps;
     c.n_split = pc.n_split;
     c.n_cyc = pc.n_cyc;
-    e = bf ? bf16_colsum(c, shape->d, pc.waves, stream) : f32_colsum(c, shape->d, stream);
-    if (e != hipSuccess) return MAGE_ERR_HIP;
-    e = launch_topk(a.alpha, a.gmax, shape->Hkv, shape->L, shape->k, idx_out, stream);
-    if (e != hipSuccess) return MAGE_ERR_HIP;
+    if (idx_out) {
+        e = bf ? bf16_colsum(c, shape->d, pc.waves, stream) : f32_colsum(c, shape->d, stream);
+        if (e != hipSuccess) return MAGE_ERR_HIP;
+        e = launch_topk(a.alpha, a.gmax, shape->Hkv, shape->L, shape->k, idx_out, stream);
+        if (e != hipSuccess) return MAGE_ERR_HIP;
+    }
+    if (pbar_out) {                                  // the same sums restricted to the B rows of one query head at a time
+        c.head_rows = shape->B;
+        c.alpha = pbar_out;
+        c.gmax = nullptr;
+        c.inv_rows = 1.f / ((float)shape->B * (float)key_weight);
+        e = bf ? bf16_colsum(c, shape->d, shape->B > 128 ? 8 : 4, stream) : f32_colsum(c, shape->d, stream);
+        if (e != hipSuccess) return MAGE_ERR_HIP;
+    }
     return MAGE_OK;
 }
 
@@ -256,7 +266,17 @@ int mage_select(const mage_shape *shape, const void *q1, const void *k_cache,
 {
     const int rc = check_shape(shape, true);
     if (rc != MAGE_OK) return rc;
-    return select_impl(shape, (float)(1.4426950408889634 / sqrt((double)shape->d)), 1, q1, k_cache, idx_out, alpha_out,
+    return select_impl(shape, (float)(1.4426950408889634 / sqrt((double)shape->d)), 1, q1, k_cache, idx_out, alpha_out, nullptr,
+                       workspace, workspace_bytes, hip_stream);
+}
+
+int mage_block_probs(const mage_shape *shape, const void *q1, const void *k_cache, float *pbar_out,
+                     void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    const int rc = check_shape(shape, true);
+    if (rc != MAGE_OK) return rc;
+    if (!pbar_out) return MAGE_ERR_NULL;
+    return select_impl(shape, (float)(1.4426950408889634 / sqrt((double)shape->d)), 1, q1, k_cache, nullptr, nullptr, pbar_out,
                        workspace, workspace_bytes, hip_stream);
 }
 
@@ -444,7 +464,7 @@ int mage_quest_select(const mage_shape *shape, int p, const void *q, const void 
     int32_t *pages = reinterpret_cast<int32_t *>(w + lay.pages);
     if (launch_quest_query(q, q2, (long long)shape->B * shape->Hq, shape->d, stream) != hipSuccess) return MAGE_ERR_HIP;
     // the bound is scaled like a logit of the original head dimension
-    const int rs = select_impl(&s2, (float)(1.4426950408889634 / sqrt((double)shape->d)), p, q2, summary, pages, est_out,
+    const int rs = select_impl(&s2, (float)(1.4426950408889634 / sqrt((double)shape->d)), p, q2, summary, pages, est_out, nullptr,
                                w + lay.select, lay.pages - lay.select, hip_stream);
     if (rs != MAGE_OK) return rs;
     if (launch_expand_pages(pages, idx_out, shape->Hkv, shape->k, p, stream) != hipSuccess) return MAGE_ERR_HIP;

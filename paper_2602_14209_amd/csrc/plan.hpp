@@ -166,7 +166,8 @@ struct KernelArgs {
     float *stat_m, *stat_l;  // exact attention, optional: prefix-only (cache keys) statistics per split, as part_m/part_l
     const float *lse2;       // column-sum pass: per-row log2-domain log-sum-exp [Hkv][rpad]
     float *lse2_out;         // combine, optional: the same, merged from stat_m / stat_l
-    float *alpha;            // column-sum pass: [Hkv][L]
+    float *alpha;            // column-sum pass: [Hkv][L] (or [Hq][L] with head_rows)
+    int head_rows;           // column-sum pass: 0, or B = one grid row per QUERY head, summing that head's B rows only (Eq. 2 per head)
     float *gmax;             // column-sum pass, optional: [Hkv][ceil(L / kGroupKeys)] maxima of alpha over groups of consecutive keys
     int B, Hq, Hkv, G, R, rpad;
     long long L;             // rows in the cache

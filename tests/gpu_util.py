@@ -51,6 +51,13 @@ class Problem:
         torch.cuda.synchronize()
         return self.idx.cpu().numpy(), (self.alpha.cpu().numpy() if with_alpha else None)
 
+    def block_probs(self):
+        B, Hq, Hkv, d, L, k = self.dims
+        pbar = torch.empty((Hq, L), dtype=torch.float32, device="cuda")
+        mb.check(mb.mage_block_probs(self.shape, self.q, self.kc, pbar, self.ws), "mage_block_probs")
+        torch.cuda.synchronize()
+        return pbar.cpu().numpy()
+
     def step1(self):
         mb.check(mb.mage_step1(self.shape, self.q, self.kc, self.vc, self.kb, self.vb, self.out, self.lse, self.idx,
                                self.alpha, self.ws), "mage_step1")

@@ -318,3 +318,28 @@ def test_long_single_row_group_loops(oracle_mod, case):
     ref = oracle_mod.select(x["q"][0], x["k_cache"], k)
     check_alpha(alpha, ref["alpha32"])
     check_index_sets(idx, ref["idx"], ref["alpha32"], L)
+
+
+@pytest.mark.parametrize("case", [
+    # name, dtype, Hq, Hkv, d, L, B  -- per-query-head block averages (Eq. 2 per head)
+    ("p1", "bf16", 8, 2, 128, 1000, 32),       # B = 32: one wavefront per head
+    ("p2", "bf16", 14, 2, 64, 777, 5),          # G = 7, B = 5: a head's rows sit inside one M tile
+    ("p3", "bf16", 4, 4, 128, 300, 48),         # B = 48: two M tiles, the second ragged
+    ("p4", "bf16", 1, 1, 128, 4097, 130),       # B > 128: the eight-wavefront column sums
+    ("p5", "f32", 6, 2, 64, 700, 7),
+    ("p6", "f32", 4, 1, 128, 129, 70),          # B > 64: two fp32 row groups per head
+])
+def test_block_probs_per_query_head(oracle_mod, case):
+    from gpu_util import Problem, check_alpha
+    name, dtype, Hq, Hkv, d, L, B = case
+    w = Workload(name, dtype, Hq=Hq, Hkv=Hkv, d=d, L=L, B=B, ks=(1,), T=2, heavy_frac=0.02, heavy_scale=3.0)
+    x = make_layer(w, 5200 + L, steps=1)
+    p = Problem(x["q"][0], x["k_cache"], x["v_cache"], None, None, 1, dtype)
+    pbar = p.block_probs()
+    pbar_ref, alpha_ref = oracle_mod.block_probs(x["q"][0], x["k_cache"])
+    assert pbar.shape == (Hq, L)
+    check_alpha(pbar, pbar_ref.astype(np.float32))            # rows sum to 1, relative error per entry
+    # the mean over a KV head's group is the alpha that mage_select ranks
+    _, alpha = p.select()
+    G = Hq // Hkv
+    np.testing.assert_allclose(pbar.reshape(Hkv, G, L).mean(axis=1), alpha, rtol=2e-5, atol=1e-9)

@@ -122,3 +122,21 @@ def test_second_workload_argument_validation():
     assert L.mage_set_overlap(fake, fake, 0, 8, 1, fake, None) == -2
     assert L.mage_set_overlap(fake, fake, 4, 0, 4, fake, None) == -2
     assert L.mage_set_overlap(fake, fake, 4, 8, 5, fake, None) == -2          # more `a` rows than rows
+
+
+def test_block_probs_argument_validation():
+    """mage_block_probs: argument errors are reported before anything is launched."""
+    L = mb.lib()
+    fake = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1004)
+    big = 1 << 40
+    s = mb.make_shape(32, 32, 8, 128, 4096, 512, "bf16")
+    assert L.mage_block_probs(None, fake, fake, fake, fake, big, None) == -1
+    assert L.mage_block_probs(ctypes.byref(s), fake, fake, None, fake, big, None) == -1
+    assert L.mage_block_probs(ctypes.byref(s), None, fake, fake, fake, big, None) == -1
+    assert L.mage_block_probs(ctypes.byref(s), fake, fake, odd, fake, big, None) == -6
+    assert L.mage_block_probs(ctypes.byref(s), fake, fake, fake, fake, 16, None) == -4
+    bad = mb.make_shape(32, 32, 8, 96, 4096, 512, "bf16")
+    assert L.mage_block_probs(ctypes.byref(bad), fake, fake, fake, fake, big, None) == -3
+    wide = mb.make_shape(128, 32, 8, 128, 4096, 512, "bf16")       # B*G = 512 rows per KV head
+    assert L.mage_block_probs(ctypes.byref(wide), fake, fake, fake, fake, big, None) == -3
