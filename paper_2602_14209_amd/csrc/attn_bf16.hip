@@ -766,8 +766,16 @@ void attn_bf16_kernel(const KernelArgs a)
 
 // Second pass of selection.  Scores are produced untransposed (S = Q K^T: the query fragment
 // is the A operand), so a lane holds 16 query rows of ONE key and the sum over rows is in-lane.
+// Registers are capped so that the LDS, not the register file, decides how many workgroups share
+// a CU: three of the 4-wavefront kind, two of the 8-wavefront kind (d = 256: one fewer).
 template <int D, int NW>
-__global__ __launch_bounds__(NW * 64) void colsum_bf16_kernel(const KernelArgs a)
+struct ColsumGeom {
+    static constexpr int WAVES_PER_SIMD = D > 128 ? 2 : (NW == 8 ? 4 : 3);
+};
+
+template <int D, int NW>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(ColsumGeom<D, NW>::WAVES_PER_SIMD, ColsumGeom<D, NW>::WAVES_PER_SIMD)))
+void colsum_bf16_kernel(const KernelArgs a)
 {
     using G = TileGeom<D>;
     constexpr int KS = D / 16;
@@ -899,18 +907,30 @@ __global__ __launch_bounds__(NW * 64) void colsum_bf16_kernel(const KernelArgs a
         asm volatile("" : "+v"(fa.k));
         float col[2] = {0.f, 0.f};
         if (wave_active) {
-            // sc[kt][v] = score of query row row0 + 8*(v/4) + 4*lg + v%4 against key kt*32 + l32
-            f32x16_t sc[2];
-            qk_tile<D, false>(tile_addr + fa.k, qf, sc);
+            // sc[v] = score of query row row0 + 8*(v/4) + 4*lg + v%4 against key kt*32 + l32
+            auto sum_rows = [&](const f32x16_t &sc, float &col) {
 #pragma unroll
-            for (int kt = 0; kt < 2; ++kt) {
+                for (int v = 0; v < 16; ++v) col += __builtin_amdgcn_exp2f(fmaf(sc[v], a.scale_log2, -lse2[v]));
+                // the other 16 rows of this key sit in the other half of the wavefront
+                float lo, hi;
+                lane_halves(col, lo, hi);
+                col = lo + hi;
+            };
+            if constexpr (NW == 8) {
+                // one key half after the other: half the fragment and score registers, which is what
+                // lets two 8-wavefront workgroups share a CU
+                constexpr int HALF = 32 * G::ROW_BYTES;
 #pragma unroll
-                for (int v = 0; v < 16; ++v) col[kt] += __builtin_amdgcn_exp2f(fmaf(sc[kt][v], a.scale_log2, -lse2[v]));
-                {   // the other 16 rows of this key sit in the other half of the wavefront
-                    float lo, hi;
-                    lane_halves(col[kt], lo, hi);
-                    col[kt] = lo + hi;
+                for (int kt = 0; kt < 2; ++kt) {
+                    f32x16_t sc;
+                    qk_half<D, false>(tile_addr + fa.k + kt * HALF, qf, sc);
+                    sum_rows(sc, col[kt]);
                 }
+            } else {
+                f32x16_t sc[2];
+                qk_tile<D, false>(tile_addr + fa.k, qf, sc);
+                sum_rows(sc[0], col[0]);
+                sum_rows(sc[1], col[1]);
             }
         }
         if (lg == 0) {

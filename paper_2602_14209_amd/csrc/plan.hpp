@@ -56,14 +56,14 @@ inline void plan_rows(const mage_shape &s, SplitPlan &p)
 // Dense pass over all L cache keys.  Exact attention pays a [rows x d] partial per split, so it
 // aims at two workgroups per CU; the two passes of selection leave only a (max, sum) pair per
 // row and split, so they cut the keys much finer (more workgroups in flight, even tail).
-inline SplitPlan plan_dense(const mage_shape &s, int target_workgroups = 0)
+inline SplitPlan plan_dense(const mage_shape &s, int target_workgroups = 0, bool rows_in_one_workgroup = false)
 {
     SplitPlan p{};
     plan_rows(s, p);
     if (target_workgroups == 0) target_workgroups = s.dtype == MAGE_BF16 ? kBf16Workgroups : kTargetWorkgroups;
     const int64_t tiles = (s.L + p.tile - 1) / p.tile;
-    const int64_t target = target_workgroups / ((int64_t)s.Hkv * p.row_groups) > 0
-                               ? target_workgroups / ((int64_t)s.Hkv * p.row_groups) : 1;
+    const int64_t per_split = (int64_t)s.Hkv * (rows_in_one_workgroup ? 1 : p.row_groups);   // workgroups per key split
+    const int64_t target = target_workgroups / per_split > 0 ? target_workgroups / per_split : 1;
     int64_t tps = (tiles + target - 1) / target;     // tiles per split
     const int64_t min_tps = s.dtype == MAGE_BF16 ? 4 : 8;
     if (tps < min_tps) tps = min_tps;
@@ -85,9 +85,14 @@ inline SplitPlan plan_stats(const mage_shape &s)
 // workgroup pays a pipeline fill) and a power-of-two number of them.
 constexpr int kColsumTiles = 8;
 constexpr int kGroupKeys = 16;           // keys per group maximum handed from the column sums to the top-k filter
+// The MFMA kernel keeps all rows of a KV head in one workgroup (4 or 8 wavefronts); its registers
+// and LDS let three 4-wavefront or two 8-wavefront workgroups share a CU.
+constexpr int kColsumWorkgroups4 = 768, kColsumWorkgroups8 = 512;
 inline SplitPlan plan_colsum(const mage_shape &s)
 {
-    return plan_dense(s, s.dtype == MAGE_BF16 ? kStatsWorkgroups : kSelectWorkgroups);
+    if (s.dtype != MAGE_BF16) return plan_dense(s, kSelectWorkgroups);
+    const int R = (s.Hq / s.Hkv) * s.B;
+    return plan_dense(s, R > 128 ? kColsumWorkgroups8 : kColsumWorkgroups4, true);
 }
 
 // Sparse step: k gathered cache keys, in-block keys in a split of their own when k is large
