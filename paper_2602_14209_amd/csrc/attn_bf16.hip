@@ -770,7 +770,7 @@ void attn_bf16_kernel(const KernelArgs a)
 // a CU: three of the 4-wavefront kind, two of the 8-wavefront kind (d = 256: one fewer).
 template <int D, int NW>
 struct ColsumGeom {
-    static constexpr int WAVES_PER_SIMD = D > 128 ? 2 : (NW == 8 ? 4 : 3);
+    static constexpr int WAVES_PER_SIMD = D > 128 ? (NW == 8 ? 2 : 1) : (NW == 8 ? 4 : 3);   // d = 256: one workgroup per CU (100 KB of tiles)
 };
 
 template <int D, int NW>
