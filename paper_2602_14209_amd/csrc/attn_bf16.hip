@@ -1,28 +1,30 @@
 // bf16 MFMA kernels of the MAGE hot path for gfx950 (CDNA4, 64-wide wavefronts).
 //
-//   attn_bf16_kernel<D,NW,MODE,GATHER>
+//   attn_bf16_kernel<D,MODE,GATHER,AHEAD>
 //     MODE_ATTN : split-key flash-style attention of the G*B query rows of one KV head over a
 //                 slice of keys (contiguous cache rows, or cache rows gathered through the
 //                 selected index set, then optionally the in-block keys) -- Alg. 1 main stream
 //                 "Attn(Q,K,V,C)" and Phase 2 "SparseAttn(Q_h,K_h,V_h,C[S])".
-//     MODE_STATS: the same score pass without values: per-row running max and normaliser of
+//     MODE_STATS: the same score pass without values: per-row reference and normaliser of
 //                 softmax(Q1 K^T / sqrt(d)) over the prefix (Alg. 1 select stream, first half).
+//     AHEAD     : order of the tile loop (scores one tile ahead of the softmax, or tile by tile).
 //   colsum_bf16_kernel<D,NW>
 //                 second pass of selection: recomputes the scores, normalises each row with
-//                 its final log-sum-exp and averages over the G*B rows (Eq. 5) -> alpha[h,j].
+//                 its final log-sum-exp and averages over the G*B rows (Eq. 5) -> alpha[h,j];
+//                 per query head (its B rows, Eq. 2) on request.
 //
-// Tiling: one workgroup = NW wavefronts; wavefront w owns 32 query rows (one 32x32 MFMA tile
-// along M); all wavefronts share each 64-key K / V tile.
+// Tiling: attention / statistics: one workgroup = 8 wavefronts = 4 row groups of 32 query rows x
+// 2 halves of every 64-key tile.  Column sums: 4 or 8 wavefronts, each 32 rows x the whole tile.
 //
 // Data movement: tiles go HBM -> LDS directly (global_load_lds, 16 bytes per lane, no VGPR
-// staging), double-buffered, one workgroup barrier per tile.  Rows stay row-major in LDS with an
-// XOR swizzle of their 16-byte chunks, so that
+// staging) into a ring of tile buffers, one workgroup barrier per tile.  Rows stay row-major in LDS
+// with an XOR swizzle of their 16-byte chunks, so that
 //   - the K fragment of a lane (one key row, 8 channels) is one conflict-free ds_read_b128;
 //   - the V fragment (8 keys at one channel) is two transposing reads (ds_read_b64_tr_b16), which
 //     deliver V^T straight from the row-major tile.
 //
 // Scores are produced transposed (S^T = K Q^T, v_mfma_f32_32x32x16_bf16 with the K tile as the A
-// operand): a lane then holds 32 scores of ONE query row, so the online softmax is in-lane work,
+// operand): a lane then holds 16 scores of ONE query row, so the online softmax is in-lane work,
 // and the exponentiated scores are already laid out as the B operand of O^T = V^T P^T.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
