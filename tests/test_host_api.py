@@ -140,3 +140,18 @@ def test_block_probs_argument_validation():
     assert L.mage_block_probs(ctypes.byref(bad), fake, fake, fake, fake, big, None) == -3
     wide = mb.make_shape(128, 32, 8, 128, 4096, 512, "bf16")       # B*G = 512 rows per KV head
     assert L.mage_block_probs(ctypes.byref(wide), fake, fake, fake, fake, big, None) == -3
+
+
+def test_binding_argument_counts_match_the_header():
+    """Every prototype of include/mage.h has as many parameters as the binding marshals."""
+    text = open(os.path.join(ROOT, "include", "mage.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    protos = re.findall(r"\b(mage_[a-z0-9_]+)\s*\(([^;{]*?)\)\s*;", text, flags=re.S)
+    assert len(protos) == len(mb.EXPORTS)
+    lib = mb.lib()
+    for name, params in protos:
+        params = params.strip()
+        n = 0 if params in ("", "void") else params.count(",") + 1
+        argtypes = getattr(lib, name).argtypes
+        assert argtypes is not None or n == 0, name
+        assert len(argtypes or []) == n, (name, n, len(argtypes or []))
