@@ -440,3 +440,32 @@ def test_overlap_is_set_intersection_over_k(oracle_mod):
         assert oracle_mod.overlap(b, a) == want
         assert oracle_mod.overlap(a, a[::-1].copy()) == 1.0
         assert oracle_mod.overlap(a, (a + 1000).astype(np.int32)) == 0.0
+
+
+def test_worked_example_fixture(oracle_mod):
+    """tests/golden/worked_example.json: the oracle reproduces its stored output exactly, and the stored
+    alpha of position 0 equals the closed form.  The four rows' logits over the six keys are small
+    integers (a logit is (q0*k0 + q1*k1)/8 with q in {(8,0),(0,8),(8,8),(-8,0)}):
+      row (q0,g0): k0        = [1,0,1,-1,2,1]     row (q0,g1): k1  = [0,1,1,0,0,0]
+      row (q1,g0): k0 + k1   = [1,1,2,-1,2,1]     row (q1,g1): -k0 = [-1,0,-1,1,-2,-1]
+    alpha[0] = 1/4 (e/Z1 + 1/Z2 + e/Z3 + e^-1/Z4) (Eq. 5); positions 0 and 5 hold equal keys (a tie)."""
+    import importlib.util
+    import json
+    import math
+    import os
+    here = os.path.dirname(os.path.abspath(__file__))
+    spec = importlib.util.spec_from_file_location("make_worked_example", os.path.join(here, "golden", "make_worked_example.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    stored = json.load(open(os.path.join(here, "golden", "worked_example.json")))
+    assert mod.compute() == stored
+    e = math.e
+    z1 = 3 * e + 1 + 1 / e + e * e
+    z2 = 4 + 2 * e
+    z3 = 3 * e + 2 * e * e + 1 / e
+    z4 = 3 / e + 1 + e + 1 / (e * e)
+    alpha = [float.fromhex(x) for x in stored["alpha_fp64"]]
+    assert abs(alpha[0] - 0.25 * (e / z1 + 1 / z2 + e / z3 + (1 / e) / z4)) < 1e-15
+    assert abs(alpha[4] - 0.25 * (e * e / z1 + 1 / z2 + e * e / z3 + (1 / (e * e)) / z4)) < 1e-15
+    assert alpha[0] == alpha[5] and abs(sum(alpha) - 1.0) < 1e-15
+    assert stored["idx"] == [[2, 4]]
