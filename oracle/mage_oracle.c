@@ -30,6 +30,10 @@
  * The second workload at the end of this file (page estimator, set overlap) is pinned on numpy
  * block max/min, on page size 1 being the exact selection, on pages of identical rows (bound
  * exact), on a hand-computed sign-aware bound, and on python set intersection.
+ * tests/test_oracle_mutations.py plants plausible mistakes in a copy of this file and requires every
+ * one of them to fail a pin; tests/test_oracle_sanitizers.py runs every entry point under
+ * AddressSanitizer and UndefinedBehaviorSanitizer; tests/golden/ holds a worked example small enough
+ * to follow by hand.  No function of this file is unpinned.
  */
 #include <math.h>
 #include <stdint.h>
