@@ -1,0 +1,140 @@
+"""Static checks of the gfx950 code objects that the kernel sources compile to (cross-compiled here, no
+GPU needed).  They guard assumptions that the hand-written parts of the kernels rely on and that a
+compiler or flag change could silently break:
+
+* no kernel spills registers or uses scratch memory;
+* the register and LDS budgets behind the planned occupancy (workgroups per CU) hold;
+* in the tile kernels every scalar memory load sits in the prologue, before the first LDS fragment
+  read: their LDS waits are hand-placed counts, and a scalar load in flight (same counter, out-of-order
+  return) would make a count pass early;
+* a scalar register written by a vector instruction (v_readfirstlane / v_readlane) is not used as the
+  base of a vector-memory instruction before five wait states have passed -- the compiler inserts the
+  wait states for its own instructions, but cannot for a load written as inline assembly.
+"""
+import os
+import re
+import subprocess
+
+import pytest
+
+from paper_2602_14209_amd import build as mbuild
+
+LLVM = "/opt/rocm/llvm/bin"
+CSRC = mbuild.CSRC
+
+
+def _code_object(tmp, name):
+    co, elf = os.path.join(tmp, name + ".co"), os.path.join(tmp, name + ".elf")
+    flags = [f for f in mbuild.FLAGS if f not in ("-shared", "-Wall", "-Wno-unused-function")]
+    subprocess.run(["hipcc", "--genco", *flags, "-I", os.path.join(os.path.dirname(os.path.dirname(CSRC)), "include"),
+                    os.path.join(CSRC, name + ".hip"), "-o", co], check=True, capture_output=True)
+    subprocess.run([os.path.join(LLVM, "clang-offload-bundler"), "--unbundle", "--type=o", "--input=" + co,
+                    "--targets=hipv4-amdgcn-amd-amdhsa--gfx950", "--output=" + elf], check=True, capture_output=True)
+    notes = subprocess.run([os.path.join(LLVM, "llvm-readelf"), "--notes", elf], check=True, capture_output=True, text=True).stdout
+    dis = subprocess.run([os.path.join(LLVM, "llvm-objdump"), "-d", elf], check=True, capture_output=True, text=True).stdout
+    meta = {}
+    for blk in notes.split("- .agpr_count:")[1:]:
+        g = lambda key: int(re.search(r"\.%s:\s+(\d+)" % key, blk).group(1))
+        sym = re.search(r"\.name:\s+(\S+)", blk).group(1)
+        meta[sym] = {"agpr": int(blk.split()[0]), "vgpr": g("vgpr_count"), "lds": g("group_segment_fixed_size"),
+                     "scratch": g("private_segment_fixed_size"), "vspill": g("vgpr_spill_count")}
+    kernels, cur = {}, None
+    for ln in dis.splitlines():
+        m = re.match(r"^[0-9a-f]+ <(\S+)>:", ln)
+        if m:
+            cur = kernels.setdefault(m.group(1), [])
+            continue
+        if cur is not None and ln.strip():
+            cur.append(ln.split("//")[0].strip())
+    return meta, kernels
+
+
+def _demangle(sym):
+    return subprocess.run(["c++filt", sym], capture_output=True, text=True).stdout.strip().split("(")[0].replace("void ", "")
+
+
+def _sgpr_hazards(ins):
+    """vector-memory instructions whose scalar base was written by a vector instruction fewer than five
+    wait states earlier"""
+    bad = []
+    for i, s in enumerate(ins):
+        if not re.match(r"(global|buffer|flat|scratch)_", s):
+            continue
+        m = re.search(r"\bs\[(\d+):(\d+)\]", s)
+        if not m:
+            continue
+        regs = set(range(int(m.group(1)), int(m.group(2)) + 1))
+        states = 0
+        for j in range(i - 1, max(i - 8, -1), -1):
+            p = ins[j]
+            w = re.match(r"v_read(firstlane|lane)_b32 s(\d+)", p)
+            if w and int(w.group(2)) in regs and states < 5:
+                bad.append((p, s, states))
+            nop = re.match(r"s_nop (\d+)", p)
+            states += int(nop.group(1)) + 1 if nop else 1
+            if states >= 5:
+                break
+    return bad
+
+
+@pytest.fixture(scope="module")
+def objects(tmp_path_factory):
+    tmp = str(tmp_path_factory.mktemp("co"))
+    return {n: _code_object(tmp, n) for n in ("attn_bf16", "sparse_bf16", "topk")}
+
+
+def test_no_spills_no_scratch_and_budgets(objects):
+    budgets = {                                   # demangled prefix -> (max VGPR+AGPR, max LDS bytes)
+        "mage::attn_bf16_kernel<128, 0": (256, 136 * 1024),     # attention: 2 wavefronts per SIMD, one workgroup per CU
+        "mage::attn_bf16_kernel<64, 0": (256, 80 * 1024),
+        "mage::attn_bf16_kernel<128, 1": (128, 80 * 1024),      # row statistics: 4 per SIMD, two workgroups per CU
+        "mage::attn_bf16_kernel<64, 1": (128, 80 * 1024),
+        "mage::attn_bf16_kernel<256, 1": (256, 160 * 1024),
+        "mage::colsum_bf16_kernel<128, 4>": (168, 53 * 1024 + 256),   # three workgroups per CU
+        "mage::colsum_bf16_kernel<64, 4>": (168, 53 * 1024 + 256),
+        "mage::colsum_bf16_kernel<128, 8>": (128, 80 * 1024),   # two workgroups per CU
+        "mage::colsum_bf16_kernel<64, 8>": (128, 80 * 1024),
+        "mage::colsum_bf16_kernel<256": (512, 160 * 1024),
+        "mage::sparse_bf16_kernel": (256, 160 * 1024),
+        "mage::compact_kernel": (128, 0),
+        "mage::topk_kernel": (128, 160 * 1024),                 # 16 wavefronts = 4 per SIMD
+    }
+    seen = set()
+    for meta, _ in objects.values():
+        for sym, m in meta.items():
+            name = _demangle(sym)
+            assert m["scratch"] == 0 and m["vspill"] == 0, (name, m)
+            keys = [k for k in budgets if name.startswith(k)]
+            assert keys, f"no budget recorded for {name}"
+            regs, lds = budgets[max(keys, key=len)]
+            assert m["vgpr"] + m["agpr"] <= regs and m["lds"] <= lds, (name, m, regs, lds)
+            seen.add(max(keys, key=len))
+    assert seen == set(budgets)
+
+
+def test_scalar_loads_stay_in_the_prologue_of_the_tile_kernels(objects):
+    _, kernels = objects["attn_bf16"]
+    checked = 0
+    for sym, ins in kernels.items():
+        if "attn_bf16_kernel" not in sym and "colsum_bf16_kernel" not in sym:
+            continue
+        first_lds = next(i for i, s in enumerate(ins) if s.startswith("ds_read"))
+        late = [(i, s) for i, s in enumerate(ins) if re.match(r"s_(buffer_)?load|s_mem", s) and i > first_lds]
+        assert not late, (_demangle(sym), late[:3])
+        checked += 1
+    assert checked >= 15
+
+
+def test_vector_written_scalar_bases_are_five_wait_states_old(objects):
+    for _, kernels in objects.values():
+        for sym, ins in kernels.items():
+            bad = _sgpr_hazards(ins)
+            assert not bad, (_demangle(sym), bad[:3])
+
+
+def test_hazard_scan_notices_a_planted_hazard():
+    ins = ["v_readfirstlane_b32 s8, v1", "v_mul_u32_u24_e32 v56, s18, v66", "v_readfirstlane_b32 s9, v58",
+           "global_load_dwordx4 v[132:135], v56, s[8:9]"]
+    assert _sgpr_hazards(ins)
+    ok = ins[:3] + ["s_nop 4"] + ins[3:]
+    assert not _sgpr_hazards(ok)
