@@ -80,7 +80,7 @@ def _sgpr_hazards(ins):
 @pytest.fixture(scope="module")
 def objects(tmp_path_factory):
     tmp = str(tmp_path_factory.mktemp("co"))
-    return {n: _code_object(tmp, n) for n in ("attn_bf16", "sparse_bf16", "topk")}
+    return {n: _code_object(tmp, n) for n in ("attn_bf16", "sparse_bf16", "topk", "reduce", "quest", "attn_f32")}
 
 
 def test_no_spills_no_scratch_and_budgets(objects):
@@ -98,6 +98,15 @@ def test_no_spills_no_scratch_and_budgets(objects):
         "mage::sparse_bf16_kernel": (256, 160 * 1024),
         "mage::compact_kernel": (128, 0),
         "mage::topk_kernel": (128, 160 * 1024),                 # 16 wavefronts = 4 per SIMD
+        # small kernels and the fp32 vector path: 256 threads per workgroup, at least two workgroups per CU
+        "mage::combine_kernel": (128, 8 * 1024),
+        "mage::lse_kernel": (128, 1024),
+        "mage::page_summary_kernel": (128, 1024),
+        "mage::quest_query_kernel": (128, 1024),
+        "mage::expand_pages_kernel": (128, 1024),
+        "mage::overlap_kernel": (128, 1024),
+        "mage::attn_f32_kernel": (256, 80 * 1024),              # two workgroups per CU by LDS
+        "mage::colsum_f32_kernel": (256, 64 * 1024),
     }
     seen = set()
     for meta, _ in objects.values():
