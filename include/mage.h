@@ -65,7 +65,9 @@ int mage_version(void);
 const char *mage_status_string(int status);
 
 /* Bytes of device workspace that any of the calls below needs for `shape`
- * (the maximum over them).  Host only, pure.  Returns 0 if `shape` is invalid. */
+ * (the maximum over the calls that support the shape: a bf16 shape with B*G > 256 still gets the
+ * size its attention calls need, although mage_select and mage_step1 reject it).  Host only, pure.
+ * Returns 0 if `shape` is invalid. */
 size_t mage_workspace_bytes(const mage_shape *shape);
 
 /*
@@ -214,6 +216,35 @@ int mage_quest_select(const mage_shape *shape, int p, const void *q, const void 
  *      b [n_rows,k] int32, rows duplicate-free, any order.  Out: out [n_rows] fp32.
  */
 int mage_set_overlap(const int32_t *a, const int32_t *b, int n_rows, int k, int a_rows, float *out, void *hip_stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Measurement aids (not part of the method): the floors and ceilings the benchmark prints beside the
+ * attention figures, so that a latency-bound launch can be told from a bandwidth-bound one.
+ * ------------------------------------------------------------------------------------------- */
+
+/* One kernel that does nothing: the cost of a launch slot in a stream or a HIP graph. */
+int mage_diag_empty(void *hip_stream);
+
+/* One lane follows n_hops dependent loads: i = chain[i], from i = start; the last i goes to *out.
+ * chain [n_entries] int32, every entry in [0, n_entries) (a precondition).  Time / n_hops is the
+ * latency of one dependent memory round trip (the sparse step has two: index entry, then row). */
+int mage_diag_chase(const int32_t *chain, int64_t n_entries, int start, int n_hops, int32_t *out, void *hip_stream);
+
+/* Streaming read of `bytes` bytes (16-byte loads on every CU); sink [4096] uint32 is scratch that is
+ * practically never written.  bytes / time is the read bandwidth this GPU reaches. */
+int mage_diag_read(const void *src, size_t bytes, uint32_t *sink, void *hip_stream);
+
+/* Streaming copy dst[0:bytes) = src[0:bytes) (whole 16-byte units; a tail shorter than 16 bytes is not
+ * copied).  2 * bytes / time is the copy bandwidth; it also is the kernel of known traffic that the
+ * profiler's byte counters are scaled with. */
+int mage_diag_copy(void *dst, const void *src, size_t bytes, void *hip_stream);
+
+/* The memory accesses of mage_sparse_attn_batched and nothing else: reads idx [n_seq,Hkv,k] and, for
+ * every entry, that row of k_cache and of v_cache [n_seq,L,Hkv,d].  The rate at which the gather
+ * itself can run on this GPU (a ceiling for the sparse step).  d * element size <= 256 bytes.
+ * sink [1] uint32 is practically never written. */
+int mage_diag_gather(const mage_shape *shape, int n_seq, const void *k_cache, const void *v_cache, const int32_t *idx,
+                     uint32_t *sink, void *hip_stream);
 
 #ifdef __cplusplus
 }

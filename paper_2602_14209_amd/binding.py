@@ -24,7 +24,8 @@ MAGE_OK = 0
 EXPORTS = ("mage_version", "mage_status_string", "mage_workspace_bytes",
            "mage_select", "mage_block_probs", "mage_exact_attn", "mage_sparse_attn", "mage_step1",
            "mage_compact", "mage_sparse_attn_compact", "mage_sparse_attn_batched",
-           "mage_page_summary", "mage_quest_workspace_bytes", "mage_quest_select", "mage_set_overlap")
+           "mage_page_summary", "mage_quest_workspace_bytes", "mage_quest_select", "mage_set_overlap",
+           "mage_diag_empty", "mage_diag_chase", "mage_diag_read", "mage_diag_copy", "mage_diag_gather")
 
 
 class mage_shape(ctypes.Structure):
@@ -81,6 +82,16 @@ def lib() -> ctypes.CDLL:
         L.mage_quest_select.argtypes = [shp, ctypes.c_int, vp, vp, vp, vp, vp, sz, vp]
         L.mage_set_overlap.restype = ctypes.c_int
         L.mage_set_overlap.argtypes = [vp, vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp]
+        L.mage_diag_empty.restype = ctypes.c_int
+        L.mage_diag_empty.argtypes = [vp]
+        L.mage_diag_chase.restype = ctypes.c_int
+        L.mage_diag_chase.argtypes = [vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int, vp, vp]
+        L.mage_diag_read.restype = ctypes.c_int
+        L.mage_diag_read.argtypes = [vp, sz, vp, vp]
+        L.mage_diag_copy.restype = ctypes.c_int
+        L.mage_diag_copy.argtypes = [vp, vp, sz, vp]
+        L.mage_diag_gather.restype = ctypes.c_int
+        L.mage_diag_gather.argtypes = [shp, ctypes.c_int, vp, vp, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -197,6 +208,27 @@ def mage_quest_select(shape: mage_shape, p: int, q, summary, idx_out, est_out, w
 def mage_set_overlap(a, b, n_rows: int, k: int, a_rows: int, out, stream=None) -> int:
     """out[i] = |A_(i mod a_rows) & B_i| / k (Eq. 1, Eq. 3); see include/mage.h."""
     return lib().mage_set_overlap(_ptr(a), _ptr(b), int(n_rows), int(k), int(a_rows), _ptr(out), _stream(stream))
+
+
+def mage_diag_empty(stream=None) -> int:
+    return lib().mage_diag_empty(_stream(stream))
+
+
+def mage_diag_chase(chain, start: int, n_hops: int, out, stream=None) -> int:
+    return lib().mage_diag_chase(_ptr(chain), chain.numel(), int(start), int(n_hops), _ptr(out), _stream(stream))
+
+
+def mage_diag_read(src, sink, stream=None) -> int:
+    return lib().mage_diag_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream(stream))
+
+
+def mage_diag_copy(dst, src, stream=None) -> int:
+    return lib().mage_diag_copy(_ptr(dst), _ptr(src), src.numel() * src.element_size(), _stream(stream))
+
+
+def mage_diag_gather(shape: mage_shape, n_seq: int, k_cache, v_cache, idx, sink, stream=None) -> int:
+    return lib().mage_diag_gather(ctypes.byref(shape), int(n_seq), _ptr(k_cache), _ptr(v_cache), _ptr(idx), _ptr(sink),
+                                  _stream(stream))
 
 
 def check(status: int, where: str = "mage") -> None:

@@ -31,7 +31,6 @@
 
 #include "lds_asm.hpp"
 #include "plan.hpp"
-#include "probe.hpp"
 
 namespace mage {
 
@@ -369,8 +368,6 @@ void attn_bf16_kernel(const KernelArgs a)
     const int row = row0 + l32;
     const bool wave_active = row0 < a.R;
 
-    MAGE_PROBE_DECL;
-    MAGE_PROBE_AT(0);
     const SplitRange sr = split_range(a, split);
     const int ntiles = sr.cache_tiles + sr.blk_tiles;
 
@@ -510,7 +507,6 @@ void attn_bf16_kernel(const KernelArgs a)
         // in flight; everyone is done with the tiles before.
         if (t + NBUF - (AHEAD ? 1 : 2) < ntiles) tile_barrier<(NBUF - 2) * LPT>();
         else tile_barrier<0>();
-        if (t == 0) MAGE_PROBE_AT(1);
         if (GATHER) {
             const int tn = t + NBUF - (AHEAD ? 0 : 1);   // the K tile about to be requested (V requests read no entries)
             if (tn < sr.cache_tiles && tn >= idx_t0 + kIdxTiles) {   // uniform; every wavefront is past its reads of the old entries
@@ -533,11 +529,7 @@ void attn_bf16_kernel(const KernelArgs a)
             l_pre = l_run;
         }
 
-#ifdef MAGE_PROBE_NO_COMPUTE
-        if (false) {
-#else
         if (wave_active) {
-#endif
             // K fragments of the next tile (its ring slot holds stale data after the last tile: the
             // scores computed from it are never used)
             const unsigned ka = smem_addr + ((t + (AHEAD ? 1 : 0)) % NBUF) * KPITCH + fa.k;
@@ -644,7 +636,6 @@ void attn_bf16_kernel(const KernelArgs a)
         m_pre = m_run;
         lp_tot = l_tot;
     }
-    MAGE_PROBE_AT(2);
 
     // Merge of the two key halves.  Both wavefronts of a row group end up with the merged
     // statistics, and each finishes one half of the channels: it hands the other half of its
@@ -751,8 +742,6 @@ void attn_bf16_kernel(const KernelArgs a)
         if (kh == 0) put_out(std::integral_constant<int, 0>{});
         else put_out(std::integral_constant<int, HDT>{});
     }
-    MAGE_PROBE_AT(3);
-    MAGE_PROBE_FLUSH();
     if (!owner || row >= a.R || lg != 0) return;
     if (direct) {
         if (a.lse_out) {

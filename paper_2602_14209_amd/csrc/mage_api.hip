@@ -77,11 +77,11 @@ void carve_partials(const mage_shape &s, const SplitPlan &p, void *workspace, Ke
     a.part_l = reinterpret_cast<float *>(w);
 }
 
-int run_attention(const mage_shape *shape, const SplitPlan &p, bool gather,
-                  const void *q, const void *k_cache, const void *v_cache, const int32_t *idx,
-                  const void *k_blk, const void *v_blk, float *out, float *lse_out,
-                  void *workspace, size_t workspace_bytes, void *hip_stream,
-                  float *stat_m = nullptr, float *stat_l = nullptr, float *lse2_out = nullptr)
+// Launch-free argument check of an attention call (exact, or sparse through the tiled kernels).
+int attention_check(const mage_shape *shape, const SplitPlan &p, bool gather,
+                    const void *q, const void *k_cache, const void *v_cache, const int32_t *idx,
+                    const void *k_blk, const void *v_blk, const float *out,
+                    const void *workspace, size_t workspace_bytes)
 {
     if (!q || !k_cache || !v_cache || !out || (gather && !idx)) return MAGE_ERR_NULL;
     if ((k_blk == nullptr) != (v_blk == nullptr)) return MAGE_ERR_NULL;
@@ -89,6 +89,17 @@ int run_attention(const mage_shape *shape, const SplitPlan &p, bool gather,
         !aligned16(out) || !aligned16(workspace))
         return MAGE_ERR_ALIGN;
     if (p.n_split > 1 && (!workspace || workspace_bytes < partial_bytes(*shape, p))) return MAGE_ERR_WORKSPACE;
+    return MAGE_OK;
+}
+
+int run_attention(const mage_shape *shape, const SplitPlan &p, bool gather,
+                  const void *q, const void *k_cache, const void *v_cache, const int32_t *idx,
+                  const void *k_blk, const void *v_blk, float *out, float *lse_out,
+                  void *workspace, size_t workspace_bytes, void *hip_stream,
+                  float *stat_m = nullptr, float *stat_l = nullptr, float *lse2_out = nullptr)
+{
+    const int rc = attention_check(shape, p, gather, q, k_cache, v_cache, idx, k_blk, v_blk, out, workspace, workspace_bytes);
+    if (rc != MAGE_OK) return rc;
 
     KernelArgs a = base_args(*shape, p);
     a.q = q;
@@ -168,16 +179,27 @@ int run_sparse_bf16(const mage_shape *shape, bool compact, int n_seq, const void
 // geometry.  `scale_log2` = log2(e) times the factor on the logit; `key_weight`: every key stands for
 // that many positions of equal score (its probability is shared among them); shape->d may be 256
 // here (page-summary rows).
+// Launch-free argument check of the selection pipeline (everything select_impl can reject).
+int select_check(const mage_shape *shape, const void *q1, const void *k_cache,
+                 const int32_t *idx_out, const float *alpha_out, const float *pbar_out,
+                 const void *workspace, size_t workspace_bytes)
+{
+    if (!q1 || !k_cache || (!idx_out && !pbar_out)) return MAGE_ERR_NULL;
+    const SplitPlan p = plan_stats(*shape);
+    if (shape->dtype == MAGE_BF16 && p.rpad > 256) return MAGE_ERR_UNSUPPORTED;   // the column-sum pass keeps all rows of a head in one workgroup
+    if (!aligned16(q1) || !aligned16(k_cache) || !aligned16(workspace) || !aligned16(alpha_out) || !aligned16(pbar_out)) return MAGE_ERR_ALIGN;
+    if (!workspace || workspace_bytes < select_layout(*shape, p).bytes) return MAGE_ERR_WORKSPACE;
+    return MAGE_OK;
+}
+
 int select_impl(const mage_shape *shape, float scale_log2, int key_weight, const void *q1, const void *k_cache,
                 int32_t *idx_out, float *alpha_out, float *pbar_out,
                 void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    if (!q1 || !k_cache || (!idx_out && !pbar_out)) return MAGE_ERR_NULL;
+    const int rc = select_check(shape, q1, k_cache, idx_out, alpha_out, pbar_out, workspace, workspace_bytes);
+    if (rc != MAGE_OK) return rc;
     const SplitPlan p = plan_stats(*shape), pc = plan_colsum(*shape);
-    if (shape->dtype == MAGE_BF16 && p.rpad > 256) return MAGE_ERR_UNSUPPORTED;   // the column-sum pass keeps all rows of a head in one workgroup
-    if (!aligned16(q1) || !aligned16(k_cache) || !aligned16(workspace) || !aligned16(alpha_out) || !aligned16(pbar_out)) return MAGE_ERR_ALIGN;
     const SelectLayout lay = select_layout(*shape, p);
-    if (!workspace || workspace_bytes < lay.bytes) return MAGE_ERR_WORKSPACE;
 
     char *w = static_cast<char *>(workspace);
     KernelArgs a = base_args(*shape, p);
@@ -288,7 +310,10 @@ int mage_step1(const mage_shape *shape, const void *q1, const void *k_cache, con
     if (rc != MAGE_OK) return rc;
     if (!idx_out) return MAGE_ERR_NULL;
     if (shape->dtype != MAGE_BF16) {
-        // fp32: the two calls back to back (no shared pass in the vector path)
+        // fp32: the two calls back to back (no shared pass in the vector path); both are validated
+        // before the first one launches anything
+        rc = select_check(shape, q1, k_cache, idx_out, alpha_out, nullptr, workspace, workspace_bytes);
+        if (rc != MAGE_OK) return rc;
         rc = run_attention(shape, plan_dense(*shape), false, q1, k_cache, v_cache, nullptr, k_blk, v_blk, out, lse_out,
                            workspace, workspace_bytes, hip_stream);
         if (rc != MAGE_OK) return rc;
@@ -462,6 +487,8 @@ int mage_quest_select(const mage_shape *shape, int p, const void *q, const void 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     void *q2 = w + lay.q2;
     int32_t *pages = reinterpret_cast<int32_t *>(w + lay.pages);
+    const int rv = select_check(&s2, q2, summary, pages, est_out, nullptr, w + lay.select, lay.pages - lay.select);
+    if (rv != MAGE_OK) return rv;                    // nothing has been launched yet
     if (launch_quest_query(q, q2, (long long)shape->B * shape->Hq, shape->d, stream) != hipSuccess) return MAGE_ERR_HIP;
     // the bound is scaled like a logit of the original head dimension
     const int rs = select_impl(&s2, (float)(1.4426950408889634 / sqrt((double)shape->d)), p, q2, summary, pages, est_out, nullptr,

@@ -21,7 +21,6 @@
 
 #include "lds_asm.hpp"
 #include "plan.hpp"
-#include "probe.hpp"
 
 namespace mage {
 
@@ -65,8 +64,6 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
     const int l16 = lane & 15, lg4 = lane >> 4;
     const int row = rt * 16 + l16;
 
-    MAGE_PROBE_DECL;
-    MAGE_PROBE_AT(0);
     const int n_keys = (int)a.nc + a.n_blk;
     const int ntiles = (n_keys + SP_KT - 1) / SP_KT;
     const int npass = (ntiles + SP_MAXT - 1) / SP_MAXT;
@@ -187,7 +184,6 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
                 });
             });
         }
-        MAGE_PROBE_AT(1);
         // ---- scores: sc[j][v] = S^T(key 4*lg4 + v of tile j, query row l16) ----
         f32x4_t sc[SP_TPW];
         float mx = -INFINITY;
@@ -223,11 +219,9 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
             for (int dt = 0; dt < DT; ++dt) o[dt] *= corr;
         }
 
-        MAGE_PROBE_AT(2);
         // ---- O^T += V^T P^T, 32 key positions (two tiles) per MFMA ----
         // V tiles are consumed as they land: before the MFMAs of tiles 2s and 2s+1 the wavefront
         // waits only until its direct loads of those tiles are done (loads retire in issue order).
-        MAGE_PROBE_AT(3);
         // V^T fragments by transposing LDS reads (inline assembly, see lds_asm.hpp), kPre O^T tiles
         // ahead of the MFMA that consumes them.  The swizzle and the O^T tile both act on address
         // bits 4..7 only: address = (lane constant + compile-time slot offset) ^ (dt << 5).
@@ -277,12 +271,10 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // slots past this wavefront's last tile were loaded too
     }
 
-    MAGE_PROBE_AT(4);
     // ---- merge the eight wavefronts through LDS ----
     float l_w = l_run + __shfl_xor(l_run, 16);
     l_w += __shfl_xor(l_w, 32);
     __syncthreads();                                         // every wavefront is done reading V
-    MAGE_PROBE_AT(6);
     if (lg4 == 0) {
         ml[0][wave][l16] = m_run;
         ml[1][wave][l16] = l_w;
@@ -291,7 +283,6 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) part[(wave * DT + dt) * 64 + lane] = o[dt];
     __syncthreads();
-    MAGE_PROBE_AT(7);
 
     float M = ml[0][0][l16];
 #pragma unroll
@@ -302,10 +293,7 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
         wgt[w] = __builtin_amdgcn_exp2f(ml[0][w][l16] - M);
         lt = fmaf(wgt[w], ml[1][w][l16], lt);
     }
-    if (row >= a.R) {
-        MAGE_PROBE_FLUSH();
-        return;
-    }
+    if (row >= a.R) return;
     const int gl = row / a.B, qi = row - gl * a.B;
     const long long orow = (long long)qi * a.Hq + (long long)h * a.G + gl;
     float *out = a.out + z * a.seq_out;
@@ -316,8 +304,6 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
         for (int w = 0; w < SP_WAVES; ++w) acc += part[(w * DT + dt) * 64 + lane] * wgt[w];
         *reinterpret_cast<f32x4_t *>(out + orow * D + 16 * dt + 4 * lg4) = acc * inv;
     }
-    MAGE_PROBE_AT(5);
-    MAGE_PROBE_FLUSH();
     if (a.lse_out && wave == 0 && lg4 == 0) a.lse_out[z * a.seq_lse + orow] = (M + log2f(lt)) * 0.6931471805599453f;
 }
 

@@ -22,7 +22,6 @@
 #include <stdint.h>
 
 #include "plan.hpp"
-#include "probe.hpp"
 
 namespace mage {
 
@@ -297,8 +296,6 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
     const uint32_t *u = reinterpret_cast<const uint32_t *>(alpha) + (long long)h * L;
     int32_t *out = idx_out + (long long)h * k;
 
-    MAGE_PROBE_DECL;
-    MAGE_PROBE_AT(0);
     if (k <= TK_FILTER_MAX_K) {
         const bool vec_ok = (L & 3) == 0 && (reinterpret_cast<uintptr_t>(u) & 15) == 0;
         const int lane = threadIdx.x & 63;
@@ -349,19 +346,16 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
             n_hit = 0;
         }
         __syncthreads();
-        MAGE_PROBE_AT(1);
         // a lower bound of the k-th largest group maximum (its top 20 bits), hence of the k-th
         // largest element: at least k elements are >= floor_bits
         uint32_t floor_bits = 0, rank = (uint32_t)k, bucket;
         if (in_regs) radix_hist_regs<12>(gv, 20, floor_bits, hists + H_G1);
         else radix_hist_mem<12>(gg, ng, 20, floor_bits, hists + H_G1);
         radix_pick<12>(20, floor_bits, rank, bucket, hists + H_G1, lscan, tmp);
-        MAGE_PROBE_AT(5);
         if (in_regs) radix_hist_regs<8>(gv, 12, floor_bits, hists + H_G2);
         else radix_hist_mem<8>(gg, ng, 12, floor_bits, hists + H_G2);
         radix_pick<8>(12, floor_bits, rank, bucket, hists + H_G2, lscan, tmp2);
 
-        MAGE_PROBE_AT(2);
         // appends this thread's `cnt` keepers among x[0..NX) (positions j[i] .. j[i]+3) to the candidates
         auto keep = [&](const uint4 *x, const long long *j, int nx, uint32_t cnt) {
             const uint32_t incl = wave_scan_incl(cnt);
@@ -420,7 +414,6 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
             __syncthreads();
             const uint32_t nh = n_hit;
             overflow = nh > TK_CAND;
-            MAGE_PROBE_AT(6);
             if (!overflow) {
                 constexpr int QPG = kGroupKeys / 4;            // 16-byte pieces per group
                 constexpr int NX = 4;                           // pieces in flight per thread
@@ -462,7 +455,6 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
             }
         }
         __syncthreads();
-        MAGE_PROBE_AT(3);
         const uint32_t nc = n_cand;
         if (!overflow && nc <= TK_CAND) {
             // exact k-th value among the candidates (radix select in LDS) and the number of
@@ -471,7 +463,6 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
             radix_step_once<12>(cval, nc, 20, thr, want, n_equal, hists + H_C1, lscan, tmp);
             radix_step_once<10>(cval, nc, 10, thr, want, n_equal, hists + H_C2, lscan, tmp2);
             radix_step_once<10>(cval, nc, 0, thr, want, n_equal, hists + H_C3, lscan, tmp);
-            MAGE_PROBE_AT(7);
             // n_cand now counts the winners (index-sort route); every thread read nc before the
             // barriers of the radix steps
             if (!bitmap) {
@@ -521,8 +512,6 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
                 bitonic_sort(sidx, P2);
                 for (int i = threadIdx.x; i < k; i += TK_THREADS) out[i] = sidx[i];
             }
-            MAGE_PROBE_AT(4);
-            MAGE_PROBE_FLUSH();
             return;
         }
         __syncthreads();                                 // too many ties at the bound: radix route

@@ -4,6 +4,8 @@ Bar (the benchmark spec): index sets bit-exact under the lowest-index tie-break, except 
 oracle fp32 score lies within 1e-6 relative of the oracle's k-th score; attention outputs within
 max-abs 2e-2 (bf16 inputs, fp32 accumulate) / 1e-4 (fp32 inputs).
 """
+import zlib
+
 import numpy as np
 import pytest
 
@@ -76,7 +78,7 @@ def test_small_shapes(oracle_mod, case):
     if name == "s10":
         _attention_only(oracle_mod, w, seed=77)
     else:
-        _run_workload(oracle_mod, w, seed=hash(name) % 1000 + 5)
+        _run_workload(oracle_mod, w, seed=zlib.crc32(name.encode()) % 1000 + 5)     # fixed per case, printed by the run
 
 
 def _attention_only(oracle_mod, w, seed):
@@ -111,6 +113,53 @@ def test_c1_bf16(oracle_mod):
 
 def test_c2_bf16(oracle_mod):
     _run_workload(oracle_mod, CONFIGS["c2"], seed=1002, steps=2)
+
+
+@pytest.mark.parametrize("layer", [0, 1])
+def test_c3_full_shape_two_layers(oracle_mod, layer):
+    """Config 3 at its real shape (G = 7: 224 rows per KV head, two row groups streaming the same tiles,
+    L = 65536), two of its independently seeded layers: selection, exact attention, fused step 1 and the
+    sparse steps, every output compared in full."""
+    from paper_2602_14209_amd.workloads import layer_seed
+    _run_workload(oracle_mod, CONFIGS["c3"], seed=layer_seed(1000, 3, layer), steps=2)
+
+
+def test_side_stream_select_beside_exact_attention(oracle_mod):
+    """Alg. 1's arrangement at config 2's shape: the select stream waits for the event that says Q1 is
+    ready, runs mage_select with a workspace of its own while the main stream runs mage_exact_attn of the
+    same layer, and the main stream joins once.  Both streams' results are compared with the oracle."""
+    import torch
+    import paper_2602_14209_amd.binding as mb
+    from gpu_util import Problem, check_alpha, check_index_sets, check_out, to_device
+    w = CONFIGS["c2"]
+    x = make_layer(w, 1002, steps=1)
+    k = w.k
+    print(f"[parity] side stream, c2 shape L={w.L} k={k}", flush=True)
+    p = Problem(x["q"][0], x["k_cache"], x["v_cache"], x["k_blk"][0], x["v_blk"][0], k, w.dtype)
+    ws_side = mb.alloc_workspace(p.shape)
+    main_s, side_s = torch.cuda.Stream(), torch.cuda.Stream()
+    q_host = to_device(x["q"][0], w.dtype)
+    torch.cuda.synchronize()
+    for rep in range(3):                         # the arrangement is replayed: stale results cannot pass
+        p.out.fill_(float("nan")); p.lse.fill_(float("nan")); p.idx.fill_(-1); p.alpha.fill_(float("nan"))
+        p.q.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(main_s):
+            p.q.copy_(q_host)                    # "QKVProj": Q1 becomes ready on the main stream
+            q_ready = torch.cuda.Event()
+            q_ready.record(main_s)
+        side_s.wait_event(q_ready)               # select stream: wait Q1 (non-blocking for the host)
+        mb.check(mb.mage_select(p.shape, p.q, p.kc, p.idx, p.alpha, ws_side, side_s), "mage_select")
+        mb.check(mb.mage_exact_attn(p.shape, p.q, p.kc, p.vc, p.kb, p.vb, p.out, p.lse, p.ws, main_s), "mage_exact_attn")
+        done = torch.cuda.Event()
+        done.record(side_s)
+        main_s.wait_event(done)                  # synchronize(main, select): the one join of Phase 1
+        main_s.synchronize()
+    ref = oracle_mod.select(x["q"][0], x["k_cache"], k)
+    check_alpha(p.alpha.cpu().numpy(), ref["alpha32"])
+    check_index_sets(p.idx.cpu().numpy(), ref["idx"], ref["alpha32"], w.L)
+    o_ref, l_ref = oracle_mod.exact_attn(x["q"][0], x["k_cache"], x["v_cache"], x["k_blk"][0], x["v_blk"][0])
+    check_out(p.out.cpu().numpy(), o_ref, p.lse.cpu().numpy(), l_ref, w.dtype)
 
 
 def test_sparse_k_equal_L_matches_exact_on_gpu(oracle_mod):
@@ -182,8 +231,8 @@ def test_select_long_rows_and_group_overflow(oracle_mod):
 
 
 def test_c4_full_size_headline_shape(oracle_mod):
-    """The benchmark's shape and launch configuration (L=131072, Hq=32, Hkv=8, k=512): selection
-    checked in full, exact attention on sampled block positions, one sparse step in full."""
+    """The benchmark's shape and launch configuration (L=131072, Hq=32, Hkv=8, k=512): selection,
+    exact attention (all block positions) and one sparse step per budget, all checked in full."""
     from gpu_util import Problem, check_alpha, check_index_sets, check_out
     w = CONFIGS["c4"]
     x = make_layer(w, 1004, steps=2)
@@ -196,11 +245,10 @@ def test_c4_full_size_headline_shape(oracle_mod):
     ref = oracle_mod.select(x["q"][0], x["k_cache"], k)
     check_alpha(alpha, ref["alpha32"])
     check_index_sets(idx, ref["idx"], ref["alpha32"], w.L)
-    rows = [0, 13, 31]
-    o_ref, l_ref = oracle_mod.exact_attn(x["q"][0][rows], x["k_cache"], x["v_cache"], x["k_blk"][0], x["v_blk"][0])
-    check_out(o[rows], o_ref, l[rows], l_ref, w.dtype)
+    o_ref, l_ref = oracle_mod.exact_attn(x["q"][0], x["k_cache"], x["v_cache"], x["k_blk"][0], x["v_blk"][0])
+    check_out(o, o_ref, l, l_ref, w.dtype)
     o, l, idx3, alpha3 = p.step1()
-    check_out(o[rows], o_ref, l[rows], l_ref, w.dtype)
+    check_out(o, o_ref, l, l_ref, w.dtype)
     check_alpha(alpha3, ref["alpha32"])
     check_index_sets(idx3, ref["idx"], ref["alpha32"], w.L)
     for kk in w.ks:
@@ -311,10 +359,9 @@ def test_long_single_row_group_loops(oracle_mod, case):
     p = Problem(x["q"][0], x["k_cache"], x["v_cache"], x["k_blk"][0], x["v_blk"][0], k, dtype)
     o, l = p.exact()
     o1, l1, idx, alpha = p.step1()
-    rows = [0, 7, 31]
-    o_ref, l_ref = oracle_mod.exact_attn(x["q"][0][rows], x["k_cache"], x["v_cache"], x["k_blk"][0], x["v_blk"][0])
-    check_out(o[rows], o_ref, l[rows], l_ref, dtype)
-    check_out(o1[rows], o_ref, l1[rows], l_ref, dtype)
+    o_ref, l_ref = oracle_mod.exact_attn(x["q"][0], x["k_cache"], x["v_cache"], x["k_blk"][0], x["v_blk"][0])
+    check_out(o, o_ref, l, l_ref, dtype)
+    check_out(o1, o_ref, l1, l_ref, dtype)
     ref = oracle_mod.select(x["q"][0], x["k_cache"], k)
     check_alpha(alpha, ref["alpha32"])
     check_index_sets(idx, ref["idx"], ref["alpha32"], L)

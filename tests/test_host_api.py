@@ -142,6 +142,46 @@ def test_block_probs_argument_validation():
     assert L.mage_block_probs(ctypes.byref(wide), fake, fake, fake, fake, big, None) == -3
 
 
+def test_combined_calls_validate_everything_before_their_first_launch():
+    """mage_step1 (fp32: attention, then selection) and mage_quest_select (query split, then selection over
+    pages) must report what their LATER stage would reject before the earlier stage launches anything:
+    with no GPU in this process a launch would come back as MAGE_ERR_HIP (-5) instead."""
+    L = mb.lib()
+    fake = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1004)
+    big = 1 << 40
+    sf = mb.make_shape(32, 32, 8, 128, 4096, 512, "f32")
+    # attention arguments are fine; alpha_out (selection's) is misaligned / the workspace is too small for selection
+    assert L.mage_step1(ctypes.byref(sf), fake, fake, fake, fake, fake, fake, None, fake, odd, fake, big, None) == -6
+    assert L.mage_step1(ctypes.byref(sf), fake, fake, fake, None, None, fake, None, fake, None, fake, 16, None) == -4
+    wide = mb.make_shape(128, 32, 8, 128, 4096, 512, "bf16")      # B*G = 512 rows per KV head: selection unsupported
+    assert mb.mage_quest_workspace_bytes(wide, 16) > 0
+    assert L.mage_quest_select(ctypes.byref(wide), 16, fake, fake, fake, None, fake, big, None) == -3
+    assert L.mage_step1(ctypes.byref(wide), fake, fake, fake, fake, fake, fake, None, fake, None, fake, big, None) == -3
+    assert L.mage_select(ctypes.byref(wide), fake, fake, fake, None, fake, big, None) == -3
+    # ... while the attention calls accept that geometry, which is why mage_workspace_bytes() is not 0 for it
+    assert mb.mage_workspace_bytes(wide) > 0
+
+
+def test_measurement_aids_validate_their_arguments():
+    L = mb.lib()
+    fake = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1004)
+    s = mb.make_shape(32, 32, 8, 128, 4096, 512, "bf16")
+    assert L.mage_diag_chase(None, 16, 0, 4, fake, None) == -1
+    assert L.mage_diag_chase(fake, 16, 16, 4, fake, None) == -2
+    assert L.mage_diag_chase(fake, 16, 0, 0, fake, None) == -2
+    assert L.mage_diag_read(None, 1024, fake, None) == -1
+    assert L.mage_diag_read(odd, 1024, fake, None) == -6
+    assert L.mage_diag_read(fake, 8, fake, None) == -2
+    assert L.mage_diag_copy(fake, None, 1024, None) == -1
+    assert L.mage_diag_copy(odd, fake, 1024, None) == -6
+    assert L.mage_diag_gather(ctypes.byref(s), 0, fake, fake, fake, fake, None) == -2
+    assert L.mage_diag_gather(ctypes.byref(s), 2, fake, None, fake, fake, None) == -1
+    sf = mb.make_shape(32, 32, 8, 128, 4096, 512, "f32")                # 512-byte rows
+    assert L.mage_diag_gather(ctypes.byref(sf), 2, fake, fake, fake, fake, None) == -3
+
+
 def test_binding_argument_counts_match_the_header():
     """Every prototype of include/mage.h has as many parameters as the binding marshals."""
     text = open(os.path.join(ROOT, "include", "mage.h")).read()

@@ -1,5 +1,4 @@
-"""GPU checks that are written but have not yet run on the hardware (hence the file name, which pytest
-does not collect; run it by naming the file, then rename it to test_zz_determinism_canary.py):
+"""Run-to-run determinism and guard zones of every entry point, on the GPU:
 
 * determinism: every entry point called twice on the same inputs gives bitwise identical outputs (no
   result depends on the order in which workgroups or atomics happen to run);
