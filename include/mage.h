@@ -44,7 +44,8 @@ typedef enum {
     MAGE_ERR_UNSUPPORTED = -3, /* d not in {64,128}; unknown dtype; L > 2^30; B*G too large */
     MAGE_ERR_WORKSPACE = -4,   /* workspace NULL or smaller than mage_workspace_bytes() */
     MAGE_ERR_HIP = -5,         /* a kernel launch reported an error */
-    MAGE_ERR_ALIGN = -6        /* a data pointer is not 16-byte aligned */
+    MAGE_ERR_ALIGN = -6,       /* a data pointer is not 16-byte aligned */
+    MAGE_ERR_SCRATCH = -7      /* mage_select_static: the problem needs more than mage_static_scratch_bytes() */
 } mage_status;
 
 /* Problem geometry of one layer and one block (Alg. 1 "Require: cache C, B, k, T"). */
@@ -83,6 +84,20 @@ size_t mage_workspace_bytes(const mage_shape *shape);
 int mage_select(const mage_shape *shape, const void *q1, const void *k_cache,
                 int32_t *idx_out, float *alpha_out,
                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * mage_select for callers that can neither allocate nor pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs, outputs, kernels and
+ * results as mage_select; the scratch data of the kernels lives in a static device array of
+ * mage_static_scratch_bytes() bytes (8 MiB; every GPU the library runs on holds one until the process
+ * ends), which covers e.g. Hkv = 8, L = 131072.  A shape that needs more returns MAGE_ERR_SCRATCH
+ * and launches nothing.  The call allocates nothing and frees nothing.  The current device must be
+ * the one `hip_stream` belongs to.  All calls on one GPU share that GPU's array: two calls that
+ * overlap in time (different streams, no event between them) race.
+ */
+size_t mage_static_scratch_bytes(void);
+int mage_select_static(const mage_shape *shape, const void *q1, const void *k_cache,
+                       int32_t *idx_out, float *alpha_out, void *hip_stream);
 
 /*
  * Block-averaged probabilities per QUERY head (Sec. 3, Eq. 2 written per head; the inner

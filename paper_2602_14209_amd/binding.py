@@ -25,6 +25,7 @@ EXPORTS = ("mage_version", "mage_status_string", "mage_workspace_bytes",
            "mage_select", "mage_block_probs", "mage_exact_attn", "mage_sparse_attn", "mage_step1",
            "mage_compact", "mage_sparse_attn_compact", "mage_sparse_attn_batched",
            "mage_page_summary", "mage_quest_workspace_bytes", "mage_quest_select", "mage_set_overlap",
+           "mage_static_scratch_bytes", "mage_select_static",
            "mage_diag_empty", "mage_diag_chase", "mage_diag_read", "mage_diag_copy", "mage_diag_gather")
 
 
@@ -82,6 +83,10 @@ def lib() -> ctypes.CDLL:
         L.mage_quest_select.argtypes = [shp, ctypes.c_int, vp, vp, vp, vp, vp, sz, vp]
         L.mage_set_overlap.restype = ctypes.c_int
         L.mage_set_overlap.argtypes = [vp, vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp]
+        L.mage_static_scratch_bytes.restype = sz
+        L.mage_static_scratch_bytes.argtypes = []
+        L.mage_select_static.restype = ctypes.c_int
+        L.mage_select_static.argtypes = [shp, vp, vp, vp, vp, vp]
         L.mage_diag_empty.restype = ctypes.c_int
         L.mage_diag_empty.argtypes = [vp]
         L.mage_diag_chase.restype = ctypes.c_int
@@ -208,6 +213,16 @@ def mage_quest_select(shape: mage_shape, p: int, q, summary, idx_out, est_out, w
 def mage_set_overlap(a, b, n_rows: int, k: int, a_rows: int, out, stream=None) -> int:
     """out[i] = |A_(i mod a_rows) & B_i| / k (Eq. 1, Eq. 3); see include/mage.h."""
     return lib().mage_set_overlap(_ptr(a), _ptr(b), int(n_rows), int(k), int(a_rows), _ptr(out), _stream(stream))
+
+
+def mage_static_scratch_bytes() -> int:
+    return int(lib().mage_static_scratch_bytes())
+
+
+def mage_select_static(shape: mage_shape, q1, k_cache, idx_out, alpha_out, stream=None) -> int:
+    """mage_select on the library's static scratch array (no workspace, no allocation); see include/mage.h."""
+    return lib().mage_select_static(ctypes.byref(shape), _ptr(q1), _ptr(k_cache), _ptr(idx_out), _ptr(alpha_out),
+                                    _stream(stream))
 
 
 def mage_diag_empty(stream=None) -> int:

@@ -4,6 +4,8 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "plan.hpp"
 
 namespace mage {
@@ -264,6 +266,7 @@ const char *mage_status_string(int status)
     case MAGE_ERR_WORKSPACE: return "workspace missing or smaller than mage_workspace_bytes()";
     case MAGE_ERR_HIP: return "HIP reported a launch error";
     case MAGE_ERR_ALIGN: return "a data pointer is not 16-byte aligned";
+    case MAGE_ERR_SCRATCH: return "the problem needs more scratch memory than the library's static buffer holds";
     default: return "unknown status";
     }
 }
@@ -290,6 +293,58 @@ int mage_select(const mage_shape *shape, const void *q1, const void *k_cache,
     if (rc != MAGE_OK) return rc;
     return select_impl(shape, (float)(1.4426950408889634 / sqrt((double)shape->d)), 1, q1, k_cache, idx_out, alpha_out, nullptr,
                        workspace, workspace_bytes, hip_stream);
+}
+
+}  // extern "C"
+
+// ---- selection without a caller-provided workspace ----
+// The selection kernels' scratch data (row statistics per key split, alpha when the caller does not
+// ask for it, the group maxima) live in this file-scope device array instead: every GPU the library runs
+// on holds its own copy at its own address for the life of the process.  Host code must not use the
+// array's name as a device address (in host code it is only a handle); the address on each device
+// is asked for once, with that device current, and kept.
+namespace {
+
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];        // device address of `scratch` on each device, nullptr = not asked yet
+std::mutex g_scratch_mutex;
+
+// Address of this device's copy of the scratch array (the current device's), or nullptr on error.
+void *static_scratch()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t mage_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int mage_select_static(const mage_shape *shape, const void *q1, const void *k_cache,
+                       int32_t *idx_out, float *alpha_out, void *hip_stream)
+{
+    const int rc = check_shape(shape, true);
+    if (rc != MAGE_OK) return rc;
+    if (select_layout(*shape, plan_stats(*shape)).bytes > kStaticScratchBytes) return MAGE_ERR_SCRATCH;
+    // everything but the workspace, so that argument errors are reported without touching the device
+    const int ra = select_check(shape, q1, k_cache, idx_out, alpha_out, nullptr, reinterpret_cast<const void *>(256), kStaticScratchBytes);
+    if (ra != MAGE_OK) return ra;
+    void *ws = static_scratch();
+    if (!ws) return MAGE_ERR_HIP;
+    return select_impl(shape, (float)(1.4426950408889634 / sqrt((double)shape->d)), 1, q1, k_cache, idx_out, alpha_out, nullptr,
+                       ws, kStaticScratchBytes, hip_stream);
 }
 
 int mage_block_probs(const mage_shape *shape, const void *q1, const void *k_cache, float *pbar_out,

@@ -27,7 +27,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_status_strings():
-    for code in range(0, -7, -1):
+    for code in range(0, -8, -1):
         s = mb.status_string(code)
         assert s and s != "unknown status"
     assert mb.status_string(-99) == "unknown status"
@@ -161,6 +161,22 @@ def test_combined_calls_validate_everything_before_their_first_launch():
     assert L.mage_select(ctypes.byref(wide), fake, fake, fake, None, fake, big, None) == -3
     # ... while the attention calls accept that geometry, which is why mage_workspace_bytes() is not 0 for it
     assert mb.mage_workspace_bytes(wide) > 0
+
+
+def test_static_scratch_entry_point_rejects_before_touching_the_device():
+    """mage_select_static: shape and size errors come back without any device call (none is possible here)."""
+    L = mb.lib()
+    fake = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1004)
+    assert mb.mage_static_scratch_bytes() == 8 << 20
+    ok = mb.make_shape(32, 32, 8, 128, 131072, 512, "bf16")          # the headline shape fits
+    huge = mb.make_shape(32, 32, 8, 128, 1 << 20, 512, "bf16")
+    assert L.mage_select_static(ctypes.byref(huge), fake, fake, fake, None, None) == -7
+    assert L.mage_select_static(ctypes.byref(ok), None, fake, fake, None, None) == -1
+    assert L.mage_select_static(ctypes.byref(ok), fake, fake, None, None, None) == -1
+    assert L.mage_select_static(ctypes.byref(ok), odd, fake, fake, None, None) == -6
+    assert L.mage_select_static(ctypes.byref(mb.make_shape(32, 30, 8, 128, 4096, 512, "bf16")), fake, fake, fake, None, None) == -2
+    assert L.mage_select_static(None, fake, fake, fake, None, None) == -1
 
 
 def test_measurement_aids_validate_their_arguments():
