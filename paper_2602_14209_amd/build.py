@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmage.so")
-SOURCES = ["mage_api.hip", "attn_bf16.hip", "sparse_bf16.hip", "attn_f32.hip", "reduce.hip", "topk.hip", "quest.hip", "diag.hip"]
+SOURCES = ["mage_api.hip", "attn_bf16.hip", "sparse_bf16.hip", "sparse_batch_bf16.hip", "attn_f32.hip", "reduce.hip", "topk.hip", "quest.hip", "diag.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xarch_host", "-fPIC", "-shared",   # position-independent code for the host side only (the device code objects need none)
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 VALU ops

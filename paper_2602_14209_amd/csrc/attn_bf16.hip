@@ -979,16 +979,6 @@ hipError_t bf16_attn(const KernelArgs &a, int d, int row_groups, bool gather, hi
     return hipErrorInvalidValue;
 }
 
-// Batched sparse step: n_seq independent sequences, one workgroup per (sequence, KV head, row
-// group) walks all k + B keys of its head, so every selected row is fetched by exactly one
-// workgroup and nothing is merged across workgroups.
-hipError_t bf16_attn_batched(const KernelArgs &a, int d, int row_groups, int n_seq, hipStream_t stream)
-{
-    if (d == 128) return launch_attn<128, MODE_ATTN, true, false>(a, row_groups, n_seq, stream);
-    if (d == 64) return launch_attn<64, MODE_ATTN, true, false>(a, row_groups, n_seq, stream);
-    return hipErrorInvalidValue;
-}
-
 hipError_t bf16_stats(const KernelArgs &a, int d, int row_groups, hipStream_t stream)
 {
     // two workgroups per CU already overlap each other's phases: the plain order measured faster

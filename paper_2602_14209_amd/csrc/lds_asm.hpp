@@ -93,6 +93,16 @@ __device__ __forceinline__ void lane_halves(float x, float &lo, float &hi)
     asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(lo), "+v"(hi));
 }
 
+// The same across a pair of 16-lane rows: lo = x of the even row of this lane's row pair (rows 0 and 2
+// of the wavefront), hi = x of the odd row (rows 1 and 3), same lane within the row
+// (v_permlane16_swap exchanges the odd rows of its first register with the even rows of its second).
+__device__ __forceinline__ void lane_rows16(float x, float &lo, float &hi)
+{
+    lo = x;
+    hi = x;
+    asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1" : "+v"(lo), "+v"(hi));
+}
+
 __device__ __forceinline__ unsigned lds_addr(const void *p) { return (unsigned)(uintptr_t)MAGE_LDS_PTR(p); }
 
 template <int... I, class F>

@@ -10,7 +10,7 @@
 
 namespace mage {
 hipError_t bf16_attn(const KernelArgs &a, int d, int row_groups, bool gather, hipStream_t stream);
-hipError_t bf16_attn_batched(const KernelArgs &a, int d, int row_groups, int n_seq, hipStream_t stream);
+hipError_t bf16_sparse_batched(const KernelArgs &a, int d, int row_groups, int n_seq, hipStream_t stream);
 hipError_t bf16_stats(const KernelArgs &a, int d, int row_groups, hipStream_t stream);
 hipError_t bf16_colsum(const KernelArgs &a, int d, int waves, hipStream_t stream);
 hipError_t bf16_sparse(const KernelArgs &a, int d, bool compact, int n_seq, hipStream_t stream);
@@ -167,11 +167,9 @@ int run_sparse_bf16(const mage_shape *shape, bool compact, int n_seq, const void
     }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (n_seq > 1 && !compact) {
-        // enough independent work to fill the chip: the tiled kernel with unsplit keys reads every
-        // selected row once per sequence (the latency-oriented kernel re-reads it per row tile)
-        a.kps = (int)align_up((size_t)shape->k, kBf16Tile);
-        a.blk_split = 0;
-        return bf16_attn_batched(a, shape->d, p.row_groups, n_seq, stream) == hipSuccess ? MAGE_OK : MAGE_ERR_HIP;
+        // enough independent work to fill the chip: one workgroup per (sequence, head) reads every
+        // selected row once (the latency-oriented kernel re-reads it per row tile)
+        return bf16_sparse_batched(a, shape->d, p.row_groups, n_seq, stream) == hipSuccess ? MAGE_OK : MAGE_ERR_HIP;
     }
     if (bf16_sparse(a, shape->d, compact, n_seq, stream) != hipSuccess) return MAGE_ERR_HIP;
     return MAGE_OK;

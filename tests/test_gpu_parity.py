@@ -302,28 +302,47 @@ def test_compacted_rows(oracle_mod, case):
     check_out(o, o_ref, l, l_ref, dtype)
 
 
-def test_batched_sparse_step(oracle_mod):
-    """n_seq independent sequences in one launch equal n_seq single calls (and the oracle)."""
+@pytest.mark.parametrize("case", [
+    # name, n_seq, Hq, Hkv, d, L, B, k, in-block keys
+    ("b1", 3, 8, 2, 128, 2500, 32, 300, True),       # 332 key positions: six tiles, the last one with 12 keys
+    ("b2", 2, 14, 2, 128, 1500, 32, 200, True),      # G = 7: 224 rows, two row groups per unit, the second ragged
+    ("b3", 5, 4, 4, 64, 777, 5, 65, True),           # d = 64, 5 rows, 20 units (a ragged block of workgroup ids)
+    ("b4", 2, 8, 2, 128, 300, 32, 32, True),         # k + B = 64: exactly one tile
+    ("b5", 2, 8, 2, 128, 300, 32, 7, True),          # one tile, 39 keys
+    ("b6", 9, 4, 1, 128, 500, 32, 70, False),        # no in-block keys; second tile holds 6 keys (upper half skipped); 9 units
+    ("b7", 1, 8, 2, 64, 4000, 16, 1000, True),       # a single sequence, many tiles
+    ("b8", 40, 8, 8, 128, 600, 16, 100, True),       # 320 units: more workgroups than CUs (the two-per-CU ring)
+    ("b9", 70, 8, 4, 64, 2500, 8, 2100, False),       # ... at d = 64, and more index entries than LDS holds at a time
+    ("b10", 2, 4, 2, 128, 5000, 32, 4200, True),     # the deep ring with two refills of the index entries
+])
+def test_batched_sparse_step(oracle_mod, case):
+    """n_seq independent sequences in one launch equal the oracle's sparse step of every sequence."""
     import torch
     import paper_2602_14209_amd.binding as mb
     from gpu_util import check_out, to_device
-    n_seq = 3
-    w = Workload("bt", "bf16", Hq=8, Hkv=2, d=128, L=2500, B=32, ks=(300,), T=2, heavy_frac=0.02, heavy_scale=3.0)
-    k = 300
+    name, n_seq, Hq, Hkv, d, L, B, k, blk = case
+    w = Workload(name, "bf16", Hq=Hq, Hkv=Hkv, d=d, L=L, B=B, ks=(k,), T=2, heavy_frac=0.02, heavy_scale=3.0)
     xs = [make_layer(w, 500 + s) for s in range(n_seq)]
     rng = np.random.default_rng(4)
     idx = np.stack([np.stack([np.sort(rng.choice(w.L, k, replace=False)) for _ in range(w.Hkv)]) for _ in range(n_seq)]).astype(np.int32)
     stack = lambda name, t=None: to_device(np.stack([x[name] if t is None else x[name][t] for x in xs]), "bf16")
-    q, kc, vc, kb, vb = stack("q", 1), stack("k_cache"), stack("v_cache"), stack("k_blk", 1), stack("v_blk", 1)
+    q, kc, vc = stack("q", 1), stack("k_cache"), stack("v_cache")
+    kb, vb = (stack("k_blk", 1), stack("v_blk", 1)) if blk else (None, None)
     out = torch.full((n_seq, w.B, w.Hq, w.d), float("nan"), dtype=torch.float32, device="cuda")
     lse = torch.full((n_seq, w.B, w.Hq), float("nan"), dtype=torch.float32, device="cuda")
     shape = mb.make_shape(w.B, w.Hq, w.Hkv, w.d, w.L, k, "bf16")
-    print("[parity] batched sparse step", flush=True)
+    print(f"[parity] batched sparse step {case}", flush=True)
     mb.check(mb.mage_sparse_attn_batched(shape, n_seq, q, kc, vc, torch.from_numpy(idx).cuda(), kb, vb, out, lse), "batched")
     torch.cuda.synchronize()
     for s in range(n_seq):
-        o_ref, l_ref = oracle_mod.sparse_attn(xs[s]["q"][1], xs[s]["k_cache"], xs[s]["v_cache"], idx[s], xs[s]["k_blk"][1], xs[s]["v_blk"][1])
+        o_ref, l_ref = oracle_mod.sparse_attn(xs[s]["q"][1], xs[s]["k_cache"], xs[s]["v_cache"], idx[s],
+                                              xs[s]["k_blk"][1] if blk else None, xs[s]["v_blk"][1] if blk else None)
         check_out(out[s].cpu().numpy(), o_ref, lse[s].cpu().numpy(), l_ref, "bf16")
+    # without the lse output
+    out2 = torch.full_like(out, float("nan"))
+    mb.check(mb.mage_sparse_attn_batched(shape, n_seq, q, kc, vc, torch.from_numpy(idx).cuda(), kb, vb, out2, None), "batched")
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int32), out2.view(torch.int32))
 
 
 @pytest.mark.parametrize("seed", list(range(12)))
