@@ -7,11 +7,20 @@ headline workload (config c4: bf16, Hq=32, Hkv=8, d=128, L=131072, B=32, k=512, 
                       The paper's arrangement -- mage_exact_attn on the main stream, mage_select on a side
                       stream, one join (Alg. 1) -- is timed as well and reported beside it;
   phase 2 (steps 2..T) per layer and step: mage_sparse_attn with the layer's index set.
-Every layer has its own K/V cache (distinct buffers, dependent chain), so a layer's gathered rows are
-not cache-resident when it is revisited.  The whole step is captured once in a HIP graph and replayed.
+Every layer has its own K/V cache (distinct buffers, dependent chain).  The whole step is captured once in
+a HIP graph and replayed.
 
 Prints ONE JSON line; `value` is the sparse-step attention time per layer-block (phase 2 time divided
-by layers*(T-1)), inputs resident in HBM.
+by layers*(T-1)), inputs resident in HBM.  Two things are reported beside it, because one small call cannot
+say much about a 8 TB/s memory system:
+  * cache state: in the replayed chain a layer's selected rows (2 MiB) are revisited after 28 layers' worth
+    of other rows (85 MB), which the 256 MB Infinity Cache holds -- `value` is that warm-cache latency;
+    `sparse_step_cold_us` streams 1 GiB between two denoising steps (timed alone and subtracted), so that
+    every selected row comes from HBM, as it would with a model's weights streaming between two visits;
+  * bandwidth mode: `--batch` independent sequences per launch (mage_sparse_attn_batched), with the step-1
+    index sets (warm) and with a fresh random index set per launch (cold: no row is cache-resident);
+  * floors and ceilings measured in this run: an empty kernel as a graph node, a dependent-load chase, the
+    read / copy / gather rates this GPU reaches.
 """
 from __future__ import annotations
 
@@ -36,6 +45,7 @@ def parse():
     ap.add_argument("--workload", default="c4")
     ap.add_argument("--k", type=int, default=512)
     ap.add_argument("--layers", type=int, default=28)
+    ap.add_argument("--batch", type=int, default=64, help="sequences per launch of the bandwidth-mode (batched) sparse step")
     ap.add_argument("--T", type=int, default=0, help="denoising steps per block (0 = the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--page", type=int, default=16, help="page size of the second workload (Quest-style estimator)")
@@ -63,6 +73,9 @@ def main():
     k = args.k
     T = args.T or w.T
     NL = args.layers
+    NB = max(1, args.batch)
+    NA = max(NL, NB)              # sequences in memory: the first NL double as the layers of the chain
+    cfg_index = list(CONFIGS).index(args.workload)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     shape = mb.make_shape(w.B, w.Hq, w.Hkv, w.d, w.L, k, w.dtype)
@@ -70,24 +83,36 @@ def main():
     # All layers live in one allocation per array ([layer, ...]); a layer is a view.  The same memory
     # doubles as a batch of NL independent sequences for the batched (bandwidth-mode) launch.
     dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
-    big_k = torch.empty((NL, w.L, w.Hkv, w.d), dtype=dt, device=dev)
+    big_k = torch.empty((NA, w.L, w.Hkv, w.d), dtype=dt, device=dev)
     big_v = torch.empty_like(big_k)
-    big_q = torch.empty((T, NL, w.B, w.Hq, w.d), dtype=dt, device=dev)
-    big_kb = torch.empty((T, NL, w.B, w.Hkv, w.d), dtype=dt, device=dev)
+    big_q = torch.empty((T, NA, w.B, w.Hq, w.d), dtype=dt, device=dev)
+    big_kb = torch.empty((T, NA, w.B, w.Hkv, w.d), dtype=dt, device=dev)
     big_vb = torch.empty_like(big_kb)
-    for l in range(NL):
-        x = make_layer_device(w, args.seed + 1000 * 4 + l, dev, steps=T)
+    for l in range(NA):
+        x = make_layer_device(w, args.seed + 1000 * cfg_index + l, dev, steps=T)
         big_k[l].copy_(x["k_cache"]); big_v[l].copy_(x["v_cache"])
         big_q[:, l].copy_(x["q"]); big_kb[:, l].copy_(x["k_blk"]); big_vb[:, l].copy_(x["v_blk"])
         del x
     layers = [{"q": big_q[:, l], "k_cache": big_k[l], "v_cache": big_v[l], "k_blk": big_kb[:, l], "v_blk": big_vb[:, l]}
-              for l in range(NL)]
+              for l in range(NA)]
     ws_main = mb.alloc_workspace(shape)
     ws_side = mb.alloc_workspace(shape)
-    big_idx = torch.zeros((NL, w.Hkv, k), dtype=torch.int32, device=dev)
-    idx = [big_idx[l] for l in range(NL)]
+    big_idx = torch.zeros((NA, w.Hkv, k), dtype=torch.int32, device=dev)
+    idx = [big_idx[l] for l in range(NA)]
     out = torch.empty((w.B, w.Hq, w.d), dtype=torch.float32, device=dev)
-    out_b = torch.empty((NL, w.B, w.Hq, w.d), dtype=torch.float32, device=dev)
+    out_b = torch.empty((NB, w.B, w.Hq, w.d), dtype=torch.float32, device=dev)
+    # cold variant of the batched step: a fresh random index set (ascending, duplicate-free) per launch
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(args.seed + 77)
+    cold_idx = torch.empty((T - 1, NB, w.Hkv, k), dtype=torch.int32, device=dev)
+    for t in range(T - 1):
+        for s0 in range(0, NB * w.Hkv, 256):
+            n = min(256, NB * w.Hkv - s0)
+            pick = torch.rand((n, w.L), generator=gen, device=dev).topk(k, dim=1).indices.sort(dim=1).values
+            cold_idx[t].view(NB * w.Hkv, k)[s0:s0 + n] = pick.to(torch.int32)
+            del pick
+    flush_buf = torch.zeros(1 << 30, dtype=torch.uint8, device=dev)      # streamed between steps to empty the caches
+    sink = torch.zeros(4096, dtype=torch.int32, device=dev)
     k_sel = torch.empty((NL, k, w.Hkv, w.d), dtype=dt, device=dev)
     v_sel = torch.empty_like(k_sel)
     torch.cuda.synchronize()
@@ -123,9 +148,16 @@ def main():
         mb.check(mb.mage_sparse_attn_compact(shape, x["q"][t], k_sel[l], v_sel[l], x["k_blk"][t], x["v_blk"][t], out,
                                              None, ws_main, stream), "mage_sparse_attn_compact")
 
-    def sparse_batched(t, stream):
-        mb.check(mb.mage_sparse_attn_batched(shape, NL, big_q[t], big_k, big_v, big_idx, big_kb[t], big_vb[t], out_b,
-                                             None, stream), "mage_sparse_attn_batched")
+    def sparse_batched(t, stream, index_sets=None):
+        ix = big_idx[:NB] if index_sets is None else index_sets
+        mb.check(mb.mage_sparse_attn_batched(shape, NB, big_q[t, :NB], big_k[:NB], big_v[:NB], ix, big_kb[t, :NB],
+                                             big_vb[t, :NB], out_b, None, stream), "mage_sparse_attn_batched")
+
+    def gather_only(stream, index_sets):
+        mb.check(mb.mage_diag_gather(shape, NB, big_k[:NB], big_v[:NB], index_sets, sink, stream), "mage_diag_gather")
+
+    def flush(stream):
+        mb.check(mb.mage_diag_read(flush_buf, sink, stream), "mage_diag_read")
 
     def phase1(overlap=True):
         if overlap:
@@ -153,7 +185,12 @@ def main():
     # index sets must exist before the sparse chain is first replayed
     with torch.cuda.stream(main_s):
         phase1(overlap=False)
+        for l in range(NL, NA):
+            select(l, main_s, ws_main)
     torch.cuda.synchronize()
+    # what is timed below runs on these sets: each row ascending, duplicate-free and in range
+    ih = big_idx.cpu()
+    assert int(ih.min()) >= 0 and int(ih.max()) < w.L and bool((ih[:, :, 1:] > ih[:, :, :-1]).all()), "mage_step1/mage_select left a bad index set"
 
     graphs = {
         "step": capture(lambda: ([step1(l, main_s) for l in range(NL)], phase2())),
@@ -165,12 +202,26 @@ def main():
         "compact": capture(lambda: [compact(l, main_s) for l in range(NL)]),
         "phase2_compact": capture(lambda: [sparse_compact(l, t, main_s) for t in range(1, T) for l in range(NL)]),
         "phase2_batched": capture(lambda: [sparse_batched(t, main_s) for t in range(1, T)]),
+        "phase2_batched_cold": capture(lambda: [sparse_batched(t, main_s, cold_idx[t - 1]) for t in range(1, T)]),
+        "gather_warm": capture(lambda: [gather_only(main_s, big_idx[:NB]) for t in range(1, T)]),
+        "gather_cold": capture(lambda: [gather_only(main_s, cold_idx[t - 1]) for t in range(1, T)]),
+        "phase2_cold": capture(lambda: [(flush(main_s), [sparse(l, t, main_s) for l in range(NL)]) for t in range(1, T)]),
+        "flush_only": capture(lambda: [flush(main_s) for t in range(1, T)]),
+        "exact_every_step": capture(lambda: [exact(l, main_s) for t in range(T) for l in range(NL)]),
+        "empty_nodes": capture(lambda: [mb.check(mb.mage_diag_empty(main_s), "mage_diag_empty") for _ in range(400)]),
     }
+    # the batched launch computes what the single calls compute (one sequence, one step, compared in full)
+    with torch.cuda.stream(main_s):
+        sparse_batched(1, main_s)
+        sparse(NL - 1, 1, main_s)
+    torch.cuda.synchronize()
+    dev_b = float((out_b[NL - 1] - out).abs().max()) if NL <= NB else 0.0
+    assert dev_b <= 2e-2, f"batched and single sparse step differ by {dev_b}"
 
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
-        dst.copy_(src)
+        mb.check(mb.mage_diag_copy(dst, src), "mage_diag_copy")
         torch.cuda.synchronize()
         del src, dst
 
@@ -201,7 +252,11 @@ def main():
     ab = algorithmic_bytes(w, k)
     compact_us = ms["compact"] * 1e3 / NL
     sparse_compact_us = ms["phase2_compact"] * 1e3 / n_sparse
-    batched_launch_us = ms["phase2_batched"] * 1e3 / (T - 1)          # one launch = NL sequences
+    batched_launch_us = ms["phase2_batched"] * 1e3 / (T - 1)          # one launch = NB sequences
+    batched_cold_us = ms["phase2_batched_cold"] * 1e3 / (T - 1)
+    sparse_cold_us = (ms["phase2_cold"] - ms["flush_only"]) * 1e3 / n_sparse
+    exact_every_step_ms = ms["exact_every_step"]
+    floors = measure_floors(w, k, NB, T, ms, flush_buf, sink, main_s, capture, time_graph, K)
 
     traffic = measured_traffic(w, k)
 
@@ -213,6 +268,12 @@ def main():
 
     rooflines = {
         "mage_sparse_attn": roof("mage_sparse_attn", sparse_us, ab["sparse_attn"], "sparse_bf16_kernel (one launch per call)"),
+        "mage_sparse_attn_cold": roof("mage_sparse_attn", sparse_cold_us, ab["sparse_attn"],
+                                      "sparse_bf16_kernel, 1 GiB streamed between denoising steps (timed alone and subtracted)"),
+        "mage_sparse_attn_batched": roof("mage_sparse_attn_batched", batched_launch_us, NB * ab["sparse_attn"],
+                                         f"sparse_batch_kernel, {NB} sequences per launch, step-1 index sets (selected rows cache-resident)"),
+        "mage_sparse_attn_batched_cold": roof("mage_sparse_attn_batched", batched_cold_us, NB * ab["sparse_attn"],
+                                              f"sparse_batch_kernel, {NB} sequences per launch, a fresh random index set per launch"),
         "mage_exact_attn": roof("mage_exact_attn", exact_us, ab["exact_attn"], "attn_bf16_kernel<dense> + combine_kernel"),
         "mage_select": roof("mage_select", select_us, ab["select"],
                             "attn_bf16_kernel<stats> + lse_kernel + colsum_bf16_kernel + topk_kernel"),
@@ -232,7 +293,7 @@ def main():
         "dtype": w.dtype,
         "data": "synthetic",
         "config": {"workload": f"{w.name}: L={w.L} Hq={w.Hq} Hkv={w.Hkv} d={w.d} B={w.B} k={k} T={T}",
-                   "layers": NL, "k": k, "T": T, "launch": "HIP graph replay, dependent chain over distinct layer buffers"},
+                   "layers": NL, "k": k, "T": T, "batch": NB, "launch": "HIP graph replay, dependent chain over distinct layer buffers"},
         "sparse_step_hbm_gbs": rooflines["mage_sparse_attn"]["achieved"],
         "select_us": round(select_us, 2),
         "select_exposed_us": round(phase1_us - exact_us, 2),
@@ -240,24 +301,87 @@ def main():
         "exact_attn_us": round(exact_us, 2),
         "step1_fused_us_per_layer": round(step1_us, 2),
         "two_stream_phase1_us_per_layer": round(phase1_us, 2),
-        "block_ms": {"mage": round(ms_step, 4), "exact_baseline_est": round(exact_us * NL * T / 1e3, 4)},
+        "block_ms": {"mage": round(ms_step, 4), "exact_every_step": round(exact_every_step_ms, 4)},
+        "sparse_step_cold_us": round(sparse_cold_us, 3),
         "sparse_step_compact_us": round(sparse_compact_us, 3),
         "compact_us_per_layer": round(compact_us, 2),
-        "sparse_step_batched": {"sequences_per_launch": NL, "us_per_launch": round(batched_launch_us, 2),
-                                "us_per_sequence": round(batched_launch_us / NL, 3),
-                                "hbm_gbs": round(NL * ab["sparse_attn"] / (batched_launch_us * 1e-6) / 1e9, 1),
-                                "frac_of_8TBs": round(NL * ab["sparse_attn"] / (batched_launch_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
-                                "note": "bandwidth mode: independent sequences in one launch, not a per-step latency"},
+        "sparse_step_batched": {"sequences_per_launch": NB, "us_per_launch": round(batched_launch_us, 2),
+                                "us_per_sequence": round(batched_launch_us / NB, 3),
+                                "hbm_gbs": rooflines["mage_sparse_attn_batched"]["achieved"],
+                                "frac_of_8TBs": rooflines["mage_sparse_attn_batched"]["frac"],
+                                "cold_us_per_launch": round(batched_cold_us, 2),
+                                "cold_frac_of_8TBs": rooflines["mage_sparse_attn_batched_cold"]["frac"],
+                                "frac_of_gather_ceiling": round(floors["gather_only_us_per_launch"]["warm"] / batched_launch_us, 3),
+                                "cold_frac_of_gather_ceiling": round(floors["gather_only_us_per_launch"]["cold"] / batched_cold_us, 3),
+                                "note": "bandwidth mode: independent sequences in one launch, not a per-step latency; warm = the "
+                                        "step-1 index sets at every launch (the selected rows fit the 256 MB Infinity Cache), cold = a "
+                                        "fresh random index set per launch; gather ceiling = the same launch's index and row reads alone"},
+        "floors": floors,
         "wall_ms_per_step": round(wall_step, 4),
         "roofline": rooflines["mage_sparse_attn"],
         "rooflines": rooflines,
     }
 
     if w.dtype == "bf16" and args.page > 0 and w.L % args.page == 0 and k % args.page == 0:
-        result["second_workload"] = second_workload(w, k, args.page, shape, layers, idx, ws_main, main_s, capture, time_graph, K)
+        result["second_workload"] = second_workload(w, k, args.page, shape, layers[:NL], idx, ws_main, main_s, capture, time_graph, K)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, k, args.seed)
     print(json.dumps(result), flush=True)
+
+
+def measure_floors(w, k, NB, T, ms, flush_buf, sink, main_s, capture, time_graph, reps):
+    """Floors and ceilings next to the attention figures: an empty kernel as a graph node, a dependent
+    load chase (the sparse step has two dependent loads: index entry, then row), streaming read / copy
+    rates, and the rate of the batched step's memory accesses alone."""
+    import torch
+
+    from paper_2602_14209_amd import binding as mb
+
+    dev = flush_buf.device
+    empty_us = ms["empty_nodes"] * 1e3 / 400
+    # chain over 1 GiB: hop i -> i + n/2 + c (mod n), no two consecutive hops in one DRAM page or cache line
+    n = flush_buf.numel() // 4
+    chain = flush_buf.view(torch.int32)
+    step = n // 2 + 12345 * 16 + 1
+    for j0 in range(0, n, 1 << 26):
+        j1 = min(n, j0 + (1 << 26))
+        chain[j0:j1] = ((torch.arange(j0, j1, device=dev, dtype=torch.int64) + step) % n).to(torch.int32)
+    outp = torch.zeros(1, dtype=torch.int32, device=dev)
+    hops = 2000
+
+    def walk(h, start):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(main_s)
+        mb.check(mb.mage_diag_chase(chain, start, h, outp, main_s), "mage_diag_chase")
+        e1.record(main_s)
+        main_s.synchronize()
+        return e0.elapsed_time(e1) * 1e3
+
+    walk(hops, 0)
+    # a fresh start per repetition (the lines one walk touched must not be the next walk's); the one-hop
+    # walk is the launch itself
+    launch = min(walk(1, 5 + r) for r in range(5))
+    walks = sorted(walk(hops, (r * 104729 * 64) % n) for r in range(1, 6))
+    chase_ns = (walks[2] - launch) / (hops - 1) * 1e3
+    nbytes = flush_buf.numel()
+    read_us = ms["flush_only"] * 1e3 / (T - 1)
+    dst = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+    g_copy = capture(lambda: [mb.check(mb.mage_diag_copy(dst, flush_buf[:dst.numel()], main_s), "mage_diag_copy") for _ in range(4)])
+    copy_us = time_graph(g_copy, reps, 1)[0] * 1e3 / 4
+    esz = 2 if w.dtype == "bf16" else 4
+    gather_bytes = NB * (2 * w.Hkv * k * w.d * esz + 4 * w.Hkv * k)
+    gw, gc = ms["gather_warm"] * 1e3 / (T - 1), ms["gather_cold"] * 1e3 / (T - 1)
+    flush_buf.zero_()
+    return {"empty_kernel_graph_node_us": round(empty_us, 3),
+            "dependent_load_ns": round(chase_ns, 1),
+            "launch_plus_two_dependent_loads_us": round(empty_us + 2 * chase_ns * 1e-3, 3),
+            "read_gbs": round(nbytes / (read_us * 1e-6) / 1e9, 1),
+            "copy_gbs": round(2 * dst.numel() / (copy_us * 1e-6) / 1e9, 1),
+            "gather_only_us_per_launch": {"warm": round(gw, 2), "cold": round(gc, 2)},
+            "gather_only_gbs": {"warm": round(gather_bytes / (gw * 1e-6) / 1e9, 1), "cold": round(gather_bytes / (gc * 1e-6) / 1e9, 1)},
+            "note": "empty kernel: per node of a 400-node HIP graph; dependent load: per hop of a 2000-hop chase over 1 GiB "
+                    "(HBM); read: 1 GiB streamed by mage_diag_read; copy: 256 MiB, read + write bytes; gather only: "
+                    "mage_diag_gather on the batched step's sequences and index sets (index entries and rows, no arithmetic)"}
 
 
 def second_workload(w, k, p, shape, layers, idx, ws_main, main_s, capture, time_graph, reps):

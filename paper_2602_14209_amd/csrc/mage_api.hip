@@ -25,7 +25,8 @@ hipError_t launch_page_summary(const void *kc, void *out, long long L, int Hkv, 
 hipError_t launch_quest_query(const void *q, void *q2, long long rows, int d, hipStream_t stream);
 hipError_t launch_expand_pages(const int32_t *pages, int32_t *idx, int Hkv, int k, int p, hipStream_t stream);
 hipError_t launch_overlap(const int32_t *a, const int32_t *b, int n_rows, int k, int a_rows, float *out, hipStream_t stream);
-hipError_t launch_topk(const float *alpha, const float *group_max, int Hkv, long long L, int k, int32_t *idx_out, hipStream_t stream);
+hipError_t launch_topk(const float *alpha, const float *group_max, int Hkv, long long L, int k, int32_t *idx_out, const RescoreArgs &rs,
+                       hipStream_t stream);
 }  // namespace mage
 
 using namespace mage;
@@ -33,6 +34,34 @@ using namespace mage;
 namespace {
 
 constexpr int64_t kMaxL = (int64_t)1 << 30;
+// Candidates this close (relative) to the k-th averaged probability are re-scored in fp64.  The fp32
+// alpha of the kernels is within 1e-6 (relative) of the exact value (measured at the 32K..128K shapes:
+// median 7e-8, largest 7e-7), so two candidates further apart than this band are ranked correctly.
+constexpr float kNearTieBand = 4e-6f;
+
+// The inputs and row statistics the top-k kernel re-scores near-ties from.
+RescoreArgs rescore_args(const mage_shape &s, const KernelArgs &a, const float *stat_m, const float *stat_l, int n_split, int rpad,
+                         float scale_log2, int key_weight)
+{
+    RescoreArgs r{};
+    r.q = a.q;
+    r.kc = a.kc;
+    r.stat_m = stat_m;
+    r.stat_l = stat_l;
+    r.esz = s.dtype == MAGE_BF16 ? 2 : 4;
+    r.d = s.d;
+    r.Hq = s.Hq;
+    r.Hkv = s.Hkv;
+    r.G = s.Hq / s.Hkv;
+    r.B = s.B;
+    r.R = r.G * s.B;
+    r.n_split = n_split;
+    r.rpad = rpad;
+    r.scale_log2 = scale_log2;
+    r.inv_rows = 1.0 / ((double)r.R * (double)key_weight);
+    r.eps = kNearTieBand;
+    return r;
+}
 
 int check_shape(const mage_shape *s, bool need_k)
 {
@@ -233,7 +262,8 @@ int select_impl(const mage_shape *shape, float scale_log2, int key_weight, const
     if (idx_out) {
         e = bf ? bf16_colsum(c, shape->d, pc.waves, stream) : f32_colsum(c, shape->d, stream);
         if (e != hipSuccess) return MAGE_ERR_HIP;
-        e = launch_topk(a.alpha, a.gmax, shape->Hkv, shape->L, shape->k, idx_out, stream);
+        e = launch_topk(a.alpha, a.gmax, shape->Hkv, shape->L, shape->k, idx_out,
+                        rescore_args(*shape, a, a.part_m, a.part_l, p.n_split, p.rpad, scale_log2, key_weight), stream);
         if (e != hipSuccess) return MAGE_ERR_HIP;
     }
     if (pbar_out) {                                  // the same sums restricted to the B rows of one query head at a time
@@ -405,7 +435,9 @@ int mage_step1(const mage_shape *shape, const void *q1, const void *k_cache, con
     a.alpha = alpha_out ? alpha_out : reinterpret_cast<float *>(w + lay.alpha);
     a.gmax = reinterpret_cast<float *>(w + lay.gmax);
     if (bf16_colsum(a, shape->d, ps.waves, stream) != hipSuccess) return MAGE_ERR_HIP;
-    if (launch_topk(a.alpha, a.gmax, shape->Hkv, shape->L, shape->k, idx_out, stream) != hipSuccess) return MAGE_ERR_HIP;
+    if (launch_topk(a.alpha, a.gmax, shape->Hkv, shape->L, shape->k, idx_out,
+                    rescore_args(*shape, a, stat_m, stat_l, pa.n_split, pa.rpad, a.scale_log2, 1), stream) != hipSuccess)
+        return MAGE_ERR_HIP;
     return MAGE_OK;
 }
 

@@ -185,4 +185,16 @@ struct KernelArgs {
     float inv_rows;          // 1 / (G*B)
 };
 
+// What the top-k kernel needs to re-score the few candidates whose fp32 alpha lies within `eps`
+// (relative) of the k-th value in fp64 from the inputs (see topk.hip); q == nullptr switches it off.
+struct RescoreArgs {
+    const void *q, *kc;              // queries [B,Hq,d], keys [L,Hkv,d]
+    const float *stat_m, *stat_l;    // row statistics per key split [Hkv][n_split][rpad], log2 domain
+    int esz;                         // bytes per element of q / kc: 2 (bf16) or 4 (fp32)
+    int d, Hq, Hkv, G, B, R, n_split, rpad;
+    float scale_log2;                // the factor the statistics were taken with
+    double inv_rows;                 // 1 / (R * key weight)
+    float eps;
+};
+
 }  // namespace mage

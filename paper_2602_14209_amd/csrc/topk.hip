@@ -18,6 +18,13 @@
 //   radix route (any k, any tie structure; also the overflow exit of the filter route): three
 //     MSB-first radix-select steps over the whole row find the k-th value and the number of
 //     ties to keep, then an ordered sweep emits the set.
+// Near-ties at rank k (filter route): alpha is an fp32 result whose relative error (a few 1e-6 from the
+// fp32 dot products, exponentials and sums) is of the order of typical gaps between neighbouring values
+// at rank k, so the fp32 ranking can differ from the ranking of the exactly computed averages.  The
+// candidates within `eps` (relative) of the k-th value -- usually none, a handful at most -- are therefore
+// scored again from the inputs in fp64 (exact dot products, fp64 exponentials, the row normalisers
+// merged in fp64 from the per-split statistics), rounded to fp32 once, and ranked among themselves by
+// (value, smaller index first); as many of them enter the set as the fp32 ranking had admitted.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -33,6 +40,7 @@ constexpr int TK_SLOTS = 8;                          // group maxima per thread 
 constexpr int TK_GROUPS = TK_THREADS * TK_SLOTS;     // 8192
 constexpr int TK_CAND = 4096;                        // candidate capacity of the filter route
 constexpr int TK_FILTER_MAX_K = 2048;
+constexpr int TK_NEAR_MAX = 32;                      // candidates re-scored at most; more of them (massive ties) keep the fp32 ranking
 
 // Inclusive prefix sum over the 64 lanes of a wavefront with data-parallel-primitive moves
 // (row shifts inside rows of 16 lanes, then the row broadcasts of the gfx9 family): eight
@@ -273,7 +281,77 @@ __device__ __forceinline__ int pow2_at_least(int n)
     return p;
 }
 
-__global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, const float *group_max, long long L, int k, int32_t *idx_out)
+__device__ __forceinline__ double load_elem(const void *p, long long i, int esz)
+{
+    if (esz == 2) return (double)__uint_as_float((uint32_t)static_cast<const unsigned short *>(p)[i] << 16);
+    return (double)static_cast<const float *>(p)[i];
+}
+
+// alpha[h, j] in fp64 from the inputs (Eq. 5) for the n listed candidates j = cidx[slot[c]]:
+//   1/(G*B) * sum over the R rows of exp2(q_r.k_j * scale - M_r) / L_r,
+// with (M_r, L_r) the row's softmax statistics merged in fp64 over the key splits.  Four threads per
+// row (a quarter of the channels and of the splits each), 256 rows per pass.  Every thread of the
+// workgroup calls; out[c] receives the results rounded to fp32 (valid after the final barrier).
+__device__ void rescore_candidates(const RescoreArgs &rs, int h, const uint32_t *cidx, const uint32_t *slot, int n, float *out,
+                                   float *rowM, double *rowL, double *acc, double *red)
+{
+    constexpr int ROWS = TK_THREADS / 4;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int part = threadIdx.x & 3, rl = threadIdx.x >> 2;
+    const int cpt = rs.d / 4;
+    if (threadIdx.x < n) acc[threadIdx.x] = 0.0;
+    for (int r0 = 0; r0 < rs.R; r0 += ROWS) {              // uniform trip count (one pass unless R > 256)
+        const int r = r0 + rl;
+        const bool live = r < rs.R;
+        // this row's statistics, merged over the key splits
+        float M = -INFINITY;
+        const long long base = (long long)h * rs.n_split * rs.rpad + (live ? r : 0);
+        for (int s = part; s < rs.n_split; s += 4) M = fmaxf(M, rs.stat_m[base + (long long)s * rs.rpad]);
+        M = fmaxf(M, __shfl_xor(M, 1));
+        M = fmaxf(M, __shfl_xor(M, 2));
+        double Lr = 0.0;
+        for (int s = part; s < rs.n_split; s += 4) {
+            const long long pi = base + (long long)s * rs.rpad;
+            Lr += (double)rs.stat_l[pi] * exp2((double)rs.stat_m[pi] - (double)M);
+        }
+        Lr += __shfl_xor(Lr, 1);
+        Lr += __shfl_xor(Lr, 2);
+        __syncthreads();                                   // the previous pass is done with rowM / rowL
+        if (part == 0) {
+            rowM[rl] = M;
+            rowL[rl] = Lr;
+        }
+        __syncthreads();
+        const int gl = live ? r / rs.B : 0, qi = live ? r - gl * rs.B : 0;
+        const long long qo = ((long long)qi * rs.Hq + (long long)h * rs.G + gl) * rs.d + part * cpt;
+        for (int c = 0; c < n; ++c) {
+            const long long j = (long long)cidx[slot[c]];
+            const long long ko = (j * rs.Hkv + h) * rs.d + part * cpt;
+            double p = 0.0;
+            if (live)
+                for (int e = 0; e < cpt; ++e) p = fma(load_elem(rs.q, qo + e, rs.esz), load_elem(rs.kc, ko + e, rs.esz), p);
+            p += __shfl_xor(p, 1);
+            p += __shfl_xor(p, 2);
+            double t = (live && part == 0) ? exp2(p * (double)rs.scale_log2 - (double)rowM[rl]) / rowL[rl] : 0.0;
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) t += __shfl_xor(t, d);
+            __syncthreads();                               // red may still be read from the previous candidate
+            if (lane == 0) red[wave] = t;
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                double tot = 0.0;
+                for (int w = 0; w < TK_WAVES; ++w) tot += red[w];      // fixed order
+                acc[c] += tot;
+            }
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x < n) out[threadIdx.x] = (float)(acc[threadIdx.x] * rs.inv_rows);
+    __syncthreads();
+}
+
+__global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, const float *group_max, long long L, int k, int32_t *idx_out,
+                                                          const RescoreArgs rs)
 {
     // one histogram per radix step of the filter route, zeroed together at the start; the radix
     // route reuses the first TK_BINS entries
@@ -291,6 +369,11 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
     __shared__ uint32_t cidx[TK_CAND];                   // and their positions
     __shared__ uint32_t glist[TK_CAND];                  // groups at or above the bound (handed-in maxima only)
     __shared__ uint32_t n_hit;
+    __shared__ uint32_t n_near, n_near_in;
+    __shared__ uint32_t near_slot[TK_NEAR_MAX];          // candidates within eps of the k-th value
+    __shared__ float near_val[TK_NEAR_MAX];              // their fp64 score, rounded to fp32
+    __shared__ double red64[TK_WAVES], near_acc[TK_NEAR_MAX], rowL[TK_THREADS / 4];
+    __shared__ float rowM[TK_THREADS / 4];
 
     const int h = blockIdx.x;
     const uint32_t *u = reinterpret_cast<const uint32_t *>(alpha) + (long long)h * L;
@@ -344,6 +427,8 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
         if (threadIdx.x == 0) {
             n_cand = 0;
             n_hit = 0;
+            n_near = 0;
+            n_near_in = 0;
         }
         __syncthreads();
         // a lower bound of the k-th largest group maximum (its top 20 bits), hence of the k-th
@@ -469,6 +554,11 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
                 if (threadIdx.x == 0) n_cand = 0;
                 __syncthreads();
             }
+            // who is in by the fp32 ranking (ctake); the candidates within eps of the k-th value are listed
+            uint32_t *ctake = glist;                         // (the group list has served its purpose)
+            const float thr_f = __uint_as_float(thr);
+            const uint32_t near_lo = __float_as_uint(thr_f * (1.f - rs.eps)), near_hi = __float_as_uint(thr_f * (1.f + rs.eps));
+            const bool rescoring = rs.q != nullptr;
             for (uint32_t i = threadIdx.x; i < nc; i += TK_THREADS) {
                 const uint32_t v = cval[i], j = cidx[i];
                 bool take = v > thr;
@@ -480,7 +570,32 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
                         take = below < want;
                     }
                 }
-                if (take) {
+                ctake[i] = take;
+                if (rescoring && v >= near_lo && v <= near_hi) {
+                    const uint32_t slot = atomicAdd(&n_near, 1u);
+                    if (slot < TK_NEAR_MAX) near_slot[slot] = i;
+                    if (take) atomicAdd(&n_near_in, 1u);
+                }
+            }
+            __syncthreads();
+            const uint32_t nn = n_near, nin = n_near_in;
+            if (rescoring && nn >= 2 && nn <= TK_NEAR_MAX && nin >= 1 && nin < nn) {   // uniform; rare
+                rescore_candidates(rs, h, cidx, near_slot, (int)nn, near_val, rowM, rowL, near_acc, red64);
+                if (threadIdx.x < nn) {                      // rank among the near candidates: value, then smaller position
+                    const uint32_t me = near_slot[threadIdx.x];
+                    const float v = near_val[threadIdx.x];
+                    uint32_t rank = 0;
+                    for (uint32_t c = 0; c < nn; ++c) {
+                        const uint32_t o = near_slot[c];
+                        rank += (near_val[c] > v) || (near_val[c] == v && cidx[o] < cidx[me]);
+                    }
+                    ctake[me] = rank < nin;
+                }
+                __syncthreads();
+            }
+            for (uint32_t i = threadIdx.x; i < nc; i += TK_THREADS) {
+                if (ctake[i]) {
+                    const uint32_t j = cidx[i];
                     if (bitmap) atomicOr(&bits[j >> 5], 1u << (j & 31));
                     else sidx[atomicAdd(&n_cand, 1u)] = (int32_t)j;
                 }
@@ -560,9 +675,10 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
 }
 
 // group_max: nullptr, or [Hkv][ceil(L / kGroupKeys)] maxima of alpha over groups of kGroupKeys consecutive positions
-hipError_t launch_topk(const float *alpha, const float *group_max, int Hkv, long long L, int k, int32_t *idx_out, hipStream_t stream)
+hipError_t launch_topk(const float *alpha, const float *group_max, int Hkv, long long L, int k, int32_t *idx_out, const RescoreArgs &rs,
+                       hipStream_t stream)
 {
-    hipLaunchKernelGGL(topk_kernel, dim3(Hkv), dim3(TK_THREADS), 0, stream, alpha, group_max, L, k, idx_out);
+    hipLaunchKernelGGL(topk_kernel, dim3(Hkv), dim3(TK_THREADS), 0, stream, alpha, group_max, L, k, idx_out, rs);
     return hipGetLastError();
 }
 

@@ -206,6 +206,87 @@ def test_select_ties_and_uniform_on_gpu(oracle_mod):
     check_index_sets(idx, ref["idx"], ref["alpha32"], L)
 
 
+def _plant_near_tie(oracle_mod, q, K, k, h, lo=1.5e-6, hi=3.5e-6):
+    """Make the keys at ranks k and k+1 of KV head h nearly tie: the rank-(k+1) key (a different key,
+    so the two fp32 scores carry unrelated rounding errors) is moved, one bf16 step of one channel at a
+    time, until the two averaged probabilities differ by a relative lo..hi -- more than the band that
+    excuses a mismatch, less than an fp32 pipeline resolves reliably.  The steps are chosen with a numpy
+    model of the change (a search heuristic only); the result is accepted on the oracle's values.
+    Returns (keys, gap) or None."""
+    from paper_2602_14209_amd.workloads import bf16_to_f32, round_to_bf16
+    B, Hq, d = q.shape
+    G = Hq // K.shape[1]
+    ref = oracle_mod.select(q, K, k)
+    order = np.argsort(-ref["alpha"][h], kind="stable")
+    a, b = int(order[k - 1]), int(order[k])
+    Q = q[:, h * G:(h + 1) * G].reshape(B * G, d).astype(np.float64) / np.sqrt(d)
+    K = K.copy()
+    for _ in range(60):
+        Kh = K[:, h].astype(np.float64)
+        S = Q @ Kh.T
+        m = S.max(axis=1, keepdims=True)
+        E = np.exp(S - m)
+        Z = E.sum(axis=1)
+        gap = (E[:, a] / Z).mean() / (E[:, b] / Z).mean() - 1.0          # > 0: a ahead
+        if lo <= abs(gap) <= hi:
+            break
+        # every single bf16 step of key b: new value per (channel, direction)
+        bits = round_to_bf16(K[b, h]).astype(np.int32)
+        best = None
+        for sign in (+1, -1):
+            newv = bf16_to_f32((bits + sign).astype(np.uint16)).astype(np.float64)
+            dS = Q * (newv - Kh[b])[None, :]                                # [rows, channels]: change of the logit of key b
+            Eb = E[:, b][:, None] * np.exp(dS)
+            Zn = Z[:, None] - E[:, b][:, None] + Eb
+            g = (E[:, a][:, None] / Zn).mean(axis=0) / (Eb / Zn).mean(axis=0) - 1.0
+            score = np.where(np.abs(g) >= lo, np.abs(g), np.inf)           # closest to the window from outside, never inside the excuse band
+            c = int(np.argmin(score))
+            if np.isfinite(score[c]) and (best is None or score[c] < best[0]):
+                best = (score[c], c, newv[c])
+        if best is None or best[0] >= abs(gap):
+            return None
+        K[b, h, best[1]] = np.float32(best[2])
+    else:
+        return None
+    r2 = oracle_mod.select(q, K, k)
+    al = r2["alpha"][h]
+    srt = np.argsort(-al, kind="stable")
+    gap = abs(al[a] - al[b]) / al[a]
+    if {int(srt[k - 1]), int(srt[k])} != {a, b} or not (lo <= gap <= hi) or r2["alpha32"][h, a] == r2["alpha32"][h, b]:
+        return None
+    return K, gap
+
+
+@pytest.mark.parametrize("seed", [31, 32, 33, 34, 35, 36])
+def test_near_tie_at_rank_k_follows_the_oracle(oracle_mod, seed):
+    """Two keys whose exact averaged probabilities differ by a few 1e-6 (relative) sit at ranks k and k+1:
+    the fp32 scores of the kernels cannot tell them apart reliably, the fp64 re-score of the candidates
+    near the k-th value must -- in mage_select and in the fused mage_step1."""
+    from gpu_util import Problem, check_index_sets
+    from paper_2602_14209_amd.workloads import bf16_to_f32, round_to_bf16
+    rng = np.random.default_rng(seed)
+    B, Hq, Hkv, d, L, k = 32, 8, 2, 128, 700, 64 + seed
+    qm = rng.standard_normal((1, Hq, d)).astype(np.float32)
+    q = bf16_to_f32(round_to_bf16(qm + 0.1 * rng.standard_normal((B, Hq, d)).astype(np.float32)))
+    K = bf16_to_f32(round_to_bf16(rng.standard_normal((L, Hkv, d)).astype(np.float32)))
+    V = bf16_to_f32(round_to_bf16(rng.standard_normal((L, Hkv, d)).astype(np.float32)))
+    planted = 0
+    for h in range(Hkv):
+        got = _plant_near_tie(oracle_mod, q, K, k, h)
+        if got is None:
+            continue
+        K, gap = got
+        planted += 1
+        print(f"[near-tie] seed={seed} head={h} k={k}: relative gap {gap:.2e} planted at ranks k, k+1", flush=True)
+    assert planted >= 1, "no near-tie could be planted (the construction, not the kernels, needs attention)"
+    ref = oracle_mod.select(q, K, k)
+    p = Problem(q, K, V, None, None, k, "bf16")
+    idx, _ = p.select()
+    check_index_sets(idx, ref["idx"], ref["alpha32"], L)
+    _, _, idx1, _ = p.step1()
+    check_index_sets(idx1, ref["idx"], ref["alpha32"], L)
+
+
 def test_select_long_rows_and_group_overflow(oracle_mod):
     """Top-k filter fed with group maxima: more groups than the LDS copy holds (L > 131072), and a
     row where every group reaches the bound (uniform alpha), which must leave by the radix route."""
