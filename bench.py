@@ -368,6 +368,17 @@ def measure_floors(w, k, NB, T, ms, flush_buf, sink, main_s, capture, time_graph
     dst = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
     g_copy = capture(lambda: [mb.check(mb.mage_diag_copy(dst, flush_buf[:dst.numel()], main_s), "mage_diag_copy") for _ in range(4)])
     copy_us = time_graph(g_copy, reps, 1)[0] * 1e3 / 4
+    # merging partial results across workgroups inside one launch: 64 groups of four workgroups, 8 KB each
+    n_groups = 64
+    m_src = torch.zeros(4 * n_groups * 2048, dtype=torch.float32, device=dev)
+    m_part, m_out = torch.empty_like(m_src), torch.empty(n_groups * 2048, dtype=torch.float32, device=dev)
+    m_cnt = torch.zeros(n_groups, dtype=torch.int32, device=dev)
+    merge_us = {}
+    for mode, name in ((0, "partials_only"), (1, "device_scope_fences"), (2, "fence_free")):
+        g_m = capture(lambda: [mb.check(mb.mage_diag_merge(mode, n_groups, m_part, m_cnt, m_out, m_src, main_s), "mage_diag_merge")
+                               for _ in range(50)])
+        merge_us[name] = round(time_graph(g_m, reps, 1)[0] * 1e3 / 50, 2)
+    assert float(m_out[0]) == 4.0 and float(m_out[1]) == 0.0, "the merge protocol lost a partial"
     esz = 2 if w.dtype == "bf16" else 4
     gather_bytes = NB * (2 * w.Hkv * k * w.d * esz + 4 * w.Hkv * k)
     gw, gc = ms["gather_warm"] * 1e3 / (T - 1), ms["gather_cold"] * 1e3 / (T - 1)
@@ -377,6 +388,7 @@ def measure_floors(w, k, NB, T, ms, flush_buf, sink, main_s, capture, time_graph
             "launch_plus_two_dependent_loads_us": round(empty_us + 2 * chase_ns * 1e-3, 3),
             "read_gbs": round(nbytes / (read_us * 1e-6) / 1e9, 1),
             "copy_gbs": round(2 * dst.numel() / (copy_us * 1e-6) / 1e9, 1),
+            "cross_workgroup_merge_us_per_launch": merge_us,
             "gather_only_us_per_launch": {"warm": round(gw, 2), "cold": round(gc, 2)},
             "gather_only_gbs": {"warm": round(gather_bytes / (gw * 1e-6) / 1e9, 1), "cold": round(gather_bytes / (gc * 1e-6) / 1e9, 1)},
             "note": "empty kernel: per node of a 400-node HIP graph; dependent load: per hop of a 2000-hop chase over 1 GiB "

@@ -254,6 +254,14 @@ int mage_diag_read(const void *src, size_t bytes, uint32_t *sink, void *hip_stre
  * profiler's byte counters are scaled with. */
 int mage_diag_copy(void *dst, const void *src, size_t bytes, void *hip_stream);
 
+/* What merging partial results ACROSS workgroups inside one launch costs.  4 * n_groups workgroups each write
+ * an 8 KB partial (src [4*n_groups*2048] fp32 + 1 in the first of every four floats) to part [4*n_groups*2048];
+ * the last workgroup of each group of four to arrive adds the four partials into out [n_groups*2048].
+ * mode 0: partials only, nobody merges; mode 1: device-scope fences around a counter; mode 2: no fence
+ * instruction (device-scope stores and loads, the writer waits for its stores before the counter).
+ * counters [n_groups] uint32 must be zero before the first launch and keep counting afterwards. */
+int mage_diag_merge(int mode, int n_groups, float *part, unsigned *counters, float *out, const float *src, void *hip_stream);
+
 /* The memory accesses of mage_sparse_attn_batched and nothing else: reads idx [n_seq,Hkv,k] and, for
  * every entry, that row of k_cache and of v_cache [n_seq,L,Hkv,d].  The rate at which the gather
  * itself can run on this GPU (a ceiling for the sparse step).  d * element size <= 256 bytes.

@@ -26,7 +26,7 @@ EXPORTS = ("mage_version", "mage_status_string", "mage_workspace_bytes",
            "mage_compact", "mage_sparse_attn_compact", "mage_sparse_attn_batched",
            "mage_page_summary", "mage_quest_workspace_bytes", "mage_quest_select", "mage_set_overlap",
            "mage_static_scratch_bytes", "mage_select_static",
-           "mage_diag_empty", "mage_diag_chase", "mage_diag_read", "mage_diag_copy", "mage_diag_gather")
+           "mage_diag_empty", "mage_diag_chase", "mage_diag_read", "mage_diag_copy", "mage_diag_merge", "mage_diag_gather")
 
 
 class mage_shape(ctypes.Structure):
@@ -95,6 +95,8 @@ def lib() -> ctypes.CDLL:
         L.mage_diag_read.argtypes = [vp, sz, vp, vp]
         L.mage_diag_copy.restype = ctypes.c_int
         L.mage_diag_copy.argtypes = [vp, vp, sz, vp]
+        L.mage_diag_merge.restype = ctypes.c_int
+        L.mage_diag_merge.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp, vp, vp, vp]
         L.mage_diag_gather.restype = ctypes.c_int
         L.mage_diag_gather.argtypes = [shp, ctypes.c_int, vp, vp, vp, vp, vp]
         _lib = L
@@ -239,6 +241,10 @@ def mage_diag_read(src, sink, stream=None) -> int:
 
 def mage_diag_copy(dst, src, stream=None) -> int:
     return lib().mage_diag_copy(_ptr(dst), _ptr(src), src.numel() * src.element_size(), _stream(stream))
+
+
+def mage_diag_merge(mode: int, n_groups: int, part, counters, out, src, stream=None) -> int:
+    return lib().mage_diag_merge(int(mode), int(n_groups), _ptr(part), _ptr(counters), _ptr(out), _ptr(src), _stream(stream))
 
 
 def mage_diag_gather(shape: mage_shape, n_seq: int, k_cache, v_cache, idx, sink, stream=None) -> int:

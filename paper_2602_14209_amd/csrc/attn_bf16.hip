@@ -795,7 +795,10 @@ void colsum_bf16_kernel(const KernelArgs a)
     const long long cache_stride = (long long)a.Hkv * D;
     const u16 *kc = static_cast<const u16 *>(a.kc) + (long long)h * D;
 
-    auto tile_key = [&](int t) -> long long { return sr.first + t * sr.step; };
+    // The tiles of a split are walked from the END of the cache towards its start: the pass before this
+    // one (row statistics, or the exact attention of the fused step 1) streamed the cache front to back, so
+    // its last part is what the memory-side cache (256 MB) still holds, and this pass meets it first.
+    auto tile_key = [&](int t) -> long long { return sr.first + (long long)(sr.cache_tiles - 1 - t) * sr.step; };
     auto tile_valid = [&](int t) -> int {
         const long long left = sr.nc - tile_key(t);
         return left < kBf16Tile ? (int)left : kBf16Tile;
@@ -803,10 +806,9 @@ void colsum_bf16_kernel(const KernelArgs a)
     unsigned soff[G::LOADS / NW];
     stream_offsets<D, NW>(cache_stride, soff);
     const unsigned lds_wave = __builtin_amdgcn_readfirstlane(lds_addr(smem) + wave * 1024);
-    // all tiles but possibly the last are whole: one comparison per tile in the common case
-    const int n_full = ntiles - ((ntiles > 0 && tile_valid(ntiles - 1) < kBf16Tile) ? 1 : 0);
+    // all tiles but possibly one (the last of the cache, walked first) are whole
     auto issue = [&](int t) {
-        if (t < n_full) {
+        if (tile_valid(t) == kBf16Tile) {
             issue_tile_stream<D, NW, false>(reinterpret_cast<const unsigned char *>(kc + tile_key(t) * cache_stride), 0, soff,
                                             lds_wave + (t % NBUF) * BUF_BYTES);
         } else {

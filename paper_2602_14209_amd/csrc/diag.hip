@@ -5,6 +5,8 @@
 //   chase    one lane following a chain of loads    -> latency of one dependent memory round trip
 //   read     every CU streaming 16-byte loads       -> read bandwidth this GPU reaches
 //   copy     the same with a store per load         -> copy bandwidth (read + write)
+//   merge    four workgroups hand 8 KB each to the last of them to arrive -> what merging partial results
+//            ACROSS workgroups inside one launch would cost (with a device-scope fence, and without one)
 //   gather   the sparse step's memory accesses only -> rate at which 2*Hkv*k scattered rows of d elements
 //            (index entry, then row) can be fetched at all, with no attention arithmetic behind them
 #include <hip/hip_runtime.h>
@@ -106,6 +108,53 @@ __global__ __launch_bounds__(kDiagThreads) void diag_gather_kernel(const unsigne
     if (r == 0x9e3779b9u) sink[0] = r;
 }
 
+// Cross-workgroup merge protocol: every workgroup writes an 8 KB partial; the last of each group of four
+// to arrive (a counter that keeps counting: no reset between launches) adds the four partials up.
+//   MODE 0: partials only, written through (sc1), nobody merges
+//   MODE 1: plain stores, __threadfence() (device-scope release), counter, __threadfence() (acquire), plain loads
+//   MODE 2: no fence instruction: partials written and read with device-scope accesses (sc1, which bypass
+//           the per-XCD L2), the writer waits for its stores to complete before it touches the counter
+template <int MODE>
+__global__ __launch_bounds__(512) void diag_merge_kernel(float *part, unsigned *cnt, float *out, const float *src)
+{
+    const int wg = blockIdx.x, grp = wg / 4, t = threadIdx.x;
+    float4 v = reinterpret_cast<const float4 *>(src)[(size_t)wg * 512 + t];
+    v.x += 1.f;
+    float *my = part + (size_t)wg * 2048 + t * 4;
+    if (MODE == 1) {
+        *reinterpret_cast<float4 *>(my) = v;
+    } else {
+        __hip_atomic_store(my + 0, v.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(my + 1, v.y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(my + 2, v.z, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(my + 3, v.w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (MODE == 0) return;
+    __shared__ unsigned arrival;
+    if (MODE == 1) __threadfence();
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (t == 0) arrival = __hip_atomic_fetch_add(cnt + grp, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if ((arrival & 3u) != 3u) return;
+    if (MODE == 1) __threadfence();
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int w = 0; w < 4; ++w) {
+        const float *p = part + (size_t)(grp * 4 + w) * 2048 + t * 4;
+        float4 x;
+        if (MODE == 1) {
+            x = *reinterpret_cast<const float4 *>(p);
+        } else {
+            x.x = __hip_atomic_load(p + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            x.y = __hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            x.z = __hip_atomic_load(p + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            x.w = __hip_atomic_load(p + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        acc.x += x.x; acc.y += x.y; acc.z += x.z; acc.w += x.w;
+    }
+    reinterpret_cast<float4 *>(out)[(size_t)grp * 512 + t] = acc;
+}
+
 }  // namespace mage
 
 using namespace mage;
@@ -151,6 +200,19 @@ int mage_diag_copy(void *dst, const void *src, size_t bytes, void *hip_stream)
     const size_t n16 = bytes / 16;
     hipLaunchKernelGGL(diag_copy_kernel, dim3(diag_grid(n16)), dim3(kDiagThreads), 0, static_cast<hipStream_t>(hip_stream),
                        static_cast<v4u *>(dst), static_cast<const v4u *>(src), n16);
+    return hipGetLastError() == hipSuccess ? MAGE_OK : MAGE_ERR_HIP;
+}
+
+int mage_diag_merge(int mode, int n_groups, float *part, unsigned *counters, float *out, const float *src, void *hip_stream)
+{
+    if (!part || !counters || !out || !src) return MAGE_ERR_NULL;
+    if (n_groups <= 0 || n_groups > (1 << 16) || mode < 0 || mode > 2) return MAGE_ERR_SHAPE;
+    if (((reinterpret_cast<uintptr_t>(part) | reinterpret_cast<uintptr_t>(out) | reinterpret_cast<uintptr_t>(src)) & 15u)) return MAGE_ERR_ALIGN;
+    dim3 grid(4 * n_groups), block(512);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (mode == 0) hipLaunchKernelGGL(diag_merge_kernel<0>, grid, block, 0, s, part, counters, out, src);
+    else if (mode == 1) hipLaunchKernelGGL(diag_merge_kernel<1>, grid, block, 0, s, part, counters, out, src);
+    else hipLaunchKernelGGL(diag_merge_kernel<2>, grid, block, 0, s, part, counters, out, src);
     return hipGetLastError() == hipSuccess ? MAGE_OK : MAGE_ERR_HIP;
 }
 

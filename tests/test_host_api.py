@@ -192,6 +192,10 @@ def test_measurement_aids_validate_their_arguments():
     assert L.mage_diag_read(fake, 8, fake, None) == -2
     assert L.mage_diag_copy(fake, None, 1024, None) == -1
     assert L.mage_diag_copy(odd, fake, 1024, None) == -6
+    assert L.mage_diag_merge(3, 4, fake, fake, fake, fake, None) == -2
+    assert L.mage_diag_merge(1, 0, fake, fake, fake, fake, None) == -2
+    assert L.mage_diag_merge(1, 4, fake, None, fake, fake, None) == -1
+    assert L.mage_diag_merge(1, 4, odd, fake, fake, fake, None) == -6
     assert L.mage_diag_gather(ctypes.byref(s), 0, fake, fake, fake, fake, None) == -2
     assert L.mage_diag_gather(ctypes.byref(s), 2, fake, None, fake, fake, None) == -1
     sf = mb.make_shape(32, 32, 8, 128, 4096, 512, "f32")                # 512-byte rows
