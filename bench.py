@@ -347,6 +347,7 @@ def measure_floors(w, k, NB, T, ms, flush_buf, sink, main_s, capture, time_graph
         j1 = min(n, j0 + (1 << 26))
         chain[j0:j1] = ((torch.arange(j0, j1, device=dev, dtype=torch.int64) + step) % n).to(torch.int32)
     outp = torch.zeros(1, dtype=torch.int32, device=dev)
+    torch.cuda.synchronize()          # the chain was written on torch's stream, the walks run on main_s
     hops = 2000
 
     def walk(h, start):
@@ -373,6 +374,7 @@ def measure_floors(w, k, NB, T, ms, flush_buf, sink, main_s, capture, time_graph
     m_src = torch.zeros(4 * n_groups * 2048, dtype=torch.float32, device=dev)
     m_part, m_out = torch.empty_like(m_src), torch.empty(n_groups * 2048, dtype=torch.float32, device=dev)
     m_cnt = torch.zeros(n_groups, dtype=torch.int32, device=dev)
+    torch.cuda.synchronize()
     merge_us = {}
     for mode, name in ((0, "partials_only"), (1, "device_scope_fences"), (2, "fence_free")):
         g_m = capture(lambda: [mb.check(mb.mage_diag_merge(mode, n_groups, m_part, m_cnt, m_out, m_src, main_s), "mage_diag_merge")
