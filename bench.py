@@ -16,7 +16,9 @@ say much about a 8 TB/s memory system:
   * cache state: in the replayed chain a layer's selected rows (2 MiB) are revisited after 28 layers' worth
     of other rows (85 MB), which the 256 MB Infinity Cache holds -- `value` is that warm-cache latency;
     `sparse_step_cold_us` streams 1 GiB between two denoising steps (timed alone and subtracted), so that
-    every selected row comes from HBM, as it would with a model's weights streaming between two visits;
+    every selected row comes from HBM; `sparse_step_after_streaming_all_caches_us` puts all layers' exact
+    attention (the whole of every cache, 14 GB) in front of every sparse step, which also empties the address
+    translation caches, as a model's other layers would;
   * bandwidth mode: `--batch` independent sequences per launch (mage_sparse_attn_batched), with the step-1
     index sets (warm) and with a fresh random index set per launch (cold: no row is cache-resident);
   * floors and ceilings measured in this run: an empty kernel as a graph node, a dependent-load chase, the
@@ -207,6 +209,13 @@ def main():
         "gather_cold": capture(lambda: [gather_only(main_s, cold_idx[t - 1]) for t in range(1, T)]),
         "phase2_cold": capture(lambda: [(flush(main_s), [sparse(l, t, main_s) for l in range(NL)]) for t in range(1, T)]),
         "flush_only": capture(lambda: [flush(main_s) for t in range(1, T)]),
+        # every sparse step right after all layers' exact attention (the whole of every cache streamed: translation
+        # caches and data caches start cold, as after a model's other layers); the streaming part is timed alone
+        "phase2_after_stream": capture(lambda: [([exact(l, main_s) for l in range(NL)], [sparse(l, t, main_s) for l in range(NL)])
+                                                for t in range(1, min(T, 4))]),
+        "stream_only": capture(lambda: [[exact(l, main_s) for l in range(NL)] for t in range(1, min(T, 4))]),
+        "phase2_compact_after_stream": capture(lambda: [([exact(l, main_s) for l in range(NL)], [sparse_compact(l, t, main_s) for l in range(NL)])
+                                                        for t in range(1, min(T, 4))]),
         "exact_every_step": capture(lambda: [exact(l, main_s) for t in range(T) for l in range(NL)]),
         "empty_nodes": capture(lambda: [mb.check(mb.mage_diag_empty(main_s), "mage_diag_empty") for _ in range(400)]),
     }
@@ -255,6 +264,8 @@ def main():
     batched_launch_us = ms["phase2_batched"] * 1e3 / (T - 1)          # one launch = NB sequences
     batched_cold_us = ms["phase2_batched_cold"] * 1e3 / (T - 1)
     sparse_cold_us = (ms["phase2_cold"] - ms["flush_only"]) * 1e3 / n_sparse
+    sparse_after_stream_us = (ms["phase2_after_stream"] - ms["stream_only"]) * 1e3 / (NL * (min(T, 4) - 1))
+    compact_after_stream_us = (ms["phase2_compact_after_stream"] - ms["stream_only"]) * 1e3 / (NL * (min(T, 4) - 1))
     exact_every_step_ms = ms["exact_every_step"]
     floors = measure_floors(w, k, NB, T, ms, flush_buf, sink, main_s, capture, time_graph, K)
 
@@ -303,7 +314,9 @@ def main():
         "two_stream_phase1_us_per_layer": round(phase1_us, 2),
         "block_ms": {"mage": round(ms_step, 4), "exact_every_step": round(exact_every_step_ms, 4)},
         "sparse_step_cold_us": round(sparse_cold_us, 3),
+        "sparse_step_after_streaming_all_caches_us": round(sparse_after_stream_us, 3),
         "sparse_step_compact_us": round(sparse_compact_us, 3),
+        "sparse_step_compact_after_streaming_all_caches_us": round(compact_after_stream_us, 3),
         "compact_us_per_layer": round(compact_us, 2),
         "sparse_step_batched": {"sequences_per_launch": NB, "us_per_launch": round(batched_launch_us, 2),
                                 "us_per_sequence": round(batched_launch_us / NB, 3),
