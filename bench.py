@@ -15,10 +15,10 @@ by layers*(T-1)), inputs resident in HBM.  Two things are reported beside it, be
 say much about a 8 TB/s memory system:
   * cache state: in the replayed chain a layer's selected rows (2 MiB) are revisited after 28 layers' worth
     of other rows (85 MB), which the 256 MB Infinity Cache holds -- `value` is that warm-cache latency;
-    `sparse_step_cold_us` streams 1 GiB between two denoising steps (timed alone and subtracted), so that
-    every selected row comes from HBM; `sparse_step_after_streaming_all_caches_us` puts all layers' exact
-    attention (the whole of every cache, 14 GB) in front of every sparse step, which also empties the address
-    translation caches, as a model's other layers would;
+    `sparse_step_cold_us` streams 1 GiB between two denoising steps, so that every selected row comes from
+    HBM (timed with device-clock stamps around the sparse launches); `block_phases` stamps the whole-block
+    graph after step 1 and after every denoising step: the first sparse steps follow the streaming of all
+    layers' caches (14 GB), which also empties the address translation caches, as a model's other layers would;
   * bandwidth mode: `--batch` independent sequences per launch (mage_sparse_attn_batched), with the step-1
     index sets (warm) and with a fresh random index set per launch (cold: no row is cache-resident);
   * floors and ceilings measured in this run: an empty kernel as a graph node, a dependent-load chase, the
@@ -161,6 +161,12 @@ def main():
     def flush(stream):
         mb.check(mb.mage_diag_read(flush_buf, sink, stream), "mage_diag_read")
 
+    cold_stamps = torch.zeros(2 * (T - 1), dtype=torch.int64, device=dev)
+    block_stamps = torch.zeros(NL + T, dtype=torch.int64, device=dev)
+
+    def stamp(buf, i):
+        mb.check(mb.mage_diag_stamp(buf[i:i + 1], main_s), "mage_diag_stamp")
+
     def phase1(overlap=True):
         if overlap:
             side_s.wait_stream(main_s)
@@ -207,15 +213,13 @@ def main():
         "phase2_batched_cold": capture(lambda: [sparse_batched(t, main_s, cold_idx[t - 1]) for t in range(1, T)]),
         "gather_warm": capture(lambda: [gather_only(main_s, big_idx[:NB]) for t in range(1, T)]),
         "gather_cold": capture(lambda: [gather_only(main_s, cold_idx[t - 1]) for t in range(1, T)]),
-        "phase2_cold": capture(lambda: [(flush(main_s), [sparse(l, t, main_s) for l in range(NL)]) for t in range(1, T)]),
+        "phase2_cold": capture(lambda: [(flush(main_s), stamp(cold_stamps, 2 * (t - 1)), [sparse(l, t, main_s) for l in range(NL)],
+                                         stamp(cold_stamps, 2 * (t - 1) + 1)) for t in range(1, T)]),
+        # the whole block again with a time stamp after every layer's step 1 and after every denoising step: where
+        # inside the captured chain the time goes (the first sparse steps run right after every layer's cache was streamed)
+        "step_stamped": capture(lambda: (stamp(block_stamps, 0), [(step1(l, main_s), stamp(block_stamps, 1 + l)) for l in range(NL)],
+                                         [([sparse(l, t, main_s) for l in range(NL)], stamp(block_stamps, NL + t)) for t in range(1, T)])),
         "flush_only": capture(lambda: [flush(main_s) for t in range(1, T)]),
-        # every sparse step right after all layers' exact attention (the whole of every cache streamed: translation
-        # caches and data caches start cold, as after a model's other layers); the streaming part is timed alone
-        "phase2_after_stream": capture(lambda: [([exact(l, main_s) for l in range(NL)], [sparse(l, t, main_s) for l in range(NL)])
-                                                for t in range(1, min(T, 4))]),
-        "stream_only": capture(lambda: [[exact(l, main_s) for l in range(NL)] for t in range(1, min(T, 4))]),
-        "phase2_compact_after_stream": capture(lambda: [([exact(l, main_s) for l in range(NL)], [sparse_compact(l, t, main_s) for l in range(NL)])
-                                                        for t in range(1, min(T, 4))]),
         "exact_every_step": capture(lambda: [exact(l, main_s) for t in range(T) for l in range(NL)]),
         "empty_nodes": capture(lambda: [mb.check(mb.mage_diag_empty(main_s), "mage_diag_empty") for _ in range(400)]),
     }
@@ -248,9 +252,33 @@ def main():
         wall = (time.perf_counter() - t0) * 1e3
         return e0.elapsed_time(e1) / reps, wall / reps
 
+    def stamped(g, buf, reps):
+        """ticks of the device clock stored by the stamp kernels of one replay, [reps, stamps], and the clock's rate"""
+        g.replay()
+        torch.cuda.synchronize()
+        rows = []
+        for _ in range(reps):
+            g.replay()
+            torch.cuda.synchronize()
+            rows.append(buf.cpu().clone())
+        return torch.stack(rows).double(), float(mb.mage_diag_stamp_hz())
+
     K, W = args.steps, args.warmup
     ms_step, wall_step = time_graph(graphs["step"], K, W)
-    ms = {n: time_graph(g, K, 1)[0] for n, g in graphs.items() if n != "step"}
+    ms = {n: time_graph(g, K, 1)[0] for n, g in graphs.items() if n not in ("step", "phase2_cold", "step_stamped")}
+    ticks, hz = stamped(graphs["phase2_cold"], cold_stamps, K)
+    assert hz > 0 and bool((ticks[:, 1::2] > ticks[:, 0::2]).all()), "device clock stamps are not usable"
+    sparse_cold_us = float((ticks[:, 1::2] - ticks[:, 0::2]).median(dim=0).values.mean()) / hz * 1e6 / NL
+    ticks, _ = stamped(graphs["step_stamped"], block_stamps, K)
+    phase_us = (ticks[:, 1:] - ticks[:, :-1]).median(dim=0).values / hz * 1e6          # NL layers of step 1, then steps 2..T
+    block_phases = {"step1_us_per_layer": round(float(phase_us[:NL].mean()), 2),
+                    "step1_us_by_layer": [round(float(x), 1) for x in phase_us[:NL]],
+                    "sparse_us_per_layer_by_step": [round(float(x) / NL, 2) for x in phase_us[NL:]],
+                    "stamped_block_ms": round(float((ticks[:, -1] - ticks[:, 0]).median()) / hz * 1e3, 4),
+                    "note": "the whole-block graph with a device-clock stamp (one more graph node each) after every layer's step 1 "
+                            "and after every denoising step; median over the timed replays. Against the same kernels replayed in "
+                            "loops of their own (step1_fused_us_per_layer, value) the time depends on how long the phase has been "
+                            "running, not on the layer: the chip's power management, not the caches"}
 
     n_sparse = NL * (T - 1)
     sparse_us = ms["phase2"] * 1e3 / n_sparse
@@ -263,9 +291,6 @@ def main():
     sparse_compact_us = ms["phase2_compact"] * 1e3 / n_sparse
     batched_launch_us = ms["phase2_batched"] * 1e3 / (T - 1)          # one launch = NB sequences
     batched_cold_us = ms["phase2_batched_cold"] * 1e3 / (T - 1)
-    sparse_cold_us = (ms["phase2_cold"] - ms["flush_only"]) * 1e3 / n_sparse
-    sparse_after_stream_us = (ms["phase2_after_stream"] - ms["stream_only"]) * 1e3 / (NL * (min(T, 4) - 1))
-    compact_after_stream_us = (ms["phase2_compact_after_stream"] - ms["stream_only"]) * 1e3 / (NL * (min(T, 4) - 1))
     exact_every_step_ms = ms["exact_every_step"]
     floors = measure_floors(w, k, NB, T, ms, flush_buf, sink, main_s, capture, time_graph, K)
 
@@ -280,7 +305,7 @@ def main():
     rooflines = {
         "mage_sparse_attn": roof("mage_sparse_attn", sparse_us, ab["sparse_attn"], "sparse_bf16_kernel (one launch per call)"),
         "mage_sparse_attn_cold": roof("mage_sparse_attn", sparse_cold_us, ab["sparse_attn"],
-                                      "sparse_bf16_kernel, 1 GiB streamed between denoising steps (timed alone and subtracted)"),
+                                      "sparse_bf16_kernel, 1 GiB streamed between denoising steps (device-clock stamps around the sparse launches)"),
         "mage_sparse_attn_batched": roof("mage_sparse_attn_batched", batched_launch_us, NB * ab["sparse_attn"],
                                          f"sparse_batch_kernel, {NB} sequences per launch, step-1 index sets (selected rows cache-resident)"),
         "mage_sparse_attn_batched_cold": roof("mage_sparse_attn_batched", batched_cold_us, NB * ab["sparse_attn"],
@@ -313,10 +338,9 @@ def main():
         "step1_fused_us_per_layer": round(step1_us, 2),
         "two_stream_phase1_us_per_layer": round(phase1_us, 2),
         "block_ms": {"mage": round(ms_step, 4), "exact_every_step": round(exact_every_step_ms, 4)},
+        "block_phases": block_phases,
         "sparse_step_cold_us": round(sparse_cold_us, 3),
-        "sparse_step_after_streaming_all_caches_us": round(sparse_after_stream_us, 3),
         "sparse_step_compact_us": round(sparse_compact_us, 3),
-        "sparse_step_compact_after_streaming_all_caches_us": round(compact_after_stream_us, 3),
         "compact_us_per_layer": round(compact_us, 2),
         "sparse_step_batched": {"sequences_per_launch": NB, "us_per_launch": round(batched_launch_us, 2),
                                 "us_per_sequence": round(batched_launch_us / NB, 3),

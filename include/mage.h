@@ -240,6 +240,13 @@ int mage_set_overlap(const int32_t *a, const int32_t *b, int n_rows, int k, int 
 /* One kernel that does nothing: the cost of a launch slot in a stream or a HIP graph. */
 int mage_diag_empty(void *hip_stream);
 
+/* One kernel that stores the device's constant-rate wall clock to *out (8-byte aligned device memory).
+ * Two of them around a run of launches on one stream -- also inside a captured HIP graph, where no
+ * host-side event can go -- give the time that run took: (later - earlier) / mage_diag_stamp_hz().
+ * mage_diag_stamp_hz: ticks per second of that clock on the current device, 0 if it cannot be queried. */
+int mage_diag_stamp(uint64_t *out, void *hip_stream);
+int64_t mage_diag_stamp_hz(void);
+
 /* One lane follows n_hops dependent loads: i = chain[i], from i = start; the last i goes to *out.
  * chain [n_entries] int32, every entry in [0, n_entries) (a precondition).  Time / n_hops is the
  * latency of one dependent memory round trip (the sparse step has two: index entry, then row). */

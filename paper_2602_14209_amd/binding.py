@@ -26,7 +26,7 @@ EXPORTS = ("mage_version", "mage_status_string", "mage_workspace_bytes",
            "mage_compact", "mage_sparse_attn_compact", "mage_sparse_attn_batched",
            "mage_page_summary", "mage_quest_workspace_bytes", "mage_quest_select", "mage_set_overlap",
            "mage_static_scratch_bytes", "mage_select_static",
-           "mage_diag_empty", "mage_diag_chase", "mage_diag_read", "mage_diag_copy", "mage_diag_merge", "mage_diag_gather")
+           "mage_diag_empty", "mage_diag_stamp", "mage_diag_stamp_hz", "mage_diag_chase", "mage_diag_read", "mage_diag_copy", "mage_diag_merge", "mage_diag_gather")
 
 
 class mage_shape(ctypes.Structure):
@@ -89,6 +89,10 @@ def lib() -> ctypes.CDLL:
         L.mage_select_static.argtypes = [shp, vp, vp, vp, vp, vp]
         L.mage_diag_empty.restype = ctypes.c_int
         L.mage_diag_empty.argtypes = [vp]
+        L.mage_diag_stamp.restype = ctypes.c_int
+        L.mage_diag_stamp.argtypes = [vp, vp]
+        L.mage_diag_stamp_hz.restype = ctypes.c_int64
+        L.mage_diag_stamp_hz.argtypes = []
         L.mage_diag_chase.restype = ctypes.c_int
         L.mage_diag_chase.argtypes = [vp, ctypes.c_int64, ctypes.c_int, ctypes.c_int, vp, vp]
         L.mage_diag_read.restype = ctypes.c_int
@@ -229,6 +233,15 @@ def mage_select_static(shape: mage_shape, q1, k_cache, idx_out, alpha_out, strea
 
 def mage_diag_empty(stream=None) -> int:
     return lib().mage_diag_empty(_stream(stream))
+
+
+def mage_diag_stamp(out, stream=None) -> int:
+    """out: one int64 element of a device tensor (a view such as stamps[i:i+1])."""
+    return lib().mage_diag_stamp(_ptr(out), _stream(stream))
+
+
+def mage_diag_stamp_hz() -> int:
+    return int(lib().mage_diag_stamp_hz())
 
 
 def mage_diag_chase(chain, start: int, n_hops: int, out, stream=None) -> int:

@@ -2,6 +2,8 @@
 // beside the attention kernels' figures.  None of them is part of the method; they exist so that a
 // reader of the benchmark line can tell a latency-bound launch from a bandwidth-bound one:
 //   empty    one kernel that does nothing           -> cost of a launch slot inside a stream / HIP graph
+//   stamp    one lane stores the device's wall clock -> time between two points INSIDE a HIP graph, where no
+//            host-side event can be placed (which phase of a captured chain the time goes to)
 //   chase    one lane following a chain of loads    -> latency of one dependent memory round trip
 //   read     every CU streaming 16-byte loads       -> read bandwidth this GPU reaches
 //   copy     the same with a store per load         -> copy bandwidth (read + write)
@@ -19,6 +21,12 @@ namespace mage {
 typedef unsigned v4u __attribute__((ext_vector_type(4)));   // 16 bytes, a type the nontemporal builtins take
 
 __global__ void diag_empty_kernel() {}
+
+// the constant-rate device clock (not the shader clock), stored with an ordinary vector store
+__global__ __launch_bounds__(64) void diag_stamp_kernel(unsigned long long *out)
+{
+    if (threadIdx.x == 0) *out = wall_clock64();
+}
 
 // chain[i] = index of the next entry; lane 0 of one wavefront walks n_hops dependent loads from `start`
 __global__ __launch_bounds__(64) void diag_chase_kernel(const int32_t *__restrict__ chain, int start, int n_hops, int32_t *out)
@@ -165,6 +173,23 @@ int mage_diag_empty(void *hip_stream)
 {
     hipLaunchKernelGGL(diag_empty_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(hip_stream));
     return hipGetLastError() == hipSuccess ? MAGE_OK : MAGE_ERR_HIP;
+}
+
+int mage_diag_stamp(uint64_t *out, void *hip_stream)
+{
+    if (!out) return MAGE_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(out) & 7u) return MAGE_ERR_ALIGN;
+    hipLaunchKernelGGL(diag_stamp_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(hip_stream),
+                       reinterpret_cast<unsigned long long *>(out));
+    return hipGetLastError() == hipSuccess ? MAGE_OK : MAGE_ERR_HIP;
+}
+
+int64_t mage_diag_stamp_hz(void)
+{
+    int dev = 0, khz = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess) return 0;
+    return (int64_t)khz * 1000;
 }
 
 int mage_diag_chase(const int32_t *chain, int64_t n_entries, int start, int n_hops, int32_t *out, void *hip_stream)

@@ -184,6 +184,8 @@ def test_measurement_aids_validate_their_arguments():
     fake = ctypes.c_void_p(0x1000)
     odd = ctypes.c_void_p(0x1004)
     s = mb.make_shape(32, 32, 8, 128, 4096, 512, "bf16")
+    assert L.mage_diag_stamp(None, None) == -1
+    assert L.mage_diag_stamp(odd, None) == -6
     assert L.mage_diag_chase(None, 16, 0, 4, fake, None) == -1
     assert L.mage_diag_chase(fake, 16, 16, 4, fake, None) == -2
     assert L.mage_diag_chase(fake, 16, 0, 0, fake, None) == -2
