@@ -79,7 +79,10 @@ size_t mage_workspace_bytes(const mage_shape *shape);
  * In:  q1 [B,Hq,d] (the All-[MASK] block's queries), k_cache [L,Hkv,d].
  * Out: idx_out [Hkv,k] int32, each row ascending in j;
  *      alpha_out [Hkv,L] fp32, nullable (the averaged probabilities that were ranked).
- * The ranking is taken on the fp32 alpha the kernels computed.
+ * The ranking is taken on fp32 values of alpha: the ones the kernels computed, except that candidates
+ * within 4e-6 (relative) of the k-th largest are first recomputed from the inputs in fp64 (exact dot
+ * products, fp64 normalisers and exponentials) and rounded once to fp32, so that rounding error of the
+ * fp32 pass cannot decide which of two nearly equal keys is kept.  alpha_out keeps the fp32 pass's values.
  */
 int mage_select(const mage_shape *shape, const void *q1, const void *k_cache,
                 int32_t *idx_out, float *alpha_out,
