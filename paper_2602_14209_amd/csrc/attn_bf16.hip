@@ -1,10 +1,9 @@
 // bf16 MFMA kernels of the MAGE hot path for gfx950 (CDNA4, 64-wide wavefronts).
 //
-//   attn_bf16_kernel<D,MODE,GATHER,AHEAD>
+//   attn_bf16_kernel<D,MODE,AHEAD>
 //     MODE_ATTN : split-key flash-style attention of the G*B query rows of one KV head over a
-//                 slice of keys (contiguous cache rows, or cache rows gathered through the
-//                 selected index set, then optionally the in-block keys) -- Alg. 1 main stream
-//                 "Attn(Q,K,V,C)" and Phase 2 "SparseAttn(Q_h,K_h,V_h,C[S])".
+//                 slice of keys (contiguous cache rows, then optionally the in-block keys) --
+//                 Alg. 1 main stream "Attn(Q,K,V,C)"; also Phase 2 on compacted rows.
 //     MODE_STATS: the same score pass without values: per-row reference and normaliser of
 //                 softmax(Q1 K^T / sqrt(d)) over the prefix (Alg. 1 select stream, first half).
 //     AHEAD     : order of the tile loop (scores one tile ahead of the softmax, or tile by tile).
@@ -327,7 +326,7 @@ struct AttnGeom {
     static constexpr int MAX_WAVES_PER_SIMD = (WITH_V || D > 128) ? 2 : 4;
 };
 
-template <int D, int MODE, bool GATHER, bool AHEAD>
+template <int D, int MODE, bool AHEAD>
 __global__ __launch_bounds__(kAttnWaves * 64) __attribute__((amdgpu_waves_per_eu(2, AttnGeom<D, MODE>::MAX_WAVES_PER_SIMD)))
 void attn_bf16_kernel(const KernelArgs a)
 {
@@ -357,10 +356,7 @@ void attn_bf16_kernel(const KernelArgs a)
 
     // key splits vary fastest over the grid: consecutive workgroups (dealt round-robin to the XCDs)
     // stream neighbouring tiles of the same head, so every XCD touches every HBM channel.
-    // A batched launch (independent sequences, unsplit keys) uses the x axis for the sequence.
-    const bool batched = a.seq_kv != 0;
-    const long long z = batched ? blockIdx.x : 0;
-    const int split = batched ? 0 : blockIdx.x, h = blockIdx.y, rg = blockIdx.z;
+    const int split = blockIdx.x, h = blockIdx.y, rg = blockIdx.z;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, lg = lane >> 5;
     const int rgw = wave & 3, kh = wave >> 2;            // row group and key half of this wavefront
@@ -372,11 +368,10 @@ void attn_bf16_kernel(const KernelArgs a)
     const int ntiles = sr.cache_tiles + sr.blk_tiles;
 
     const long long cache_stride = (long long)a.Hkv * D;
-    const u16 *kc = static_cast<const u16 *>(a.kc) + z * a.seq_kv + (long long)h * D;
-    const u16 *vc = static_cast<const u16 *>(a.vc) + z * a.seq_kv + (long long)h * D;
-    const u16 *kb = static_cast<const u16 *>(a.kblk) + z * a.seq_blk + (long long)h * D;
-    const u16 *vb = static_cast<const u16 *>(a.vblk) + z * a.seq_blk + (long long)h * D;
-    const int32_t *idx = GATHER ? a.idx + z * a.seq_idx + (long long)h * a.nc : nullptr;
+    const u16 *kc = static_cast<const u16 *>(a.kc) + (long long)h * D;
+    const u16 *vc = static_cast<const u16 *>(a.vc) + (long long)h * D;
+    const u16 *kb = static_cast<const u16 *>(a.kblk) + (long long)h * D;
+    const u16 *vb = static_cast<const u16 *>(a.vblk) + (long long)h * D;
 
     auto tile_valid = [&](int t) -> int {
         if (t < sr.cache_tiles) {
@@ -389,25 +384,10 @@ void attn_bf16_kernel(const KernelArgs a)
     unsigned soff[G::LOADS / NW];      // this lane's byte offsets inside a streamed tile
     stream_offsets<D, NW>(cache_stride, soff);
     const unsigned lds_wave = __builtin_amdgcn_readfirstlane(lds_addr(smem) + wave * 1024);
-    // Gathered rows: the index entries of the next kIdxTiles tiles wait in LDS, fetched ahead in
-    // one go.  An index loaded into a register right before its row would sit behind every tile
-    // load in flight (loads retire in order), i.e. drain the ring at every tile.
-    constexpr int kIdxTiles = 16;
-    __shared__ int32_t idx_lds[GATHER ? kIdxTiles * kBf16Tile : 1];
-    const unsigned idx_addr = lds_addr(idx_lds);
-    int idx_t0 = 0;                    // first tile whose entries idx_lds holds
-    auto load_idx = [&](int tc0) {
-        for (int e = threadIdx.x; e < kIdxTiles * kBf16Tile; e += NW * 64) {
-            const int tt = tc0 + e / kBf16Tile;
-            long long pos = sr.first + tt * sr.step + (e % kBf16Tile);
-            if (pos >= sr.nc) pos = sr.nc - 1;              // padding positions re-read the last key (masked below)
-            idx_lds[e] = tt < sr.cache_tiles ? idx[pos] : 0;
-        }
-    };
     // Tiles 0 .. n_full-1 are whole tiles of contiguous cache rows: the common case takes one
-    // comparison per tile; everything else (a ragged last tile, gathered rows, in-block keys) goes
-    // through the general path.
-    const int n_full = GATHER ? 0 : sr.cache_tiles - ((sr.cache_tiles > 0 && tile_valid(sr.cache_tiles - 1) < kBf16Tile) ? 1 : 0);
+    // comparison per tile; everything else (a ragged last tile, in-block keys) goes through the
+    // general path.
+    const int n_full = sr.cache_tiles - ((sr.cache_tiles > 0 && tile_valid(sr.cache_tiles - 1) < kBf16Tile) ? 1 : 0);
     // one matrix (K: IS_V = false, V: true) of tile t into its ring slot; outside the common case
     // the V request of a tile reuses the offsets of its K request, which must be the latest one
     long long goff[G::LOADS / NW];
@@ -425,14 +405,7 @@ void attn_bf16_kernel(const KernelArgs a)
             const int valid = tile_valid(t);
             if (t < sr.cache_tiles) {
                 const long long base = sr.first + t * sr.step;
-                rows_to_offsets<D, NW>(cache_stride, [&](int r) -> long long {
-                    if (GATHER) {
-                        float v = lds_read_f32<0>(idx_addr + ((t - idx_t0) * kBf16Tile + r) * 4);
-                        lds_wait<0>(v);
-                        return (long long)__builtin_bit_cast(int, v);
-                    }
-                    return base + (r < valid ? r : valid - 1);
-                }, goff);
+                rows_to_offsets<D, NW>(cache_stride, [&](int r) -> long long { return base + (r < valid ? r : valid - 1); }, goff);
             } else {
                 const int base = (t - sr.cache_tiles) * kBf16Tile;
                 rows_to_offsets<D, NW>(cache_stride, [&](int r) -> long long { return base + (r < valid ? r : valid - 1); }, goff);
@@ -445,11 +418,7 @@ void attn_bf16_kernel(const KernelArgs a)
 
     // queries first: waiting for them later (loads retire in order) must not mean waiting for tiles
     bf16x8_t qf[KS];
-    load_q_frag<D>(a, static_cast<const u16 *>(a.q) + z * a.seq_q, h, row, qf);
-    if (GATHER) {
-        load_idx(0);
-        __syncthreads();
-    }
+    load_q_frag<D>(a, static_cast<const u16 *>(a.q), h, row, qf);
     // load order (loads retire in it).  AHEAD: K(0), then pairs [V(j), K(j+1)].  Otherwise pairs
     // [K(j), V(j)].  Either way the V request follows the K request of the same tile directly.
     if constexpr (AHEAD) issue_k(0);
@@ -507,14 +476,6 @@ void attn_bf16_kernel(const KernelArgs a)
         // in flight; everyone is done with the tiles before.
         if (t + NBUF - (AHEAD ? 1 : 2) < ntiles) tile_barrier<(NBUF - 2) * LPT>();
         else tile_barrier<0>();
-        if (GATHER) {
-            const int tn = t + NBUF - (AHEAD ? 0 : 1);   // the K tile about to be requested (V requests read no entries)
-            if (tn < sr.cache_tiles && tn >= idx_t0 + kIdxTiles) {   // uniform; every wavefront is past its reads of the old entries
-                load_idx(tn);
-                idx_t0 = tn;
-                __syncthreads();
-            }
-        }
         if constexpr (AHEAD) {
             issue_v(t + NBUF - 1);
             issue_k(t + NBUF);
@@ -726,7 +687,7 @@ void attn_bf16_kernel(const KernelArgs a)
         float *dst;
         if (direct) {
             const int gl = row / a.B, qi = row - gl * a.B;
-            dst = a.out + z * a.seq_out + ((long long)qi * a.Hq + (long long)h * a.G + gl) * D;
+            dst = a.out + ((long long)qi * a.Hq + (long long)h * a.G + gl) * D;
         } else {
             dst = a.part_o + (((long long)h * a.n_split + split) * a.rpad + row) * D;
         }
@@ -746,7 +707,7 @@ void attn_bf16_kernel(const KernelArgs a)
     if (direct) {
         if (a.lse_out) {
             const int gl = row / a.B, qi = row - gl * a.B;
-            a.lse_out[z * a.seq_lse + (long long)qi * a.Hq + (long long)h * a.G + gl] = (m_run + log2f(l_tot)) * 0.6931471805599453f;
+            a.lse_out[(long long)qi * a.Hq + (long long)h * a.G + gl] = (m_run + log2f(l_tot)) * 0.6931471805599453f;
         }
     } else {
         const long long pi = ((long long)h * a.n_split + split) * a.rpad + row;
@@ -941,11 +902,11 @@ void colsum_bf16_kernel(const KernelArgs a)
 }
 
 // ------------------------------------------------------------------------------ launchers
-template <int D, int MODE, bool GATHER, bool AHEAD>
+template <int D, int MODE, bool AHEAD>
 static hipError_t launch_attn(const KernelArgs &a, int row_groups, int grid_x, hipStream_t stream)
 {
     dim3 grid(grid_x, a.Hkv, row_groups), block(kAttnWaves * 64);
-    hipLaunchKernelGGL((attn_bf16_kernel<D, MODE, GATHER, AHEAD>), grid, block, 0, stream, a);
+    hipLaunchKernelGGL((attn_bf16_kernel<D, MODE, AHEAD>), grid, block, 0, stream, a);
     return hipGetLastError();
 }
 
@@ -967,26 +928,26 @@ static bool scores_ahead(const KernelArgs &a, int row_groups)
 }
 
 template <int D>
-static hipError_t launch_attn_any(const KernelArgs &a, int row_groups, bool gather, hipStream_t stream)
+static hipError_t launch_attn_any(const KernelArgs &a, int row_groups, hipStream_t stream)
 {
-    if (gather) return launch_attn<D, MODE_ATTN, true, false>(a, row_groups, a.n_split, stream);
-    return scores_ahead(a, row_groups) ? launch_attn<D, MODE_ATTN, false, true>(a, row_groups, a.n_split, stream)
-                                       : launch_attn<D, MODE_ATTN, false, false>(a, row_groups, a.n_split, stream);
+    return scores_ahead(a, row_groups) ? launch_attn<D, MODE_ATTN, true>(a, row_groups, a.n_split, stream)
+                                       : launch_attn<D, MODE_ATTN, false>(a, row_groups, a.n_split, stream);
 }
 
-hipError_t bf16_attn(const KernelArgs &a, int d, int row_groups, bool gather, hipStream_t stream)
+// dense keys only (the whole cache, or compacted rows): gathered rows are sparse_bf16.hip's
+hipError_t bf16_attn(const KernelArgs &a, int d, int row_groups, hipStream_t stream)
 {
-    if (d == 128) return launch_attn_any<128>(a, row_groups, gather, stream);
-    if (d == 64) return launch_attn_any<64>(a, row_groups, gather, stream);
+    if (d == 128) return launch_attn_any<128>(a, row_groups, stream);
+    if (d == 64) return launch_attn_any<64>(a, row_groups, stream);
     return hipErrorInvalidValue;
 }
 
 hipError_t bf16_stats(const KernelArgs &a, int d, int row_groups, hipStream_t stream)
 {
     // two workgroups per CU already overlap each other's phases: the plain order measured faster
-    if (d == 128) return launch_attn<128, MODE_STATS, false, false>(a, row_groups, a.n_split, stream);
-    if (d == 64) return launch_attn<64, MODE_STATS, false, false>(a, row_groups, a.n_split, stream);
-    if (d == 256) return launch_attn<256, MODE_STATS, false, false>(a, row_groups, a.n_split, stream);   // page-summary rows [max | min] of d = 128
+    if (d == 128) return launch_attn<128, MODE_STATS, false>(a, row_groups, a.n_split, stream);
+    if (d == 64) return launch_attn<64, MODE_STATS, false>(a, row_groups, a.n_split, stream);
+    if (d == 256) return launch_attn<256, MODE_STATS, false>(a, row_groups, a.n_split, stream);   // page-summary rows [max | min] of d = 128
     return hipErrorInvalidValue;
 }
 

@@ -9,7 +9,7 @@
 #include "plan.hpp"
 
 namespace mage {
-hipError_t bf16_attn(const KernelArgs &a, int d, int row_groups, bool gather, hipStream_t stream);
+hipError_t bf16_attn(const KernelArgs &a, int d, int row_groups, hipStream_t stream);
 hipError_t bf16_sparse_batched(const KernelArgs &a, int d, int row_groups, int n_seq, hipStream_t stream);
 hipError_t bf16_stats(const KernelArgs &a, int d, int row_groups, hipStream_t stream);
 hipError_t bf16_colsum(const KernelArgs &a, int d, int waves, hipStream_t stream);
@@ -115,6 +115,7 @@ int attention_check(const mage_shape *shape, const SplitPlan &p, bool gather,
                     const void *workspace, size_t workspace_bytes)
 {
     if (!q || !k_cache || !v_cache || !out || (gather && !idx)) return MAGE_ERR_NULL;
+    if (gather && shape->dtype == MAGE_BF16) return MAGE_ERR_UNSUPPORTED;     // bf16 gathers rows in the sparse kernels, not here
     if ((k_blk == nullptr) != (v_blk == nullptr)) return MAGE_ERR_NULL;
     if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(k_blk) || !aligned16(v_blk) ||
         !aligned16(out) || !aligned16(workspace))
@@ -150,7 +151,7 @@ int run_attention(const mage_shape *shape, const SplitPlan &p, bool gather,
     if (p.n_split > 1) carve_partials(*shape, p, workspace, a);
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    hipError_t e = shape->dtype == MAGE_BF16 ? bf16_attn(a, shape->d, p.row_groups, gather, stream)
+    hipError_t e = shape->dtype == MAGE_BF16 ? bf16_attn(a, shape->d, p.row_groups, stream)
                                              : f32_attn(a, shape->d, p.row_groups, gather, stream);
     if (e != hipSuccess) return MAGE_ERR_HIP;
     if (p.n_split > 1) {
