@@ -10,9 +10,15 @@
 //     (coalesced 64-byte pieces, moved to their MFMA operand lanes by a lane permute) and V rows
 //     straight into LDS (global_load_lds), from where transposing reads (ds_read_b64_tr_b16)
 //     deliver V^T fragments;
+//   - the step has too little work for 256 compute units if a row tile is one workgroup (64 at
+//     Hkv = 8, G*B = 128), and keys cannot be split over workgroups without a merge through memory
+//     that costs more than it saves.  The OUTPUT CHANNELS can: up to four workgroups share a row
+//     tile, each computes the full scores (the softmax statistics are simply computed four times)
+//     but fetches and multiplies only its quarter of every V row.  Measured at Hkv = 8, k = 512:
+//     9.5 us with one workgroup per row tile, 8.4 with two, 7.8 with four;
 //   - workgroups of one KV head sit on the same XCD when Hkv is a multiple of 8 (linear
-//     workgroup id = head + Hkv * row_tile), so a gathered row is fetched from HBM once and
-//     shared through that XCD's L2.
+//     workgroup id = head + Hkv * (row tile, channel part)), so a gathered row is fetched from HBM
+//     once and shared through that XCD's L2.
 // Key positions form one sequence: 0..k-1 are cache rows idx[h,p], k..k+B-1 the in-block rows.
 // v_mfma_f32_16x16x32_bf16 throughout; scores are produced transposed (S^T = K Q^T) so that a
 // lane holds scores of one query row and P^T is already the B operand of O^T = V^T P^T.
@@ -39,17 +45,23 @@ constexpr int SP_MAXT = SP_WAVES * SP_TPW;   // tiles per pass: all of LDS holds
 __device__ __forceinline__ int sp_swz(int r) { return ((r & 7) << 1) | (r >> 3); }
 
 // COMPACT: the k cache positions are rows 0..k-1 of a compacted cache (no index set to read).
+// DS: the output channels of a row tile are dealt to DS workgroups.  Each of them computes the
+// full scores (every K row, all D channels) but fetches and multiplies only its D/DS channels of
+// V: no result crosses workgroups, the softmax statistics are simply computed DS times, and a
+// compute unit has 1/DS of the V bytes to pull through its memory path.
 // Grid z = sequence of a batched launch.
-template <int D, bool COMPACT>
+template <int D, int DS, bool COMPACT>
 __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2))) void sparse_bf16_kernel(const KernelArgs a)
 {
     constexpr int KS = D / 32;                  // MFMA k-steps of the score product
-    constexpr int DT = D / 16;                  // 16-channel tiles of O^T
-    constexpr int CH = D / 8;                   // 16-byte chunks per row
-    constexpr int ROW_BYTES = D * 2;
+    constexpr int DV = D / DS;                  // V channels (and output channels) of this workgroup
+    constexpr int DT = DV / 16;                 // 16-channel tiles of O^T
+    constexpr int CH = DV / 8;                  // 16-byte chunks per V row slice
+    constexpr int ROW_BYTES = DV * 2;           // V row slice in LDS
     constexpr int TILE_BYTES = SP_KT * ROW_BYTES;
     constexpr int VLOADS = TILE_BYTES / 1024;   // wavefront-wide 1 KB loads per V tile
     constexpr int RPL = 1024 / ROW_BYTES;       // rows per such load
+    static_assert(DV % 32 == 0 && VLOADS >= 1, "a V tile is at least one wavefront-wide load");
 
     // V tiles: slot j*8 + wave belongs to this wavefront alone (distinct compile-time offsets, so
     // the compiler sees that the direct loads never overlap).  After the key loop the same memory
@@ -59,7 +71,7 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
     static_assert(PART_BYTES + 2 * SP_WAVES * 16 * 4 <= SP_MAXT * TILE_BYTES, "merge buffers must fit in the V tiles");
     float (*ml)[SP_WAVES][16] = reinterpret_cast<float (*)[SP_WAVES][16]>(vlds + PART_BYTES);
 
-    const int h = blockIdx.x, rt = blockIdx.y;
+    const int h = blockIdx.x, rt = blockIdx.y / DS, dpart = blockIdx.y % DS;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l16 = lane & 15, lg4 = lane >> 4;
     const int row = rt * 16 + l16;
@@ -72,9 +84,9 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
     const long long stride = (long long)a.Hkv * D;
     const long long z = blockIdx.z;
     const u16 *kc = static_cast<const u16 *>(a.kc) + z * a.seq_kv + (long long)h * D;
-    const u16 *vc = static_cast<const u16 *>(a.vc) + z * a.seq_kv + (long long)h * D;
+    const u16 *vc = static_cast<const u16 *>(a.vc) + z * a.seq_kv + (long long)h * D + dpart * DV;
     const u16 *kb = static_cast<const u16 *>(a.kblk) + z * a.seq_blk + (long long)h * D;
-    const u16 *vb = static_cast<const u16 *>(a.vblk) + z * a.seq_blk + (long long)h * D;
+    const u16 *vb = static_cast<const u16 *>(a.vblk) + z * a.seq_blk + (long long)h * D + dpart * DV;
     const int32_t *idx = COMPACT ? nullptr : a.idx + z * a.seq_idx + (long long)h * a.nc;
 
     // query fragment: row l16 of this row tile, channels 32*ks + 8*lg4 .. +7.  Branch-free (rows
@@ -302,9 +314,9 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
         f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int w = 0; w < SP_WAVES; ++w) acc += part[(w * DT + dt) * 64 + lane] * wgt[w];
-        *reinterpret_cast<f32x4_t *>(out + orow * D + 16 * dt + 4 * lg4) = acc * inv;
+        *reinterpret_cast<f32x4_t *>(out + orow * D + dpart * DV + 16 * dt + 4 * lg4) = acc * inv;
     }
-    if (a.lse_out && wave == 0 && lg4 == 0) a.lse_out[z * a.seq_lse + orow] = (M + log2f(lt)) * 0.6931471805599453f;
+    if (a.lse_out && dpart == 0 && wave == 0 && lg4 == 0) a.lse_out[z * a.seq_lse + orow] = (M + log2f(lt)) * 0.6931471805599453f;
 }
 
 // Copies the selected rows into a cache of length k: dst[p,h,:] = src[idx[h,p],h,:] (16 bytes per
@@ -341,19 +353,31 @@ hipError_t launch_compact(const void *k_src, const void *v_src, const int32_t *i
     return hipGetLastError();
 }
 
+template <int D, int DS>
+static hipError_t launch_sparse(const KernelArgs &a, bool compact, int n_seq, hipStream_t stream)
+{
+    dim3 grid(a.Hkv, ((a.R + 15) / 16) * DS, n_seq), block(SP_WAVES * 64);
+    if (compact) hipLaunchKernelGGL((sparse_bf16_kernel<D, DS, true>), grid, block, 0, stream, a);
+    else hipLaunchKernelGGL((sparse_bf16_kernel<D, DS, false>), grid, block, 0, stream, a);
+    return hipGetLastError();
+}
+
+// The output channels are split over as many workgroups (1, 2 or 4 per row tile) as still leaves
+// every workgroup a compute unit of its own.
 hipError_t bf16_sparse(const KernelArgs &a, int d, bool compact, int n_seq, hipStream_t stream)
 {
-    dim3 grid(a.Hkv, (a.R + 15) / 16, n_seq), block(SP_WAVES * 64);
+    const long long wgs = (long long)a.Hkv * ((a.R + 15) / 16) * n_seq;
+    const int ds = 4 * wgs <= kBf16Workgroups ? 4 : 2 * wgs <= kBf16Workgroups ? 2 : 1;
     if (d == 128) {
-        if (compact) hipLaunchKernelGGL((sparse_bf16_kernel<128, true>), grid, block, 0, stream, a);
-        else hipLaunchKernelGGL((sparse_bf16_kernel<128, false>), grid, block, 0, stream, a);
-    } else if (d == 64) {
-        if (compact) hipLaunchKernelGGL((sparse_bf16_kernel<64, true>), grid, block, 0, stream, a);
-        else hipLaunchKernelGGL((sparse_bf16_kernel<64, false>), grid, block, 0, stream, a);
-    } else {
-        return hipErrorInvalidValue;
+        if (ds == 4) return launch_sparse<128, 4>(a, compact, n_seq, stream);
+        if (ds == 2) return launch_sparse<128, 2>(a, compact, n_seq, stream);
+        return launch_sparse<128, 1>(a, compact, n_seq, stream);
     }
-    return hipGetLastError();
+    if (d == 64) {
+        if (ds >= 2) return launch_sparse<64, 2>(a, compact, n_seq, stream);
+        return launch_sparse<64, 1>(a, compact, n_seq, stream);
+    }
+    return hipErrorInvalidValue;
 }
 
 }  // namespace mage

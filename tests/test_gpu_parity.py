@@ -100,6 +100,40 @@ def _attention_only(oracle_mod, w, seed):
     assert rc == -3        # MAGE_ERR_UNSUPPORTED: B*G > 256 with bf16
 
 
+@pytest.mark.parametrize("case", [
+    # the sparse kernel deals a row tile's output channels to 4, 2 or 1 workgroups, by how many workgroups
+    # (KV heads x row tiles) the call has: <= 64, <= 128, more.  name, Hq, Hkv, d, L, B, k
+    ("w1", 40, 20, 128, 900, 56, 150),      # 20 heads x 7 row tiles = 140 workgroups: channels unsplit
+    ("w2", 32, 16, 128, 900, 40, 150),      # 16 x 5 = 80: two workgroups per row tile
+    ("w3", 40, 20, 64, 900, 56, 150),       # d = 64, unsplit
+    ("w4", 8, 2, 128, 3000, 32, 1100),      # four per row tile and two passes over the key positions
+    ("w5", 32, 16, 64, 700, 40, 700),       # d = 64, 80 workgroups: two per row tile, two passes, k = L
+])
+def test_sparse_channel_split_variants(oracle_mod, case):
+    import torch
+    import paper_2602_14209_amd.binding as mb
+    from gpu_util import Problem, check_out
+    name, Hq, Hkv, d, L, B, k = case
+    w = Workload(name, "bf16", Hq=Hq, Hkv=Hkv, d=d, L=L, B=B, ks=(k,), T=2, heavy_frac=0.02, heavy_scale=3.0)
+    seed = zlib.crc32(name.encode()) % 1000 + 5
+    x = make_layer(w, seed, steps=2)
+    rng = np.random.default_rng(seed)
+    idx = np.stack([np.sort(rng.choice(L, k, replace=False)) for _ in range(Hkv)]).astype(np.int32)
+    p = Problem(x["q"][1], x["k_cache"], x["v_cache"], x["k_blk"][1], x["v_blk"][1], k, w.dtype)
+    o_ref, l_ref = oracle_mod.sparse_attn(x["q"][1], x["k_cache"], x["v_cache"], idx, x["k_blk"][1], x["v_blk"][1])
+    print(f"[parity] channel split {case}", flush=True)
+    o, l = p.sparse(idx)
+    check_out(o, o_ref, l, l_ref, w.dtype)
+    k_sel = torch.zeros((k, Hkv, d), dtype=p.kc.dtype, device="cuda")
+    v_sel = torch.zeros_like(k_sel)
+    mb.check(mb.mage_compact(p.shape, p.kc, p.vc, torch.from_numpy(idx).cuda(), k_sel, v_sel), "mage_compact")
+    p.out.fill_(float("nan"))
+    p.lse.fill_(float("nan"))
+    mb.check(mb.mage_sparse_attn_compact(p.shape, p.q, k_sel, v_sel, p.kb, p.vb, p.out, p.lse, p.ws), "compact attn")
+    torch.cuda.synchronize()
+    check_out(p.out.cpu().numpy(), o_ref, p.lse.cpu().numpy(), l_ref, w.dtype)
+
+
 def test_no_block_keys(oracle_mod):
     w = Workload("nb", "bf16", Hq=8, Hkv=2, d=128, L=600, B=32, ks=(128,), T=2, heavy_frac=0.02, heavy_scale=3.0)
     _run_workload(oracle_mod, w, seed=11, blk=False)
