@@ -29,6 +29,7 @@
 #include <stdint.h>
 
 #include "lds_asm.hpp"
+#include "ids.hpp"
 #include "plan.hpp"
 
 namespace mage {
@@ -72,7 +73,7 @@ __device__ __forceinline__ void issue_tile(const u16 *kbase, const u16 *vbase, l
                                            unsigned char *buf, RowOf row_of)
 {
     using G = TileGeom<D>;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = tid_x() & 63, wave = tid_x() >> 6;
 #pragma unroll
     for (int n = 0; n < G::LOADS / NW; ++n) {
         const int unit = n * NW + wave;                            // which 1 KB of the matrix
@@ -92,7 +93,7 @@ template <int D, int NW, class RowOf>
 __device__ __forceinline__ void rows_to_offsets(long long row_stride, RowOf row_of, long long (&off)[TileGeom<D>::LOADS / NW])
 {
     using G = TileGeom<D>;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = tid_x() & 63, wave = tid_x() >> 6;
 #pragma unroll
     for (int n = 0; n < G::LOADS / NW; ++n) {
         const int r = (n * NW + wave) * G::RPI + lane / G::CH;
@@ -104,7 +105,7 @@ template <int D, int NW>
 __device__ __forceinline__ void issue_offsets(const u16 *base, const long long (&off)[TileGeom<D>::LOADS / NW], unsigned char *buf)
 {
     using G = TileGeom<D>;
-    const int wave = threadIdx.x >> 6;
+    const int wave = tid_x() >> 6;
 #pragma unroll
     for (int n = 0; n < G::LOADS / NW; ++n)
         __builtin_amdgcn_global_load_lds(MAGE_GLOBAL_PTR(base + off[n]), MAGE_LDS_PTR(buf + (n * NW + wave) * 1024), 16, 0, 0);
@@ -132,7 +133,7 @@ template <int D, int NW>
 __device__ __forceinline__ void stream_offsets(long long row_stride, unsigned (&off)[TileGeom<D>::LOADS / NW])
 {
     using G = TileGeom<D>;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = tid_x() & 63, wave = tid_x() >> 6;
 #pragma unroll
     for (int n = 0; n < G::LOADS / NW; ++n) {
         const int r = (n * NW + wave) * G::RPI + lane / G::CH;
@@ -265,7 +266,7 @@ __device__ __forceinline__ void issue_vt_group(const unsigned (&va)[2], u32x2_t 
 template <int D>
 __device__ __forceinline__ void load_q_frag(const KernelArgs &a, const u16 *q, int h, int row, bf16x8_t (&qf)[D / 16])
 {
-    const int lg = (threadIdx.x & 63) >> 5;
+    const int lg = (tid_x() & 63) >> 5;
     if (row < a.R) {
         const int gl = row / a.B, qi = row - gl * a.B;
         const u16 *src = q + ((long long)qi * a.Hq + (long long)h * a.G + gl) * D + 8 * lg;
@@ -356,8 +357,8 @@ void attn_bf16_kernel(const KernelArgs a)
 
     // key splits vary fastest over the grid: consecutive workgroups (dealt round-robin to the XCDs)
     // stream neighbouring tiles of the same head, so every XCD touches every HBM channel.
-    const int split = blockIdx.x, h = blockIdx.y, rg = blockIdx.z;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int split = wg_x(), h = wg_y(), rg = wg_z();
+    const int lane = tid_x() & 63, wave = tid_x() >> 6;
     const int l32 = lane & 31, lg = lane >> 5;
     const int rgw = wave & 3, kh = wave >> 2;            // row group and key half of this wavefront
     const int row0 = rg * kAttnRows + rgw * 32;              // first row of this wavefront's M tile
@@ -741,12 +742,12 @@ void colsum_bf16_kernel(const KernelArgs a)
 
     // One grid row per KV head sums all G*B rows of the head (Eq. 5); with head_rows = B there is
     // one grid row per query head, which sums the B rows of that head alone (Eq. 2 per head).
-    const int split = blockIdx.x, hy = blockIdx.y;
+    const int split = wg_x(), hy = wg_y();
     const bool per_head = a.head_rows > 0;
     const int h = per_head ? hy / a.G : hy;                     // KV head whose keys are read
     const int row_lo = per_head ? (hy % a.G) * a.B : 0;         // first row (of the KV head's row space) summed here
     const int R = per_head ? a.head_rows : a.R;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = tid_x() & 63, wave = tid_x() >> 6;
     const int l32 = lane & 31, lg = lane >> 5;
     const int row0 = wave * 32;
     const bool wave_active = row0 < R;
@@ -803,8 +804,8 @@ void colsum_bf16_kernel(const KernelArgs a)
     // and written with inline assembly for the same reason as the tiles.
     const unsigned red_addr = lds_addr(red), ring_addr = lds_addr(ring);
     auto finish = [&](int t) {
-        if (threadIdx.x < kBf16Tile) {
-            const unsigned src = red_addr + ((t & 1) * NW * kBf16Tile + threadIdx.x) * 4;
+        if (tid_x() < kBf16Tile) {
+            const unsigned src = red_addr + ((t & 1) * NW * kBf16Tile + tid_x()) * 4;
             float part[NW];
             static_for<NW>([&](auto W) {
                 constexpr int w = decltype(W)::value;
@@ -817,7 +818,7 @@ void colsum_bf16_kernel(const KernelArgs a)
                 acc += part[w];
             });
             acc *= a.inv_rows;
-            const unsigned dst = ring_addr + ((t % kColsumTiles) * kBf16Tile + threadIdx.x) * 4;
+            const unsigned dst = ring_addr + ((t % kColsumTiles) * kBf16Tile + tid_x()) * 4;
             asm volatile("ds_write_b32 %0, %1" ::"v"(dst), "v"(acc) : "memory");
         }
     };

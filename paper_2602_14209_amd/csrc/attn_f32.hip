@@ -7,6 +7,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "ids.hpp"
 #include "plan.hpp"
 
 namespace mage {
@@ -35,7 +36,7 @@ template <int D>
 __device__ __forceinline__ void f32_load_q(const KernelArgs &a, int h, int row0, float (*qs)[D + 1], int row_end = 1 << 30)
 {
     const float *q = static_cast<const float *>(a.q);
-    for (int e = threadIdx.x; e < kF32Rows * D; e += 256) {
+    for (int e = tid_x(); e < kF32Rows * D; e += 256) {
         const int r = e / D, c = e - r * D, row = row0 + r;
         float v = 0.f;
         if (row < a.R && row < row_end) {
@@ -56,8 +57,8 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const KernelArgs a)
     __shared__ float vs[WITH_V ? kF32Tile : 1][D];
     __shared__ float ps[kF32Rows][kF32Tile + 1];
 
-    const int h = blockIdx.x, split = blockIdx.y, rg = blockIdx.z;
-    const int r = threadIdx.x >> 2, sub = threadIdx.x & 3;
+    const int h = wg_x(), split = wg_y(), rg = wg_z();
+    const int r = tid_x() >> 2, sub = tid_x() & 3;
     const int row0 = rg * kF32Rows, row = row0 + r;
 
     const F32Range sr = f32_range(a, split);
@@ -91,7 +92,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const KernelArgs a)
             valid = left < kF32Tile ? left : kF32Tile;
         }
         __syncthreads();      // previous tile fully consumed (also orders the Q load before first use)
-        for (int e = threadIdx.x; e < kF32Tile * D; e += 256) {
+        for (int e = tid_x(); e < kF32Tile * D; e += 256) {
             const int key = e / D, c = e - key * D;
             const long long pos = base + (key < valid ? key : valid - 1);
             const long long src = from_cache ? (GATHER ? (long long)idx[pos] : pos) : pos;
@@ -182,12 +183,12 @@ __global__ __launch_bounds__(256) void colsum_f32_kernel(const KernelArgs a)
     __shared__ float ls[kF32Rows];
 
     // one grid column per KV head (all G*B rows, Eq. 5), or with head_rows = B per QUERY head (its B rows, Eq. 2)
-    const int hy = blockIdx.x, split = blockIdx.y;
+    const int hy = wg_x(), split = wg_y();
     const bool per_head = a.head_rows > 0;
     const int h = per_head ? hy / a.G : hy;
     const int row_lo = per_head ? (hy % a.G) * a.B : 0;
     const int row_end = per_head ? row_lo + a.head_rows : a.R;
-    const int r = threadIdx.x >> 2, sub = threadIdx.x & 3;
+    const int r = tid_x() >> 2, sub = tid_x() & 3;
     const F32Range sr = f32_range(a, split);
     const int row_groups = per_head ? (a.head_rows + kF32Rows - 1) / kF32Rows : a.rpad / kF32Rows;
     const long long stride = (long long)a.Hkv * D;
@@ -198,7 +199,7 @@ __global__ __launch_bounds__(256) void colsum_f32_kernel(const KernelArgs a)
         const long long left = sr.c1 - base;
         const int valid = left < kF32Tile ? (int)left : kF32Tile;
         __syncthreads();
-        for (int e = threadIdx.x; e < kF32Tile * D; e += 256) {
+        for (int e = tid_x(); e < kF32Tile * D; e += 256) {
             const int key = e / D, c = e - key * D;
             ks[key][c] = kc[(base + (key < valid ? key : valid - 1)) * stride + c];
         }
@@ -207,9 +208,9 @@ __global__ __launch_bounds__(256) void colsum_f32_kernel(const KernelArgs a)
             if (rg > 0 || t == 0 || row_groups > 1) {
                 __syncthreads();
                 f32_load_q<D>(a, h, row_lo + rg * kF32Rows, qs, row_end);
-                if (threadIdx.x < kF32Rows) {
-                    const int row = row_lo + rg * kF32Rows + threadIdx.x;
-                    ls[threadIdx.x] = row < row_end ? a.lse2[(long long)h * a.rpad + row] : INFINITY;
+                if (tid_x() < kF32Rows) {
+                    const int row = row_lo + rg * kF32Rows + tid_x();
+                    ls[tid_x()] = row < row_end ? a.lse2[(long long)h * a.rpad + row] : INFINITY;
                 }
             }
             __syncthreads();
@@ -223,10 +224,10 @@ __global__ __launch_bounds__(256) void colsum_f32_kernel(const KernelArgs a)
                 ps[r][key] = exp2f(fmaf(acc, a.scale_log2, -lse2));
             }
             __syncthreads();
-            if (threadIdx.x < kF32Tile)
-                for (int rr = 0; rr < kF32Rows; ++rr) col += ps[rr][threadIdx.x];
+            if (tid_x() < kF32Tile)
+                for (int rr = 0; rr < kF32Rows; ++rr) col += ps[rr][tid_x()];
         }
-        if (threadIdx.x < kF32Tile && (int)threadIdx.x < valid) a.alpha[(long long)hy * a.L + base + threadIdx.x] = col * a.inv_rows;
+        if (tid_x() < kF32Tile && (int)tid_x() < valid) a.alpha[(long long)hy * a.L + base + tid_x()] = col * a.inv_rows;
     }
 }
 

@@ -15,6 +15,7 @@
 #include <stdint.h>
 
 #include "../../include/mage.h"
+#include "ids.hpp"
 
 namespace mage {
 
@@ -25,13 +26,13 @@ __global__ void diag_empty_kernel() {}
 // the constant-rate device clock (not the shader clock), stored with an ordinary vector store
 __global__ __launch_bounds__(64) void diag_stamp_kernel(unsigned long long *out)
 {
-    if (threadIdx.x == 0) *out = wall_clock64();
+    if (tid_x() == 0) *out = wall_clock64();
 }
 
 // chain[i] = index of the next entry; lane 0 of one wavefront walks n_hops dependent loads from `start`
 __global__ __launch_bounds__(64) void diag_chase_kernel(const int32_t *__restrict__ chain, int start, int n_hops, int32_t *out)
 {
-    if (threadIdx.x != 0) return;
+    if (tid_x() != 0) return;
     int i = start;
     for (int h = 0; h < n_hops; ++h) i = __builtin_nontemporal_load(chain + i);
     *out = i;
@@ -41,10 +42,10 @@ constexpr int kDiagThreads = 256;
 constexpr int kDiagUnroll = 8;      // 16-byte loads in flight per lane
 
 // grid-stride streaming read; the xor of everything read goes to sink[workgroup] so the loads stay
-__global__ __launch_bounds__(kDiagThreads) void diag_read_kernel(const v4u *__restrict__ src, size_t n16, uint32_t *sink)
+__global__ __launch_bounds__(kDiagThreads) void diag_read_kernel(const v4u *__restrict__ src, size_t n16, uint32_t *sink, int n_wg)
 {
-    const size_t stride = (size_t)gridDim.x * kDiagThreads;
-    size_t i = (size_t)blockIdx.x * kDiagThreads + threadIdx.x;
+    const size_t stride = (size_t)n_wg * kDiagThreads;     // n_wg = workgroups launched
+    size_t i = (size_t)wg_x() * kDiagThreads + tid_x();
     v4u acc = {0u, 0u, 0u, 0u};
     for (; i + (kDiagUnroll - 1) * stride < n16; i += kDiagUnroll * stride) {
         v4u v[kDiagUnroll];
@@ -60,13 +61,13 @@ __global__ __launch_bounds__(kDiagThreads) void diag_read_kernel(const v4u *__re
         acc.x ^= v.x; acc.y ^= v.y; acc.z ^= v.z; acc.w ^= v.w;
     }
     const uint32_t r = acc.x ^ acc.y ^ acc.z ^ acc.w;
-    if (r == 0x9e3779b9u) sink[blockIdx.x] = r;      // practically never true: the compiler cannot drop the loads
+    if (r == 0x9e3779b9u) sink[wg_x()] = r;      // practically never true: the compiler cannot drop the loads
 }
 
-__global__ __launch_bounds__(kDiagThreads) void diag_copy_kernel(v4u *__restrict__ dst, const v4u *__restrict__ src, size_t n16)
+__global__ __launch_bounds__(kDiagThreads) void diag_copy_kernel(v4u *__restrict__ dst, const v4u *__restrict__ src, size_t n16, int n_wg)
 {
-    const size_t stride = (size_t)gridDim.x * kDiagThreads;
-    size_t i = (size_t)blockIdx.x * kDiagThreads + threadIdx.x;
+    const size_t stride = (size_t)n_wg * kDiagThreads;     // n_wg = workgroups launched
+    size_t i = (size_t)wg_x() * kDiagThreads + tid_x();
     for (; i + (kDiagUnroll - 1) * stride < n16; i += kDiagUnroll * stride) {
         v4u v[kDiagUnroll];
 #pragma unroll
@@ -87,9 +88,9 @@ __global__ __launch_bounds__(kDiagThreads) void diag_gather_kernel(const unsigne
 {
     const int lanes_per_row = row_bytes / 16;                 // 16 at d = 128 bf16
     const int rows_per_load = 64 / lanes_per_row;             // rows one wavefront-wide load covers
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int z = blockIdx.z, h = blockIdx.y;
-    const int e0 = (blockIdx.x * (kDiagThreads / 64) + wave) * kGatherLoads * rows_per_load;
+    const int lane = tid_x() & 63, wave = tid_x() >> 6;
+    const int z = wg_z(), h = wg_y();
+    const int e0 = (wg_x() * (kDiagThreads / 64) + wave) * kGatherLoads * rows_per_load;
     if (e0 >= k) return;
     const int32_t *ix = idx + ((long long)z * Hkv + h) * k;
     const long long seq = (long long)z * L * Hkv * row_bytes;
@@ -125,7 +126,7 @@ __global__ __launch_bounds__(kDiagThreads) void diag_gather_kernel(const unsigne
 template <int MODE>
 __global__ __launch_bounds__(512) void diag_merge_kernel(float *part, unsigned *cnt, float *out, const float *src)
 {
-    const int wg = blockIdx.x, grp = wg / 4, t = threadIdx.x;
+    const int wg = wg_x(), grp = wg / 4, t = tid_x();
     float4 v = reinterpret_cast<const float4 *>(src)[(size_t)wg * 512 + t];
     v.x += 1.f;
     float *my = part + (size_t)wg * 2048 + t * 4;
@@ -212,8 +213,9 @@ int mage_diag_read(const void *src, size_t bytes, uint32_t *sink, void *hip_stre
     if (!src || !sink) return MAGE_ERR_NULL;
     if (bytes < 16 || (reinterpret_cast<uintptr_t>(src) & 15u)) return bytes < 16 ? MAGE_ERR_SHAPE : MAGE_ERR_ALIGN;
     const size_t n16 = bytes / 16;
-    hipLaunchKernelGGL(diag_read_kernel, dim3(diag_grid(n16)), dim3(kDiagThreads), 0, static_cast<hipStream_t>(hip_stream),
-                       static_cast<const v4u *>(src), n16, sink);
+    const int n_wg = diag_grid(n16);
+    hipLaunchKernelGGL(diag_read_kernel, dim3(n_wg), dim3(kDiagThreads), 0, static_cast<hipStream_t>(hip_stream),
+                       static_cast<const v4u *>(src), n16, sink, n_wg);
     return hipGetLastError() == hipSuccess ? MAGE_OK : MAGE_ERR_HIP;
 }
 
@@ -223,8 +225,9 @@ int mage_diag_copy(void *dst, const void *src, size_t bytes, void *hip_stream)
     if (bytes < 16) return MAGE_ERR_SHAPE;
     if ((reinterpret_cast<uintptr_t>(src) & 15u) || (reinterpret_cast<uintptr_t>(dst) & 15u)) return MAGE_ERR_ALIGN;
     const size_t n16 = bytes / 16;
-    hipLaunchKernelGGL(diag_copy_kernel, dim3(diag_grid(n16)), dim3(kDiagThreads), 0, static_cast<hipStream_t>(hip_stream),
-                       static_cast<v4u *>(dst), static_cast<const v4u *>(src), n16);
+    const int n_wg = diag_grid(n16);
+    hipLaunchKernelGGL(diag_copy_kernel, dim3(n_wg), dim3(kDiagThreads), 0, static_cast<hipStream_t>(hip_stream),
+                       static_cast<v4u *>(dst), static_cast<const v4u *>(src), n16, n_wg);
     return hipGetLastError() == hipSuccess ? MAGE_OK : MAGE_ERR_HIP;
 }
 

@@ -13,7 +13,7 @@ hipError_t bf16_attn(const KernelArgs &a, int d, int row_groups, hipStream_t str
 hipError_t bf16_sparse_batched(const KernelArgs &a, int d, int row_groups, int n_seq, hipStream_t stream);
 hipError_t bf16_stats(const KernelArgs &a, int d, int row_groups, hipStream_t stream);
 hipError_t bf16_colsum(const KernelArgs &a, int d, int waves, hipStream_t stream);
-hipError_t bf16_sparse(const KernelArgs &a, int d, bool compact, int n_seq, hipStream_t stream);
+hipError_t bf16_sparse(const KernelArgs &a, int d, bool compact, hipStream_t stream);
 hipError_t launch_compact(const void *k_src, const void *v_src, const int32_t *idx, void *k_dst, void *v_dst,
                           int Hkv, int d, int k, int esz, hipStream_t stream);
 hipError_t f32_attn(const KernelArgs &a, int d, int row_groups, bool gather, hipStream_t stream);
@@ -201,7 +201,8 @@ int run_sparse_bf16(const mage_shape *shape, bool compact, int n_seq, const void
         // selected row once (the latency-oriented kernel re-reads it per row tile)
         return bf16_sparse_batched(a, shape->d, p.row_groups, n_seq, stream) == hipSuccess ? MAGE_OK : MAGE_ERR_HIP;
     }
-    if (bf16_sparse(a, shape->d, compact, n_seq, stream) != hipSuccess) return MAGE_ERR_HIP;
+    if (n_seq != 1) return MAGE_ERR_UNSUPPORTED;            // compacted rows: one sequence per call
+    if (bf16_sparse(a, shape->d, compact, stream) != hipSuccess) return MAGE_ERR_HIP;
     return MAGE_OK;
 }
 

@@ -9,6 +9,7 @@
 // pages and the block/group average run on the MFMA selection kernels with head dimension 2d.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include "ids.hpp"
 
 namespace mage {
 
@@ -20,7 +21,7 @@ __global__ __launch_bounds__(256) void page_summary_kernel(const unsigned char *
 {
     constexpr int ESZ = BF16 ? 2 : 4, VEC = 16 / ESZ;
     const int cpr = d / VEC;
-    const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+    const long long t = (long long)wg_x() * 256 + tid_x();
     if (t >= n_pages * Hkv * cpr) return;
     const long long P = t / ((long long)Hkv * cpr);
     const int rem = (int)(t % ((long long)Hkv * cpr)), h = rem / cpr, c = rem % cpr;
@@ -60,7 +61,7 @@ __global__ __launch_bounds__(256) void page_summary_kernel(const unsigned char *
 // q2[q][g][0:d] = max(q, 0), q2[q][g][d:2d] = min(q, 0)   (bf16 bit patterns; -0 counts as negative)
 __global__ __launch_bounds__(256) void quest_query_kernel(const uint16_t *__restrict__ q, uint16_t *__restrict__ q2, long long rows, int d)
 {
-    const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+    const long long t = (long long)wg_x() * 256 + tid_x();
     if (t >= rows * d) return;
     const long long r = t / d;
     const int c = (int)(t % d);
@@ -73,7 +74,7 @@ __global__ __launch_bounds__(256) void quest_query_kernel(const uint16_t *__rest
 // idx[h][i] = pages[h][i / p] * p + i % p: the positions of the selected pages, ascending when the pages are
 __global__ __launch_bounds__(256) void expand_pages_kernel(const int32_t *__restrict__ pages, int32_t *__restrict__ idx, int Hkv, int k, int p)
 {
-    const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+    const long long t = (long long)wg_x() * 256 + tid_x();
     if (t >= (long long)Hkv * k) return;
     const int h = (int)(t / k), i = (int)(t % k);
     idx[t] = pages[(long long)h * (k / p) + i / p] * p + i % p;
@@ -84,10 +85,10 @@ __global__ __launch_bounds__(256) void overlap_kernel(const int32_t *__restrict_
                                                       float *__restrict__ out)
 {
     __shared__ int part[4];
-    const int i = blockIdx.x;
+    const int i = wg_x();
     const int32_t *ar = a + (long long)(i % a_rows) * k, *br = b + (long long)i * k;
     int cnt = 0;
-    for (int e = threadIdx.x; e < k; e += 256) {
+    for (int e = tid_x(); e < k; e += 256) {
         const int32_t v = br[e];
         int lo = 0, hi = k;                 // first position with ar[pos] >= v
         while (lo < hi) {
@@ -99,9 +100,9 @@ __global__ __launch_bounds__(256) void overlap_kernel(const int32_t *__restrict_
     }
 #pragma unroll
     for (int dlt = 32; dlt >= 1; dlt >>= 1) cnt += __shfl_xor(cnt, dlt);
-    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = cnt;
+    if ((tid_x() & 63) == 0) part[tid_x() >> 6] = cnt;
     __syncthreads();
-    if (threadIdx.x == 0) out[i] = (float)(part[0] + part[1] + part[2] + part[3]) / (float)k;
+    if (tid_x() == 0) out[i] = (float)(part[0] + part[1] + part[2] + part[3]) / (float)k;
 }
 
 hipError_t launch_page_summary(const void *kc, void *out, long long L, int Hkv, int d, int p, bool bf16, hipStream_t stream)

@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "ids.hpp"
 #include "plan.hpp"
 
 namespace mage {
@@ -21,14 +22,14 @@ __global__ __launch_bounds__(256) void combine_kernel(const KernelArgs a)
     __shared__ float red_m[4];
     __shared__ float4 red_o[SG][TPR];
     __shared__ float red_l[SG];
-    const int row = blockIdx.x, h = blockIdx.y;
-    const int c4 = threadIdx.x % TPR, sg = threadIdx.x / TPR;
+    const int row = wg_x(), h = wg_y();
+    const int c4 = tid_x() % TPR, sg = tid_x() / TPR;
     const long long base = (long long)h * a.n_split * a.rpad + row;
 
     // fused step 1: the last wavefront also merges the prefix-only statistics of this row into the
     // log-sum-exp that the column sums need (as lse_kernel would)
-    if (a.lse2_out != nullptr && (threadIdx.x >> 6) == 3) {
-        const int lane = threadIdx.x & 63;
+    if (a.lse2_out != nullptr && (tid_x() >> 6) == 3) {
+        const int lane = tid_x() & 63;
         float Mp = -INFINITY;
         for (int s = lane; s < a.n_split; s += 64) Mp = fmaxf(Mp, a.stat_m[base + (long long)s * a.rpad]);
 #pragma unroll
@@ -44,10 +45,10 @@ __global__ __launch_bounds__(256) void combine_kernel(const KernelArgs a)
     }
 
     float M = -INFINITY;
-    for (int s = threadIdx.x; s < a.n_split; s += 256) M = fmaxf(M, a.part_m[base + (long long)s * a.rpad]);
+    for (int s = tid_x(); s < a.n_split; s += 256) M = fmaxf(M, a.part_m[base + (long long)s * a.rpad]);
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) M = fmaxf(M, __shfl_xor(M, d));
-    if ((threadIdx.x & 63) == 0) red_m[threadIdx.x >> 6] = M;
+    if ((tid_x() & 63) == 0) red_m[tid_x() >> 6] = M;
     __syncthreads();
     M = fmaxf(fmaxf(red_m[0], red_m[1]), fmaxf(red_m[2], red_m[3]));
 
@@ -90,9 +91,9 @@ __global__ __launch_bounds__(256) void combine_kernel(const KernelArgs a)
 // s, s+64, ...; the sum is accumulated in fp64 in a fixed order.
 __global__ __launch_bounds__(256) void lse_kernel(const KernelArgs a, float *lse2_out)
 {
-    const int h = blockIdx.y;
-    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int lane = threadIdx.x & 63;
+    const int h = wg_y();
+    const int row = wg_x() * 4 + (tid_x() >> 6);
+    const int lane = tid_x() & 63;
     if (row >= a.R) return;
     float M = -INFINITY;
     for (int s = lane; s < a.n_split; s += 64) M = fmaxf(M, a.part_m[((long long)h * a.n_split + s) * a.rpad + row]);

@@ -30,6 +30,7 @@
 #include <stdint.h>
 
 #include "lds_asm.hpp"
+#include "ids.hpp"
 #include "plan.hpp"
 
 namespace mage {
@@ -70,13 +71,13 @@ void sparse_batch_kernel(const KernelArgs a, int n_units, int row_groups)
     // Workgroup id -> (unit, row group): blocks of 8 * row_groups consecutive ids hold 8 units; the
     // row groups of a unit are 8 ids apart, i.e. on the same XCD (ids are dealt round-robin to the 8
     // XCDs) and close in time, so the second reader of a selected row finds it in that XCD's L2.
-    const int blk = blockIdx.x / (8 * row_groups), within = blockIdx.x % (8 * row_groups);
+    const int blk = wg_x() / (8 * row_groups), within = wg_x() % (8 * row_groups);
     const int unit = blk * 8 + (within & 7), rg = within >> 3;
     if (unit >= n_units) return;                         // uniform: ids past the last unit of a ragged block
     const long long z = unit / a.Hkv;
     const int h = unit % a.Hkv;
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: what depends on it alone stays in scalar registers
+    const int lane = tid_x() & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid_x() >> 6);   // scalar: what depends on it alone stays in scalar registers
     const int l16 = lane & 15, lg4 = lane >> 4;
     const int row0 = rg * SB_ROWS + wave * 16, row = row0 + l16;
     const bool wave_active = row0 < a.R;
@@ -100,11 +101,11 @@ void sparse_batch_kernel(const KernelArgs a, int n_units, int row_groups)
         int e[PER];
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
-            const int p = first + i * NW * 64 + (int)threadIdx.x;
+            const int p = first + i * NW * 64 + (int)tid_x();
             e[i] = p < nk ? idx[p] : 0;
         }
 #pragma unroll
-        for (int i = 0; i < PER; ++i) idx_lds[i * NW * 64 + threadIdx.x] = e[i];
+        for (int i = 0; i < PER; ++i) idx_lds[i * NW * 64 + tid_x()] = e[i];
     };
     const unsigned idx_addr = lds_addr(idx_lds);
     // This wavefront's share of a tile: load unit u = n*NW + wave of the 2*MAT_UNITS units (K matrix,

@@ -26,6 +26,7 @@
 #include <stdint.h>
 
 #include "lds_asm.hpp"
+#include "ids.hpp"
 #include "plan.hpp"
 
 namespace mage {
@@ -44,14 +45,26 @@ constexpr int SP_MAXT = SP_WAVES * SP_TPW;   // tiles per pass: all of LDS holds
 // chunk swizzle of a 16-row V tile: rows 0..7 (one half of a transposing read) spread over all banks
 __device__ __forceinline__ int sp_swz(int r) { return ((r & 7) << 1) | (r >> 3); }
 
+// The kernel's own argument block: one launch is so short that the instructions in front of the first
+// load are a visible part of it, so everything that needs a division is worked out on the host.
+struct SparseArgs {
+    const void *q, *kc, *vc, *kblk, *vblk;
+    const int32_t *idx;          // [Hkv][nc] (unused when COMPACT)
+    float *out, *lse_out;
+    int B, Hq, Hkv, G, R;
+    int nc, n_blk;               // cache key positions (k) and in-block keys
+    int ntiles, npass, tpp;      // tiles of SP_KT key positions, passes over the LDS window, tiles per pass (balanced)
+    unsigned inv_B;              // ceil(2^32 / B) for B >= 2: row / B == mulhi(row, inv_B) while row * B < 2^32
+    float scale_log2;
+};
+
 // COMPACT: the k cache positions are rows 0..k-1 of a compacted cache (no index set to read).
 // DS: the output channels of a row tile are dealt to DS workgroups.  Each of them computes the
 // full scores (every K row, all D channels) but fetches and multiplies only its D/DS channels of
 // V: no result crosses workgroups, the softmax statistics are simply computed DS times, and a
 // compute unit has 1/DS of the V bytes to pull through its memory path.
-// Grid z = sequence of a batched launch.
 template <int D, int DS, bool COMPACT>
-__global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2))) void sparse_bf16_kernel(const KernelArgs a)
+__global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2))) void sparse_bf16_kernel(const SparseArgs a)
 {
     constexpr int KS = D / 32;                  // MFMA k-steps of the score product
     constexpr int DV = D / DS;                  // V channels (and output channels) of this workgroup
@@ -71,32 +84,31 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
     static_assert(PART_BYTES + 2 * SP_WAVES * 16 * 4 <= SP_MAXT * TILE_BYTES, "merge buffers must fit in the V tiles");
     float (*ml)[SP_WAVES][16] = reinterpret_cast<float (*)[SP_WAVES][16]>(vlds + PART_BYTES);
 
-    const int h = blockIdx.x, rt = blockIdx.y / DS, dpart = blockIdx.y % DS;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int h = wg_x(), rt = wg_y() / DS, dpart = wg_y() % DS;
+    const int lane = tid_x() & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid_x() >> 6);     // uniform: tile bookkeeping stays on the scalar unit
     const int l16 = lane & 15, lg4 = lane >> 4;
     const int row = rt * 16 + l16;
 
-    const int n_keys = (int)a.nc + a.n_blk;
-    const int ntiles = (n_keys + SP_KT - 1) / SP_KT;
-    const int npass = (ntiles + SP_MAXT - 1) / SP_MAXT;
-    const int tpp = (ntiles + npass - 1) / npass;           // tiles per pass, balanced
+    const int n_keys = a.nc + a.n_blk;
+    const int ntiles = a.ntiles, npass = a.npass, tpp = a.tpp;
 
     const long long stride = (long long)a.Hkv * D;
-    const long long z = blockIdx.z;
-    const u16 *kc = static_cast<const u16 *>(a.kc) + z * a.seq_kv + (long long)h * D;
-    const u16 *vc = static_cast<const u16 *>(a.vc) + z * a.seq_kv + (long long)h * D + dpart * DV;
-    const u16 *kb = static_cast<const u16 *>(a.kblk) + z * a.seq_blk + (long long)h * D;
-    const u16 *vb = static_cast<const u16 *>(a.vblk) + z * a.seq_blk + (long long)h * D + dpart * DV;
-    const int32_t *idx = COMPACT ? nullptr : a.idx + z * a.seq_idx + (long long)h * a.nc;
+    const u16 *kc = static_cast<const u16 *>(a.kc) + h * D;
+    const u16 *vc = static_cast<const u16 *>(a.vc) + h * D + dpart * DV;
+    const u16 *kb = static_cast<const u16 *>(a.kblk) + h * D;
+    const u16 *vb = static_cast<const u16 *>(a.vblk) + h * D + dpart * DV;
+    const int32_t *idx = COMPACT ? nullptr : a.idx + (long long)h * a.nc;
 
     // query fragment: row l16 of this row tile, channels 32*ks + 8*lg4 .. +7.  Branch-free (rows
     // past R re-read the last row and are never stored): a branch here would end in a wait for
     // these loads before the index entries are even requested.
     bf16x8_t qf[KS];
+    const int rq = row < a.R ? row : a.R - 1;
+    const int gl = a.B == 1 ? rq : (int)(((unsigned long long)(unsigned)rq * a.inv_B) >> 32), qi = rq - gl * a.B;
+    const int orow = qi * a.Hq + h * a.G + gl;                  // row of q, out and lse
     {
-        const int rq = row < a.R ? row : a.R - 1;
-        const int gl = rq / a.B, qi = rq - gl * a.B;
-        const u16 *src = static_cast<const u16 *>(a.q) + z * a.seq_q + ((long long)qi * a.Hq + (long long)h * a.G + gl) * D + 8 * lg4;
+        const u16 *src = static_cast<const u16 *>(a.q) + (long long)orow * D + 8 * lg4;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) qf[ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(src + ks * 32));
     }
@@ -124,16 +136,17 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
         auto src_row = [&](int tile, int r) {
             int p = tile * SP_KT + r;
             p = p < n_keys ? p : n_keys - 1;                // padding positions re-read the last key (masked below)
-            const int pc = p < (int)a.nc ? p : (int)a.nc - 1;
+            const int pc = p < a.nc ? p : a.nc - 1;
             const int ci = COMPACT ? pc : idx[pc];
-            return p < (int)a.nc ? ci : -1 - (p - (int)a.nc);
+            return p < a.nc ? ci : -1 - (p - a.nc);
         };
 #pragma unroll
         for (int j = 0; j < SP_TPW; ++j) {
             tile_of[j] = first + SP_WAVES * (j < my_tiles ? j : my_tiles - 1);
             ek[j] = src_row(tile_of[j], lane >> 2);
 #pragma unroll
-            for (int n = 0; n < VLOADS; ++n) ev[j][n] = src_row(tile_of[j], n * RPL + lane / CH);
+            for (int n = 0; n < VLOADS; ++n)                  // a 64-byte V slice is fetched by the lane quad that fetches the K row
+                ev[j][n] = (RPL == SP_KT && CH == 4) ? ek[j] : src_row(tile_of[j], n * RPL + lane / CH);
         }
         // K fragments.  The MFMA wants lane (16*c + r) to hold channels [32*ks + 8*c, +8) of tile row r,
         // but a load in that pattern touches 64 separate 16-byte pieces per instruction.  Load
@@ -306,17 +319,15 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
         lt = fmaf(wgt[w], ml[1][w][l16], lt);
     }
     if (row >= a.R) return;
-    const int gl = row / a.B, qi = row - gl * a.B;
-    const long long orow = (long long)qi * a.Hq + (long long)h * a.G + gl;
-    float *out = a.out + z * a.seq_out;
+    float *out = a.out;
     const float inv = 1.f / lt;
     for (int dt = wave; dt < DT; dt += SP_WAVES) {
         f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int w = 0; w < SP_WAVES; ++w) acc += part[(w * DT + dt) * 64 + lane] * wgt[w];
-        *reinterpret_cast<f32x4_t *>(out + orow * D + dpart * DV + 16 * dt + 4 * lg4) = acc * inv;
+        *reinterpret_cast<f32x4_t *>(out + (long long)orow * D + dpart * DV + 16 * dt + 4 * lg4) = acc * inv;
     }
-    if (a.lse_out && dpart == 0 && wave == 0 && lg4 == 0) a.lse_out[z * a.seq_lse + orow] = (M + log2f(lt)) * 0.6931471805599453f;
+    if (a.lse_out && dpart == 0 && wave == 0 && lg4 == 0) a.lse_out[orow] = (M + log2f(lt)) * 0.6931471805599453f;
 }
 
 // Copies the selected rows into a cache of length k: dst[p,h,:] = src[idx[h,p],h,:] (16 bytes per
@@ -328,7 +339,7 @@ __global__ __launch_bounds__(256) void compact_kernel(const unsigned char *__res
                                                       unsigned char *__restrict__ v_dst, int Hkv, int d, int k)
 {
     const int cpr = d * ESZ / 16;                                // 16-byte chunks per row
-    const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+    const long long t = (long long)wg_x() * 256 + tid_x();
     const long long rowid = t / cpr;                             // (p, h)
     const int c = (int)(t % cpr);
     if (rowid >= (long long)k * Hkv) return;
@@ -354,9 +365,9 @@ hipError_t launch_compact(const void *k_src, const void *v_src, const int32_t *i
 }
 
 template <int D, int DS>
-static hipError_t launch_sparse(const KernelArgs &a, bool compact, int n_seq, hipStream_t stream)
+static hipError_t launch_sparse(const SparseArgs &a, bool compact, hipStream_t stream)
 {
-    dim3 grid(a.Hkv, ((a.R + 15) / 16) * DS, n_seq), block(SP_WAVES * 64);
+    dim3 grid(a.Hkv, ((a.R + 15) / 16) * DS), block(SP_WAVES * 64);
     if (compact) hipLaunchKernelGGL((sparse_bf16_kernel<D, DS, true>), grid, block, 0, stream, a);
     else hipLaunchKernelGGL((sparse_bf16_kernel<D, DS, false>), grid, block, 0, stream, a);
     return hipGetLastError();
@@ -364,18 +375,29 @@ static hipError_t launch_sparse(const KernelArgs &a, bool compact, int n_seq, hi
 
 // The output channels are split over as many workgroups (1, 2 or 4 per row tile) as still leaves
 // every workgroup a compute unit of its own.
-hipError_t bf16_sparse(const KernelArgs &a, int d, bool compact, int n_seq, hipStream_t stream)
+hipError_t bf16_sparse(const KernelArgs &k, int d, bool compact, hipStream_t stream)
 {
-    const long long wgs = (long long)a.Hkv * ((a.R + 15) / 16) * n_seq;
+    if (k.nc <= 0 || k.nc > 0x7fffffff - k.n_blk || k.R <= 0 || (long long)k.R * k.B >= (1ll << 32)) return hipErrorInvalidValue;
+    SparseArgs a{};
+    a.q = k.q; a.kc = k.kc; a.vc = k.vc; a.kblk = k.kblk; a.vblk = k.vblk; a.idx = k.idx;
+    a.out = k.out; a.lse_out = k.lse_out;
+    a.B = k.B; a.Hq = k.Hq; a.Hkv = k.Hkv; a.G = k.G; a.R = k.R;
+    a.nc = (int)k.nc; a.n_blk = k.n_blk;
+    a.ntiles = (a.nc + a.n_blk + SP_KT - 1) / SP_KT;
+    a.npass = (a.ntiles + SP_MAXT - 1) / SP_MAXT;
+    a.tpp = (a.ntiles + a.npass - 1) / a.npass;
+    a.inv_B = k.B >= 2 ? (unsigned)(((1ull << 32) + k.B - 1) / k.B) : 0u;
+    a.scale_log2 = k.scale_log2;
+    const long long wgs = (long long)a.Hkv * ((a.R + 15) / 16);
     const int ds = 4 * wgs <= kBf16Workgroups ? 4 : 2 * wgs <= kBf16Workgroups ? 2 : 1;
     if (d == 128) {
-        if (ds == 4) return launch_sparse<128, 4>(a, compact, n_seq, stream);
-        if (ds == 2) return launch_sparse<128, 2>(a, compact, n_seq, stream);
-        return launch_sparse<128, 1>(a, compact, n_seq, stream);
+        if (ds == 4) return launch_sparse<128, 4>(a, compact, stream);
+        if (ds == 2) return launch_sparse<128, 2>(a, compact, stream);
+        return launch_sparse<128, 1>(a, compact, stream);
     }
     if (d == 64) {
-        if (ds >= 2) return launch_sparse<64, 2>(a, compact, n_seq, stream);
-        return launch_sparse<64, 1>(a, compact, n_seq, stream);
+        if (ds >= 2) return launch_sparse<64, 2>(a, compact, stream);
+        return launch_sparse<64, 1>(a, compact, stream);
     }
     return hipErrorInvalidValue;
 }

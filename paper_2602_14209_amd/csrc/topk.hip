@@ -28,6 +28,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "ids.hpp"
 #include "plan.hpp"
 
 namespace mage {
@@ -70,7 +71,7 @@ __device__ __forceinline__ uint32_t lane_value(uint32_t v, int lane_uniform)
 // per-wavefront totals itself (TK_WAVES <= 64 lanes), so nothing runs on a single thread.
 __device__ __forceinline__ uint32_t block_scan_incl(uint32_t v, uint32_t *tmp, uint32_t &total)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = tid_x() & 63, wave = tid_x() >> 6;
     const uint32_t x = wave_scan_incl(v);
     __syncthreads();                      // tmp may still be read from a previous call
     if (lane == 63) tmp[wave] = x;
@@ -102,7 +103,7 @@ __device__ __forceinline__ void radix_count(uint32_t x, bool in, int shift, uint
 template <int BITS, int UNR = 8>
 __device__ __forceinline__ void radix_hist_mem(const uint32_t *u, long long n, int shift, uint32_t prefix, uint32_t *hist)
 {
-    for (long long j0 = threadIdx.x; j0 < n; j0 += (long long)TK_THREADS * UNR) {
+    for (long long j0 = tid_x(); j0 < n; j0 += (long long)TK_THREADS * UNR) {
         uint32_t x[UNR];
 #pragma unroll
         for (int i = 0; i < UNR; ++i) {
@@ -128,16 +129,16 @@ __device__ __forceinline__ void radix_pick(int shift, uint32_t &prefix, uint32_t
 {
     constexpr int NB = 1 << BITS;
     constexpr int PER = NB > TK_THREADS ? NB / TK_THREADS : 1;       // bins per thread
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = tid_x() & 63, wave = tid_x() >> 6;
     __syncthreads();
     uint32_t mine = 0;
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
-        const int b = threadIdx.x * PER + i;
+        const int b = tid_x() * PER + i;
         mine += b < NB ? hist[b] : 0u;
     }
     const uint32_t incl = wave_scan_incl(mine);
-    lscan[threadIdx.x] = incl;
+    lscan[tid_x()] = incl;
     if (lane == 63) wtot[wave] = incl;
     __syncthreads();
     // the wavefront, then the thread, in whose bins the running count reaches `want`
@@ -174,7 +175,7 @@ template <int BITS>
 __device__ __forceinline__ void radix_step_once(const uint32_t *u, uint32_t n, int shift, uint32_t &prefix, uint32_t &want,
                                                 uint32_t &bucket, uint32_t *hist, uint32_t *lscan, uint32_t *wtot)
 {
-    for (uint32_t j = threadIdx.x; j < n; j += TK_THREADS) radix_count<BITS>(u[j], true, shift, prefix, hist);
+    for (uint32_t j = tid_x(); j < n; j += TK_THREADS) radix_count<BITS>(u[j], true, shift, prefix, hist);
     radix_pick<BITS>(shift, prefix, want, bucket, hist, lscan, wtot);
 }
 
@@ -188,10 +189,10 @@ __device__ __forceinline__ void radix_step(const uint32_t *u, long long n, int s
 {
     const int nb = 1 << bits;
     const uint32_t hi_mask = (shift + bits >= 32) ? 0u : (0xffffffffu << (shift + bits));
-    for (int b = threadIdx.x; b < nb; b += TK_THREADS) hist[b] = 0;
+    for (int b = tid_x(); b < nb; b += TK_THREADS) hist[b] = 0;
     __syncthreads();
     constexpr int UNR = 8;      // independent loads in flight per thread
-    for (long long j0 = threadIdx.x; j0 < n; j0 += (long long)TK_THREADS * UNR) {
+    for (long long j0 = tid_x(); j0 < n; j0 += (long long)TK_THREADS * UNR) {
         uint32_t x[UNR];
 #pragma unroll
         for (int i = 0; i < UNR; ++i) {
@@ -209,7 +210,7 @@ __device__ __forceinline__ void radix_step(const uint32_t *u, long long n, int s
     const int per = (nb + TK_THREADS - 1) / TK_THREADS;
     uint32_t mine = 0;
     for (int i = 0; i < per; ++i) {
-        const int b = nb - 1 - (threadIdx.x * per + i);
+        const int b = nb - 1 - (tid_x() * per + i);
         if (b >= 0) mine += hist[b];
     }
     uint32_t total;
@@ -218,7 +219,7 @@ __device__ __forceinline__ void radix_step(const uint32_t *u, long long n, int s
     if (excl < want && want <= incl) {     // exactly one thread: the bucket lies in its bins
         uint32_t run = excl;
         for (int i = 0; i < per; ++i) {
-            const int b = nb - 1 - (threadIdx.x * per + i);
+            const int b = nb - 1 - (tid_x() * per + i);
             if (b < 0) break;
             const uint32_t c = hist[b];
             if (run < want && want <= run + c) {
@@ -249,7 +250,7 @@ __device__ __forceinline__ void bitonic_sort(T *a, int P)
             if (j >= 64 || need_barrier) __syncthreads();
             else __builtin_amdgcn_wave_barrier();
             need_barrier = j >= 64;          // the stage after a cross-wavefront stage must see its writes
-            for (int i = threadIdx.x; i < P / 2; i += TK_THREADS) {
+            for (int i = tid_x(); i < P / 2; i += TK_THREADS) {
                 const int lo = ((i & ~(j - 1)) << 1) | (i & (j - 1)), hi = lo | j;
                 const bool up = (lo & k2) == 0;
                 const T x = a[lo], y = a[hi];
@@ -296,10 +297,10 @@ __device__ void rescore_candidates(const RescoreArgs &rs, int h, const uint32_t 
                                    float *rowM, double *rowL, double *acc, double *red)
 {
     constexpr int ROWS = TK_THREADS / 4;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int part = threadIdx.x & 3, rl = threadIdx.x >> 2;
+    const int lane = tid_x() & 63, wave = tid_x() >> 6;
+    const int part = tid_x() & 3, rl = tid_x() >> 2;
     const int cpt = rs.d / 4;
-    if (threadIdx.x < n) acc[threadIdx.x] = 0.0;
+    if (tid_x() < n) acc[tid_x()] = 0.0;
     for (int r0 = 0; r0 < rs.R; r0 += ROWS) {              // uniform trip count (one pass unless R > 256)
         const int r = r0 + rl;
         const bool live = r < rs.R;
@@ -338,7 +339,7 @@ __device__ void rescore_candidates(const RescoreArgs &rs, int h, const uint32_t 
             __syncthreads();                               // red may still be read from the previous candidate
             if (lane == 0) red[wave] = t;
             __syncthreads();
-            if (threadIdx.x == 0) {
+            if (tid_x() == 0) {
                 double tot = 0.0;
                 for (int w = 0; w < TK_WAVES; ++w) tot += red[w];      // fixed order
                 acc[c] += tot;
@@ -346,7 +347,7 @@ __device__ void rescore_candidates(const RescoreArgs &rs, int h, const uint32_t 
         }
     }
     __syncthreads();
-    if (threadIdx.x < n) out[threadIdx.x] = (float)(acc[threadIdx.x] * rs.inv_rows);
+    if (tid_x() < n) out[tid_x()] = (float)(acc[tid_x()] * rs.inv_rows);
     __syncthreads();
 }
 
@@ -375,13 +376,13 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
     __shared__ double red64[TK_WAVES], near_acc[TK_NEAR_MAX], rowL[TK_THREADS / 4];
     __shared__ float rowM[TK_THREADS / 4];
 
-    const int h = blockIdx.x;
+    const int h = wg_x();
     const uint32_t *u = reinterpret_cast<const uint32_t *>(alpha) + (long long)h * L;
     int32_t *out = idx_out + (long long)h * k;
 
     if (k <= TK_FILTER_MAX_K) {
         const bool vec_ok = (L & 3) == 0 && (reinterpret_cast<uintptr_t>(u) & 15) == 0;
-        const int lane = threadIdx.x & 63;
+        const int lane = tid_x() & 63;
         const long long ng = (L + kGroupKeys - 1) / kGroupKeys;       // handed-in group maxima
         // the maxima buffer serves the last phase only (position bitmap / index sort buffer)
         const bool bitmap = L <= (long long)TK_GROUPS * 32;
@@ -401,7 +402,7 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
             if (in_regs) {
 #pragma unroll
                 for (int s = 0; s < TK_SLOTS; ++s) {
-                    const int g = s * TK_THREADS + threadIdx.x;
+                    const int g = s * TK_THREADS + tid_x();
                     if (g < ng) gv[s] = gg[g];
                 }
             }
@@ -411,7 +412,7 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
             for (long long base0 = 0; base0 < L; base0 += 4ll * TK_GROUPS) {
                 uint4 x[TK_SLOTS];
 #pragma unroll
-                for (int s = 0; s < TK_SLOTS; ++s) x[s] = load4(u, base0 + 4ll * (s * TK_THREADS + threadIdx.x), L, vec_ok);
+                for (int s = 0; s < TK_SLOTS; ++s) x[s] = load4(u, base0 + 4ll * (s * TK_THREADS + tid_x()), L, vec_ok);
 #pragma unroll
                 for (int s = 0; s < TK_SLOTS; ++s) {
                     const uint32_t a = x[s].x > x[s].y ? x[s].x : x[s].y, b = x[s].z > x[s].w ? x[s].z : x[s].w;
@@ -421,10 +422,10 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
             }
         }
         // while the loads travel: every histogram and the buffer of the last phase start at zero
-        for (int i = threadIdx.x; i < H_ALL; i += TK_THREADS) hists[i] = 0u;
-        if (bitmap) for (int i = threadIdx.x; i < words; i += TK_THREADS) bits[i] = 0u;
-        else for (int i = threadIdx.x; i < P2; i += TK_THREADS) sidx[i] = 0x7fffffff;
-        if (threadIdx.x == 0) {
+        for (int i = tid_x(); i < H_ALL; i += TK_THREADS) hists[i] = 0u;
+        if (bitmap) for (int i = tid_x(); i < words; i += TK_THREADS) bits[i] = 0u;
+        else for (int i = tid_x(); i < P2; i += TK_THREADS) sidx[i] = 0x7fffffff;
+        if (tid_x() == 0) {
             n_cand = 0;
             n_hit = 0;
             n_near = 0;
@@ -471,14 +472,14 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
                 if (!in_regs) {
 #pragma unroll
                     for (int s = 0; s < TK_SLOTS; ++s) {
-                        const long long g = g0 + (long long)s * TK_THREADS + threadIdx.x;
+                        const long long g = g0 + (long long)s * TK_THREADS + tid_x();
                         gv[s] = g < ng ? gg[g] : 0u;
                     }
                 }
                 uint32_t cnt = 0;
 #pragma unroll
                 for (int s = 0; s < TK_SLOTS; ++s) {
-                    const long long g = g0 + (long long)s * TK_THREADS + threadIdx.x;
+                    const long long g = g0 + (long long)s * TK_THREADS + tid_x();
                     cnt += (g < ng && gv[s] >= floor_bits);
                 }
                 const uint32_t incl = wave_scan_incl(cnt);
@@ -489,7 +490,7 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
                 uint32_t pos = lane_value(base, 0) + incl - cnt;
 #pragma unroll
                 for (int s = 0; s < TK_SLOTS; ++s) {
-                    const long long g = g0 + (long long)s * TK_THREADS + threadIdx.x;
+                    const long long g = g0 + (long long)s * TK_THREADS + tid_x();
                     if (g < ng && gv[s] >= floor_bits) {
                         if (pos < TK_CAND) glist[pos] = (uint32_t)g;
                         ++pos;
@@ -508,7 +509,7 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
                     long long j[NX];
 #pragma unroll
                     for (int s = 0; s < NX; ++s) {
-                        const uint32_t i = i0 + s * TK_THREADS + threadIdx.x;
+                        const uint32_t i = i0 + s * TK_THREADS + tid_x();
                         j[s] = i < items ? (long long)glist[i / QPG] * kGroupKeys + 4 * (i % QPG) : -1;
                         x[s] = j[s] >= 0 ? load4(u, j[s], L, vec_ok) : make_uint4(0, 0, 0, 0);
                     }
@@ -528,7 +529,7 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
                 long long j[TK_SLOTS];
 #pragma unroll
                 for (int s = 0; s < TK_SLOTS; ++s) {
-                    j[s] = base0 + 4ll * (s * TK_THREADS + threadIdx.x);
+                    j[s] = base0 + 4ll * (s * TK_THREADS + tid_x());
                     x[s] = load4(u, j[s], L, vec_ok);
                 }
                 uint32_t cnt = 0;
@@ -551,7 +552,7 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
             // n_cand now counts the winners (index-sort route); every thread read nc before the
             // barriers of the radix steps
             if (!bitmap) {
-                if (threadIdx.x == 0) n_cand = 0;
+                if (tid_x() == 0) n_cand = 0;
                 __syncthreads();
             }
             // who is in by the fp32 ranking (ctake); the candidates within eps of the k-th value are listed
@@ -559,7 +560,7 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
             const float thr_f = __uint_as_float(thr);
             const uint32_t near_lo = __float_as_uint(thr_f * (1.f - rs.eps)), near_hi = __float_as_uint(thr_f * (1.f + rs.eps));
             const bool rescoring = rs.q != nullptr;
-            for (uint32_t i = threadIdx.x; i < nc; i += TK_THREADS) {
+            for (uint32_t i = tid_x(); i < nc; i += TK_THREADS) {
                 const uint32_t v = cval[i], j = cidx[i];
                 bool take = v > thr;
                 if (v == thr) {
@@ -581,9 +582,9 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
             const uint32_t nn = n_near, nin = n_near_in;
             if (rescoring && nn >= 2 && nn <= TK_NEAR_MAX && nin >= 1 && nin < nn) {   // uniform; rare
                 rescore_candidates(rs, h, cidx, near_slot, (int)nn, near_val, rowM, rowL, near_acc, red64);
-                if (threadIdx.x < nn) {                      // rank among the near candidates: value, then smaller position
-                    const uint32_t me = near_slot[threadIdx.x];
-                    const float v = near_val[threadIdx.x];
+                if (tid_x() < nn) {                      // rank among the near candidates: value, then smaller position
+                    const uint32_t me = near_slot[tid_x()];
+                    const float v = near_val[tid_x()];
                     uint32_t rank = 0;
                     for (uint32_t c = 0; c < nn; ++c) {
                         const uint32_t o = near_slot[c];
@@ -593,7 +594,7 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
                 }
                 __syncthreads();
             }
-            for (uint32_t i = threadIdx.x; i < nc; i += TK_THREADS) {
+            for (uint32_t i = tid_x(); i < nc; i += TK_THREADS) {
                 if (ctake[i]) {
                     const uint32_t j = cidx[i];
                     if (bitmap) atomicOr(&bits[j >> 5], 1u << (j & 31));
@@ -606,13 +607,13 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
                 const int wpt = (words + TK_THREADS - 1) / TK_THREADS;      // consecutive words per thread (<= 8)
                 uint32_t mine = 0;
                 for (int i = 0; i < wpt; ++i) {
-                    const int wi = threadIdx.x * wpt + i;
+                    const int wi = tid_x() * wpt + i;
                     if (wi < words) mine += __popc(bits[wi]);
                 }
                 uint32_t total;
                 uint32_t pos = block_scan_incl(mine, tmp, total) - mine;
                 for (int i = 0; i < wpt; ++i) {
-                    const int wi = threadIdx.x * wpt + i;
+                    const int wi = tid_x() * wpt + i;
                     if (wi < words) {
                         uint32_t b = bits[wi];
                         while (b) {
@@ -625,7 +626,7 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
                 }
             } else {
                 bitonic_sort(sidx, P2);
-                for (int i = threadIdx.x; i < k; i += TK_THREADS) out[i] = sidx[i];
+                for (int i = tid_x(); i < k; i += TK_THREADS) out[i] = sidx[i];
             }
             return;
         }
@@ -643,7 +644,7 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
     // ordered sweep: element j goes to slot (#greater before j) + min(#equal before j, want)
     uint32_t base_gt = 0, base_eq = 0;
     for (long long c0 = 0; c0 < L; c0 += (long long)TK_THREADS * TK_EPT) {
-        const long long j0 = c0 + (long long)threadIdx.x * TK_EPT;
+        const long long j0 = c0 + (long long)tid_x() * TK_EPT;
         uint32_t x[TK_EPT];
         uint32_t ngt = 0, neq = 0;
 #pragma unroll

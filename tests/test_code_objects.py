@@ -7,6 +7,10 @@ compiler or flag change could silently break:
 * in the tile kernels every scalar memory load sits in the prologue, before the first LDS fragment
   read: their LDS waits are hand-placed counts, and a scalar load in flight (same counter, out-of-order
   return) would make a count pass early;
+* no kernel calls a device-library function except the few listed (fp64 exp2/log2 on rare paths, the
+  device clock of the stamp kernel): these sources switch a target feature off, LLVM then refuses to
+  inline the library's functions, and blockIdx/threadIdx spelled the HIP way become real calls of
+  hundreds of instructions at the top of every kernel (csrc/ids.hpp has the register reads);
 * a scalar register written by a vector instruction (v_readfirstlane / v_readlane) is not used as the
   base of a vector-memory instruction before five wait states have passed -- the compiler inserts the
   wait states for its own instructions, but cannot for a load written as inline assembly.
@@ -142,6 +146,21 @@ def test_scalar_loads_stay_in_the_prologue_of_the_tile_kernels(objects):
         assert not late, (_demangle(sym), late[:3])
         checked += 1
     assert checked == 15          # 7 attention/statistics + 6 column-sum + 2 batched instantiations
+
+
+def test_no_device_library_calls_except_the_listed_ones(objects):
+    allowed = {"mage::topk_kernel": 2,            # __ocml_exp2_f64 in the fp64 re-score of near-ties (rarely taken)
+               "mage::lse_kernel": 1, "mage::combine_kernel": 1,      # __ocml_log2_f64, once per row at the very end
+               "mage::diag_stamp_kernel": 1}      # the device clock
+    for meta, kernels in objects.values():
+        for sym, ins in kernels.items():
+            name = _demangle(sym)
+            calls = sum(1 for x in ins if x.startswith("s_swappc") or x.startswith("s_setpc"))
+            if sym not in meta:                    # a function that is not a kernel: only the library functions named above
+                assert any(n in sym for n in ("__ocml_exp2_f64", "__ocml_log2_f64", "__ockl_steadyctr_u64")), sym
+                continue
+            limit = max((v for k, v in allowed.items() if name.startswith(k)), default=0)
+            assert calls <= limit, (name, calls)
 
 
 def test_vector_written_scalar_bases_are_five_wait_states_old(objects):
