@@ -42,6 +42,15 @@ constexpr int SP_KT = 16;          // key positions per tile
 constexpr int SP_TPW = 5;          // tiles per wavefront per pass (register arrays)
 constexpr int SP_MAXT = SP_WAVES * SP_TPW;   // tiles per pass: all of LDS holds V (640 key positions at d=128)
 
+// The compiler may not read, copy or move these registers across this point (they are the
+// destinations of loads it does not know about).
+__device__ __forceinline__ void hold_reg(u32x4_t &r) { asm volatile("" : "+v"(r)); }
+template <int N>
+__device__ __forceinline__ void hold_regs(u32x4_t (&r)[N])
+{
+    static_for<N>([&](auto I) { hold_reg(r[decltype(I)::value]); });
+}
+
 // chunk swizzle of a 16-row V tile: rows 0..7 (one half of a transposing read) spread over all banks
 __device__ __forceinline__ int sp_swz(int r) { return ((r & 7) << 1) | (r >> 3); }
 
@@ -100,18 +109,15 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
     const u16 *vb = static_cast<const u16 *>(a.vblk) + h * D + dpart * DV;
     const int32_t *idx = COMPACT ? nullptr : a.idx + (long long)h * a.nc;
 
-    // query fragment: row l16 of this row tile, channels 32*ks + 8*lg4 .. +7.  Branch-free (rows
-    // past R re-read the last row and are never stored): a branch here would end in a wait for
-    // these loads before the index entries are even requested.
-    bf16x8_t qf[KS];
-    const int rq = row < a.R ? row : a.R - 1;
-    const int gl = a.B == 1 ? rq : (int)(((unsigned long long)(unsigned)rq * a.inv_B) >> 32), qi = rq - gl * a.B;
-    const int orow = qi * a.Hq + h * a.G + gl;                  // row of q, out and lse
-    {
-        const u16 *src = static_cast<const u16 *>(a.q) + (long long)orow * D + 8 * lg4;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) qf[ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(src + ks * 32));
-    }
+    // row of q, out and lse that this lane's query row is (rows past R stand in for the last row and are never stored)
+    auto io_row = [&]() {
+        const int rq = row < a.R ? row : a.R - 1;
+        const int gl = a.B == 1 ? rq : (int)(((unsigned long long)(unsigned)rq * a.inv_B) >> 32), qi = rq - gl * a.B;
+        return qi * a.Hq + h * a.G + gl;
+    };
+    // query fragment: row l16 of this row tile, channels 32*ks + 8*lg4 .. +7; requested in the first pass, right
+    // after the index entries
+    u32x4_t qraw[KS];
 
     f32x4_t o[DT];
 #pragma unroll
@@ -155,7 +161,19 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
         // The loads are inline assembly so that the waits can be ours: behind the conditional last
         // slot the compiler's own bookkeeping would wait for every outstanding load, V included.
         u32x4_t kraw[SP_TPW][KS];
-        __builtin_amdgcn_sched_barrier(0);     // every index entry is requested before the first row
+        __builtin_amdgcn_sched_barrier(0);     // every index entry is requested before anything else: the entries head the
+                                               // longest dependent chain of the launch (entry -> row -> scores), and the code
+                                               // in front of them is fetched from a cold instruction cache
+        if (pass == 0) {
+            // The queries: assembly loads like the K rows (the compiler must not count them: its wait for them would
+            // sit in front of the first MFMA and take most of the K and V loads with it).  They are older than every
+            // K row, so they have landed when the first K tile has.
+            const u16 *src = static_cast<const u16 *>(a.q) + (long long)io_row() * D + 8 * lg4;
+            static_for<KS>([&](auto S) {
+                constexpr int ks = decltype(S)::value;
+                qraw[ks] = global_load_b128<ks * 64>(src);
+            });
+        }
         auto load_k = [&](int j) {
             const int e = ek[j];
             const u16 *src = (e >= 0 ? kc + (long long)e * stride : kb + (long long)(-1 - e) * stride) + 8 * (lane & 3);
@@ -200,6 +218,8 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
                 static_for<KS>([&](auto S) {
                     constexpr int ks = decltype(S)::value;
                     vm_wait<younger + (j < SP_TPW - 1 ? KS - 1 - ks : 0)>(kraw[j][ks]);
+                    if constexpr (j == 0 && ks == 0)      // the queries are older than this K piece: landed, and not to be touched before here
+                        hold_regs(qraw);
                     u32x4_t t;
                     t.x = __builtin_amdgcn_ds_bpermute(from, kraw[j][ks].x);
                     t.y = __builtin_amdgcn_ds_bpermute(from, kraw[j][ks].y);
@@ -216,7 +236,8 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
         for (int j = 0; j < SP_TPW; ++j) {
             sc[j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) sc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[j][ks], qf[ks], sc[j], 0, 0, 0);
+            for (int ks = 0; ks < KS; ++ks)
+                sc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[j][ks], __builtin_bit_cast(bf16x8_t, qraw[ks]), sc[j], 0, 0, 0);
             const int p0 = tile_of[j] * SP_KT + 4 * lg4;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
@@ -319,6 +340,7 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
         lt = fmaf(wgt[w], ml[1][w][l16], lt);
     }
     if (row >= a.R) return;
+    const int orow = io_row();
     float *out = a.out;
     const float inv = 1.f / lt;
     for (int dt = wave; dt < DT; dt += SP_WAVES) {
