@@ -102,11 +102,6 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
     const int n_keys = a.nc + a.n_blk;
     const int ntiles = a.ntiles, npass = a.npass, tpp = a.tpp;
 
-    const long long stride = (long long)a.Hkv * D;
-    const u16 *kc = static_cast<const u16 *>(a.kc) + h * D;
-    const u16 *vc = static_cast<const u16 *>(a.vc) + h * D + dpart * DV;
-    const u16 *kb = static_cast<const u16 *>(a.kblk) + h * D;
-    const u16 *vb = static_cast<const u16 *>(a.vblk) + h * D + dpart * DV;
     const int32_t *idx = COMPACT ? nullptr : a.idx + (long long)h * a.nc;
 
     // row of q, out and lse that this lane's query row is (rows past R stand in for the last row and are never stored)
@@ -124,11 +119,14 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
     for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     float m_run = -INFINITY, l_run = 0.f;       // l_run: this lane's share (its 4 keys per tile)
 
-    for (int pass = 0; pass < npass; ++pass) {
+    // One pass over (up to) SP_MAXT tiles.  A function object called for pass 0 on its own: written as the body of a
+    // loop, everything in it that does not depend on the pass would be computed in front of the loop, i.e. in front
+    // of the index requests.
+    auto run_pass = [&](int pass) {
         const int t0 = pass * tpp;
         const int t1 = t0 + tpp < ntiles ? t0 + tpp : ntiles;
         const int first = t0 + wave;                        // this wavefront's tiles: first + 8*j
-        if (first >= t1) continue;                          // nothing for this wavefront in this pass
+        if (first >= t1) return;                            // nothing for this wavefront in this pass
         const int my_tiles = (t1 - first + SP_WAVES - 1) / SP_WAVES;
 
         // ---- issue every load of the pass, branch-free (a branch would make the compiler wait
@@ -164,6 +162,11 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
         __builtin_amdgcn_sched_barrier(0);     // every index entry is requested before anything else: the entries head the
                                                // longest dependent chain of the launch (entry -> row -> scores), and the code
                                                // in front of them is fetched from a cold instruction cache
+        const long long stride = (long long)a.Hkv * D;
+        const u16 *kc = static_cast<const u16 *>(a.kc) + h * D;
+        const u16 *vc = static_cast<const u16 *>(a.vc) + h * D + dpart * DV;
+        const u16 *kb = static_cast<const u16 *>(a.kblk) + h * D;
+        const u16 *vb = static_cast<const u16 *>(a.vblk) + h * D + dpart * DV;
         if (pass == 0) {
             // The queries: assembly loads like the K rows (the compiler must not count them: its wait for them would
             // sit in front of the first MFMA and take most of the K and V loads with it).  They are older than every
@@ -315,7 +318,9 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
         };
         pv(std::integral_constant<int, SP_TPW - 1>{});       // counts without the conditional last slot: never too lax
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // slots past this wavefront's last tile were loaded too
-    }
+    };
+    run_pass(0);
+    for (int pass = 1; pass < npass; ++pass) run_pass(pass);
 
     // ---- merge the eight wavefronts through LDS ----
     float l_w = l_run + __shfl_xor(l_run, 16);
