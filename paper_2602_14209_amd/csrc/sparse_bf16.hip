@@ -45,6 +45,13 @@ constexpr int SP_MAXT = SP_WAVES * SP_TPW;   // tiles per pass: all of LDS holds
 // The compiler may not read, copy or move these registers across this point (they are the
 // destinations of loads it does not know about).
 __device__ __forceinline__ void hold_reg(u32x4_t &r) { asm volatile("" : "+v"(r)); }
+__device__ __forceinline__ void hold_int(int &r) { asm volatile("" : "+v"(r)); }
+__device__ __forceinline__ int global_load_b32(const void *p)      // a load the compiler keeps no books on (see lds_asm.hpp)
+{
+    int r;
+    asm volatile("global_load_dword %0, %1, off" : "=&v"(r) : "v"(p));
+    return r;
+}
 template <int N>
 __device__ __forceinline__ void hold_regs(u32x4_t (&r)[N])
 {
@@ -136,21 +143,26 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
         // -1-r).  Every lane reads the index entries of exactly the rows it will fetch -- row
         // (lane / 4) for its K pieces, rows n*RPL + lane / CH for its V loads -- with all those small
         // loads in flight at once; they hit the same few cache lines.
-        int tile_of[SP_TPW], ek[SP_TPW], ev[SP_TPW][VLOADS];
-        auto src_row = [&](int tile, int r) {
-            int p = tile * SP_KT + r;
-            p = p < n_keys ? p : n_keys - 1;                // padding positions re-read the last key (masked below)
-            const int pc = p < a.nc ? p : a.nc - 1;
-            const int ci = COMPACT ? pc : idx[pc];
-            return p < a.nc ? ci : -1 - (p - a.nc);
+        // The entries are assembly loads too, issued back to back: left to the compiler, each load sinks below the
+        // test "is this position a cache row?" and ends up behind a branch of its own.
+        constexpr bool V_AS_K = RPL == SP_KT && CH == 4;    // a 64-byte V slice is fetched by the lane quad that fetches the K row
+        int tile_of[SP_TPW], ek[SP_TPW], ev[SP_TPW][VLOADS], pk[SP_TPW], posv[SP_TPW][VLOADS];
+        auto key_pos = [&](int tile, int r) {
+            const int p = tile * SP_KT + r;
+            return p < n_keys ? p : n_keys - 1;             // padding positions re-read the last key (masked below)
         };
+        auto request = [&](int p) { return COMPACT ? p : global_load_b32(idx + (p < a.nc ? p : a.nc - 1)); };
+        auto resolve = [&](int p, int entry) { return p < a.nc ? entry : -1 - (p - a.nc); };
 #pragma unroll
         for (int j = 0; j < SP_TPW; ++j) {
             tile_of[j] = first + SP_WAVES * (j < my_tiles ? j : my_tiles - 1);
-            ek[j] = src_row(tile_of[j], lane >> 2);
+            pk[j] = key_pos(tile_of[j], lane >> 2);
+            ek[j] = request(pk[j]);
 #pragma unroll
-            for (int n = 0; n < VLOADS; ++n)                  // a 64-byte V slice is fetched by the lane quad that fetches the K row
-                ev[j][n] = (RPL == SP_KT && CH == 4) ? ek[j] : src_row(tile_of[j], n * RPL + lane / CH);
+            for (int n = 0; n < VLOADS; ++n) {
+                posv[j][n] = key_pos(tile_of[j], n * RPL + lane / CH);
+                ev[j][n] = V_AS_K ? 0 : request(posv[j][n]);
+            }
         }
         // K fragments.  The MFMA wants lane (16*c + r) to hold channels [32*ks + 8*c, +8) of tile row r,
         // but a load in that pattern touches 64 separate 16-byte pieces per instruction.  Load
@@ -162,7 +174,7 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
         __builtin_amdgcn_sched_barrier(0);     // every index entry is requested before anything else: the entries head the
                                                // longest dependent chain of the launch (entry -> row -> scores), and the code
                                                // in front of them is fetched from a cold instruction cache
-        const long long stride = (long long)a.Hkv * D;
+        const unsigned stride_bytes = (unsigned)a.Hkv * (D * 2);       // bytes from a cache row to the next
         const u16 *kc = static_cast<const u16 *>(a.kc) + h * D;
         const u16 *vc = static_cast<const u16 *>(a.vc) + h * D + dpart * DV;
         const u16 *kb = static_cast<const u16 *>(a.kblk) + h * D;
@@ -177,13 +189,31 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
                 qraw[ks] = global_load_b128<ks * 64>(src);
             });
         }
+        // the index entries have landed once nothing but the query loads of the first pass is outstanding
+        if (pass == 0) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(KS) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int j = 0; j < SP_TPW; ++j) {
+            hold_int(ek[j]);
+            ek[j] = resolve(pk[j], ek[j]);
+#pragma unroll
+            for (int n = 0; n < VLOADS; ++n) {
+                if (!V_AS_K) hold_int(ev[j][n]);
+                ev[j][n] = V_AS_K ? ek[j] : resolve(posv[j][n], ev[j][n]);
+            }
+        }
+        // address of a key row: one 32 x 32 -> 64 bit multiply-add (row and row pitch are both below 2^32)
+        auto row_ptr = [&](const u16 *cache, const u16 *blk, int e) {
+            const unsigned r = e >= 0 ? (unsigned)e : (unsigned)(-1 - e);
+            return reinterpret_cast<const unsigned char *>(e >= 0 ? cache : blk) + (unsigned long long)r * stride_bytes;
+        };
         auto load_k = [&](int j) {
-            const int e = ek[j];
-            const u16 *src = (e >= 0 ? kc + (long long)e * stride : kb + (long long)(-1 - e) * stride) + 8 * (lane & 3);
+            const unsigned char *src = row_ptr(kc, kb, ek[j]) + 16 * (lane & 3);
             static_for<KS>([&](auto S) {
                 constexpr int ks = decltype(S)::value;
                 kraw[j][ks] = global_load_b128<ks * 64>(src);
             });
+            __builtin_amdgcn_sched_barrier(0);     // the next tile's address arithmetic stays behind these loads
         };
         auto load_v = [&](int j) {
             unsigned char *dst = vlds + (j * SP_WAVES + wave) * TILE_BYTES;
@@ -191,9 +221,9 @@ __global__ __launch_bounds__(SP_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2
             for (int n = 0; n < VLOADS; ++n) {
                 const int r = n * RPL + lane / CH;                           // tile row this lane fetches
                 const int e = ev[j][n];
-                const u16 *src = e >= 0 ? vc + (long long)e * stride : vb + (long long)(-1 - e) * stride;
+                const unsigned char *src = row_ptr(vc, vb, e);
                 const int chunk = (lane % CH) ^ (sp_swz(r) & (CH - 1));
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + chunk * 8),
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + chunk * 16),
                                                  (__attribute__((address_space(3))) void *)(dst + n * 1024), 16, 0, 0);
             }
         };
@@ -404,7 +434,9 @@ static hipError_t launch_sparse(const SparseArgs &a, bool compact, hipStream_t s
 // every workgroup a compute unit of its own.
 hipError_t bf16_sparse(const KernelArgs &k, int d, bool compact, hipStream_t stream)
 {
-    if (k.nc <= 0 || k.nc > 0x7fffffff - k.n_blk || k.R <= 0 || (long long)k.R * k.B >= (1ll << 32)) return hipErrorInvalidValue;
+    if (k.nc <= 0 || k.nc > 0x7fffffff - k.n_blk || k.R <= 0 || (long long)k.R * k.B >= (1ll << 32) ||
+        (long long)k.Hkv * d * 2 >= (1ll << 31))
+        return hipErrorInvalidValue;
     SparseArgs a{};
     a.q = k.q; a.kc = k.kc; a.vc = k.vc; a.kblk = k.kblk; a.vblk = k.vblk; a.idx = k.idx;
     a.out = k.out; a.lse_out = k.lse_out;
