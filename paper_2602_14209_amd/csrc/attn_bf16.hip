@@ -261,6 +261,12 @@ __device__ __forceinline__ void issue_vt_group(const unsigned (&va)[2], u32x2_t 
     });
 }
 
+// row / B without a division (inv_B comes from the host)
+__device__ __forceinline__ int row_group(const KernelArgs &a, int row)
+{
+    return a.B == 1 ? row : (int)(((unsigned long long)(unsigned)row * a.inv_B) >> 32);
+}
+
 // Query fragment of this lane: row (l % 32) of the wavefront's M tile, 8 consecutive channels
 // per MFMA k-step.  Row r of a KV head's row space is (g_local = r / B, q = r % B).
 template <int D>
@@ -268,7 +274,7 @@ __device__ __forceinline__ void load_q_frag(const KernelArgs &a, const u16 *q, i
 {
     const int lg = (tid_x() & 63) >> 5;
     if (row < a.R) {
-        const int gl = row / a.B, qi = row - gl * a.B;
+        const int gl = row_group(a, row), qi = row - gl * a.B;
         const u16 *src = q + ((long long)qi * a.Hq + (long long)h * a.G + gl) * D + 8 * lg;
 #pragma unroll
         for (int ks = 0; ks < D / 16; ++ks) qf[ks] = as_bf16x8(*reinterpret_cast<const uint4 *>(src + ks * 16));
@@ -295,11 +301,11 @@ struct SplitRange {
 __device__ __forceinline__ SplitRange split_range(const KernelArgs &a, int s)
 {
     SplitRange r;
-    const long long total = (a.nc + kBf16Tile - 1) / kBf16Tile;
     r.first = (long long)s * kBf16Tile;
     r.step = (long long)a.n_cyc * kBf16Tile;
     r.nc = a.nc;
-    r.cache_tiles = __builtin_amdgcn_readfirstlane((s < a.n_cyc && total > s) ? (int)((total - s + a.n_cyc - 1) / a.n_cyc) : 0);
+    // tiles s, s + n_cyc, ... below tiles_q * n_cyc + tiles_r: one more for the first tiles_r splits
+    r.cache_tiles = __builtin_amdgcn_readfirstlane(s < a.n_cyc ? a.tiles_q + (s < a.tiles_r ? 1 : 0) : 0);
     r.blk_tiles = __builtin_amdgcn_readfirstlane((s == a.blk_split) ? (a.n_blk + kBf16Tile - 1) / kBf16Tile : 0);
     return r;
 }
@@ -687,7 +693,7 @@ void attn_bf16_kernel(const KernelArgs a)
         if (row >= a.R) return;
         float *dst;
         if (direct) {
-            const int gl = row / a.B, qi = row - gl * a.B;
+            const int gl = row_group(a, row), qi = row - gl * a.B;
             dst = a.out + ((long long)qi * a.Hq + (long long)h * a.G + gl) * D;
         } else {
             dst = a.part_o + (((long long)h * a.n_split + split) * a.rpad + row) * D;
@@ -707,7 +713,7 @@ void attn_bf16_kernel(const KernelArgs a)
     if (!owner || row >= a.R || lg != 0) return;
     if (direct) {
         if (a.lse_out) {
-            const int gl = row / a.B, qi = row - gl * a.B;
+            const int gl = row_group(a, row), qi = row - gl * a.B;
             a.lse_out[(long long)qi * a.Hq + (long long)h * a.G + gl] = (m_run + log2f(l_tot)) * 0.6931471805599453f;
         }
     } else {
@@ -903,17 +909,33 @@ void colsum_bf16_kernel(const KernelArgs a)
 }
 
 // ------------------------------------------------------------------------------ launchers
-template <int D, int MODE, bool AHEAD>
-static hipError_t launch_attn(const KernelArgs &a, int row_groups, int grid_x, hipStream_t stream)
+// the division results the kernels would otherwise start with
+static KernelArgs fill_split_consts(const KernelArgs &k)
 {
+    KernelArgs a = k;
+    const long long tiles = (a.nc + kBf16Tile - 1) / kBf16Tile;
+    const int n = a.n_cyc > 0 ? a.n_cyc : 1;
+    a.tiles_q = (int)(tiles / n);
+    a.tiles_r = (int)(tiles % n);
+    a.inv_B = a.B >= 2 ? (unsigned)(((1ull << 32) + a.B - 1) / a.B) : 0u;
+    return a;
+}
+
+template <int D, int MODE, bool AHEAD>
+static hipError_t launch_attn(const KernelArgs &k, int row_groups, int grid_x, hipStream_t stream)
+{
+    if ((long long)k.R * k.B >= (1ll << 32)) return hipErrorInvalidValue;      // row_group's precondition
+    const KernelArgs a = fill_split_consts(k);
     dim3 grid(grid_x, a.Hkv, row_groups), block(kAttnWaves * 64);
     hipLaunchKernelGGL((attn_bf16_kernel<D, MODE, AHEAD>), grid, block, 0, stream, a);
     return hipGetLastError();
 }
 
 template <int D, int NW>
-static hipError_t launch_colsum(const KernelArgs &a, hipStream_t stream)
+static hipError_t launch_colsum(const KernelArgs &k, hipStream_t stream)
 {
+    if ((long long)k.R * k.B >= (1ll << 32)) return hipErrorInvalidValue;      // row_group's precondition
+    const KernelArgs a = fill_split_consts(k);
     dim3 grid(a.n_split, a.head_rows > 0 ? a.Hq : a.Hkv), block(NW * 64);
     hipLaunchKernelGGL((colsum_bf16_kernel<D, NW>), grid, block, 0, stream, a);
     return hipGetLastError();

@@ -183,6 +183,9 @@ struct KernelArgs {
     long long seq_q, seq_kv, seq_idx, seq_blk, seq_out, seq_lse;
     float scale_log2;        // log2(e) / sqrt(d)
     float inv_rows;          // 1 / (G*B)
+    // worked out on the host so that the bf16 kernels start without a division (fill_split_consts):
+    int tiles_q, tiles_r;    // ceil(nc / 64) cache tiles = tiles_q * n_cyc + tiles_r
+    unsigned inv_B;          // ceil(2^32 / B) for B >= 2: row / B == (row * inv_B) >> 32 while row * B < 2^32
 };
 
 // What the top-k kernel needs to re-score the few candidates whose fp32 alpha lies within `eps`
