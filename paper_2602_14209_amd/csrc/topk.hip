@@ -116,11 +116,21 @@ __device__ __forceinline__ void radix_hist_mem(const uint32_t *u, long long n, i
 }
 
 // the same over TK_SLOTS elements per thread that already sit in registers
+// `live` slots only: the slots past the end of a short row hold zeros, and thousands of them would all
+// be added, one after the other, to the single bin of the value zero; padding(...) accounts for them with
+// one addition.
 template <int BITS>
-__device__ __forceinline__ void radix_hist_regs(const uint32_t (&x)[TK_SLOTS], int shift, uint32_t prefix, uint32_t *hist)
+__device__ __forceinline__ void radix_hist_regs(const uint32_t (&x)[TK_SLOTS], int live, int shift, uint32_t prefix, uint32_t *hist)
 {
 #pragma unroll
-    for (int i = 0; i < TK_SLOTS; ++i) radix_count<BITS>(x[i], true, shift, prefix, hist);
+    for (int i = 0; i < TK_SLOTS; ++i) radix_count<BITS>(x[i], i < live, shift, prefix, hist);
+}
+
+// n_pad elements of value zero, counted by one thread (they match a prefix of zero only)
+template <int BITS>
+__device__ __forceinline__ void radix_hist_padding(uint32_t n_pad, uint32_t prefix, uint32_t *hist)
+{
+    if (tid_x() == 0 && n_pad != 0 && prefix == 0) atomicAdd(&hist[(1 << BITS) - 1], n_pad);
 }
 
 template <int BITS>
@@ -435,11 +445,24 @@ __global__ __launch_bounds__(TK_THREADS) void topk_kernel(const float *alpha, co
         // a lower bound of the k-th largest group maximum (its top 20 bits), hence of the k-th
         // largest element: at least k elements are >= floor_bits
         uint32_t floor_bits = 0, rank = (uint32_t)k, bucket;
-        if (in_regs) radix_hist_regs<12>(gv, 20, floor_bits, hists + H_G1);
-        else radix_hist_mem<12>(gg, ng, 20, floor_bits, hists + H_G1);
+        // slots of this thread that hold a group (group = slot * 1024 + thread); the zeros behind the end of a
+        // short row take part in the ranking as one bulk count
+        const long long mine = ng > tid_x() ? (ng - tid_x() + TK_THREADS - 1) / TK_THREADS : 0;
+        const int live = (group_max != nullptr && in_regs) ? (int)(mine < TK_SLOTS ? mine : TK_SLOTS) : TK_SLOTS;
+        const uint32_t n_pad = (group_max != nullptr && in_regs) ? (uint32_t)(TK_GROUPS - ng) : 0u;
+        if (in_regs) {
+            radix_hist_regs<12>(gv, live, 20, floor_bits, hists + H_G1);
+            radix_hist_padding<12>(n_pad, floor_bits, hists + H_G1);
+        } else {
+            radix_hist_mem<12>(gg, ng, 20, floor_bits, hists + H_G1);
+        }
         radix_pick<12>(20, floor_bits, rank, bucket, hists + H_G1, lscan, tmp);
-        if (in_regs) radix_hist_regs<8>(gv, 12, floor_bits, hists + H_G2);
-        else radix_hist_mem<8>(gg, ng, 12, floor_bits, hists + H_G2);
+        if (in_regs) {
+            radix_hist_regs<8>(gv, live, 12, floor_bits, hists + H_G2);
+            radix_hist_padding<8>(n_pad, floor_bits, hists + H_G2);
+        } else {
+            radix_hist_mem<8>(gg, ng, 12, floor_bits, hists + H_G2);
+        }
         radix_pick<8>(12, floor_bits, rank, bucket, hists + H_G2, lscan, tmp2);
 
         // appends this thread's `cnt` keepers among x[0..NX) (positions j[i] .. j[i]+3) to the candidates
