@@ -3,9 +3,10 @@
 //
 // The step moves a few MB, so it is bound by dependent-load latency and by how many compute
 // units take part, not by bandwidth.  Layout of the work, chosen for that:
-//   - one workgroup per (KV head, 16 query rows); its 8 wavefronts split the KEYS (tiles of 16
-//     key positions, round-robin), so no partial result ever leaves the compute unit: the eight
-//     partial (max, sum, O) are merged through LDS and every output row is written once;
+//   - one workgroup per (KV head, 16 query rows, slice of the output channels); its 8 wavefronts
+//     split the KEYS (tiles of 16 key positions, round-robin), so no partial result ever leaves
+//     the compute unit: the eight partial (max, sum, O) are merged through LDS and every output
+//     element is written once;
 //   - every load of a pass is in flight at once: the index entries, then K rows into registers
 //     (coalesced 64-byte pieces, moved to their MFMA operand lanes by a lane permute) and V rows
 //     straight into LDS (global_load_lds), from where transposing reads (ds_read_b64_tr_b16)
@@ -16,6 +17,12 @@
 //     tile, each computes the full scores (the softmax statistics are simply computed four times)
 //     but fetches and multiplies only its quarter of every V row.  Measured at Hkv = 8, k = 512:
 //     9.5 us with one workgroup per row tile, 8.4 with two, 7.8 with four;
+//   - the instruction cache is cold at the start of every launch (straight-line code runs at
+//     about 13 cycles per instruction the first time, 3 the second), and nearly all of this kernel
+//     runs once.  What sits in front of a load on the chain index entry -> row -> scores is
+//     therefore kept short: divisions are done on the host, the index entries are requested
+//     before anything else, then the queries, then the address arithmetic that does not depend
+//     on them; the first pass over the keys is not the body of a loop (see run_pass);
 //   - workgroups of one KV head sit on the same XCD when Hkv is a multiple of 8 (linear
 //     workgroup id = head + Hkv * (row tile, channel part)), so a gathered row is fetched from HBM
 //     once and shared through that XCD's L2.
