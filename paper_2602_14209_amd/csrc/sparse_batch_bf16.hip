@@ -18,11 +18,12 @@
 //     right before its row is requested would sit behind every tile load in flight (loads retire in
 //     order), i.e. drain the ring at every tile;
 //   - with so little matrix work per tile (16 MFMAs per wavefront) the tile loop is bound by the number
-//     of vector-ALU instructions issued around them, so those are kept few: the ring is walked by an
-//     unrolled loop, which makes every LDS fragment address a lane constant plus an immediate, and what
-//     depends on the wavefront number alone stays in scalar registers.  What then bounds a workgroup that
-//     has its CU to itself is the LDS: every wavefront reads the whole K and V tile (128 KB per tile and
-//     workgroup).
+//     of vector-ALU instructions issued around them, so those are kept few: every LDS fragment address
+//     is a lane constant plus the ring slot's offset, and what depends on the wavefront number alone
+//     stays in scalar registers.  (Unrolling the tile loop over the ring turns the slot into an
+//     immediate, twelve additions less per tile, and doubles the code: measured the same, 40.3 us at 64
+//     sequences either way, so the loop is rolled.)  What then bounds a workgroup that has its CU to
+//     itself is the LDS: every wavefront reads the whole K and V tile (128 KB per tile and workgroup).
 // Scores are produced transposed (S^T = K Q^T: a lane holds 4 keys of ONE query row per 16-key block),
 // so the probabilities are already the B operand of O^T = V^T P^T; V^T fragments come from transposing
 // LDS reads of the row-major tile.
@@ -64,7 +65,6 @@ void sparse_batch_kernel(const KernelArgs a, int n_units, int row_groups)
     constexpr int BUF_BYTES = 2 * MAT_BYTES;             // K tile, then V tile
     static_assert(UPW >= 1 && UPW * NW == 2 * MAT_UNITS, "a tile is a whole number of loads per wavefront");
     static_assert((NBUF - 2) * UPW < 64, "outstanding loads must fit the counter");
-    static_assert((NBUF - 1) * BUF_BYTES + MAT_BYTES + 16 * ROW_BYTES < 65536, "fragment reads address the ring through 16-bit immediates");
     __shared__ __attribute__((aligned(1024))) unsigned char smem[NBUF * BUF_BYTES];
     __shared__ int32_t idx_lds[SB_IDX_TILES * TK];
 
@@ -144,9 +144,8 @@ void sparse_batch_kernel(const KernelArgs a, int n_units, int row_groups)
             ent[n] = lds_read_f32<0>(idx_addr + (unsigned)p * 4);
         }
     };
-    auto issue = [&](int t, auto SLOT) {
-        constexpr int slot = decltype(SLOT)::value;
-        const unsigned dst = lds_wave + slot * BUF_BYTES;
+    auto issue = [&](int t) {
+        const unsigned dst = lds_wave + (unsigned)(t % NBUF) * BUF_BYTES;
         static_for<UPW>([&](auto NI) {
             constexpr int n = decltype(NI)::value;
             lds_wait<UPW - 1 - n>(ent[n]);
@@ -175,14 +174,14 @@ void sparse_batch_kernel(const KernelArgs a, int n_units, int row_groups)
         constexpr int j = decltype(J)::value;
         if (j < ntiles) {
             request_entries(j);
-            issue(j, J);
+            issue(j);
         }
     });
     request_entries(NBUF - 1);
 
     // Fragment read addresses.  The swizzle, the MFMA k-step (K) and the O^T tile (V) all act on address
-    // bits 4..7 only, so each read's address is a lane constant; ring slot, matrix and 16-key block are
-    // immediate offsets (the tile loop is unrolled over the ring).
+    // bits 4..7 only, so each read's address is a lane constant plus the ring slot's offset (one
+    // addition per read); the 16-key block is an immediate offset.
     const unsigned smem_addr = lds_addr(smem);
     // K fragment (A operand): key row l16 of a block, channels 32*ks + 8*lg4 .. +7 = chunk 4*ks + lg4
     unsigned kaddr[KS];
@@ -209,10 +208,12 @@ void sparse_batch_kernel(const KernelArgs a, int n_units, int row_groups)
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) asm volatile("" ::"v"(qf[ks]));
 
-    // one tile: SLOT = t % NBUF, known at compile time
-    auto step = [&](int t, auto SLOT) {
-        constexpr int slot = decltype(SLOT)::value;
-        constexpr int KOFF = slot * BUF_BYTES, VOFF = slot * BUF_BYTES + MAT_BYTES, BLK = 16 * ROW_BYTES;
+    // one tile, in ring slot t % NBUF.  The loop over the tiles is NOT unrolled over the ring: the slot is
+    // one scalar addition per fragment address, while an unrolled body is four times the instructions
+    // to fetch into an instruction cache that starts cold at every launch.
+    auto step = [&](int t) {
+        constexpr int BLK = 16 * ROW_BYTES;
+        const unsigned koff = (unsigned)(t % NBUF) * BUF_BYTES, voff = koff + MAT_BYTES;
         // tile t has landed; NBUF-2 younger tiles may still be in flight; everyone is done with tile t-1
         if (t + NBUF - 2 < ntiles) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((NBUF - 2) * UPW) : "memory");
         else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
@@ -225,7 +226,7 @@ void sparse_batch_kernel(const KernelArgs a, int n_units, int row_groups)
                 __syncthreads();
                 request_entries(tn);
             }
-            issue(tn, std::integral_constant<int, (slot + NBUF - 1) % NBUF>{});
+            issue(tn);
             request_entries(tn + 1);                      // lands while this tile is computed; waited for at the next barrier
         }
         if (!wave_active) return;
@@ -240,8 +241,8 @@ void sparse_batch_kernel(const KernelArgs a, int n_units, int row_groups)
             u32x4_t kf[KB][2];
             static_for<KB>([&](auto S) {
                 constexpr int i = decltype(S)::value;
-                kf[i][0] = lds_read_b128<KOFF>(kaddr[k0 + i]);
-                kf[i][1] = lds_read_b128<KOFF + BLK>(kaddr[k0 + i]);
+                kf[i][0] = lds_read_b128<0>(kaddr[k0 + i] + koff);
+                kf[i][1] = lds_read_b128<BLK>(kaddr[k0 + i] + koff);
             });
             static_for<KB>([&](auto S) {
                 constexpr int i = decltype(S)::value;
@@ -257,8 +258,8 @@ void sparse_batch_kernel(const KernelArgs a, int n_units, int row_groups)
         u32x2_t lo[DT], hi[DT];
         static_for<kPre>([&](auto T) {
             constexpr int dt = decltype(T)::value;
-            lo[dt] = lds_read_tr16_b64<VOFF>(vaddr[dt]);
-            hi[dt] = lds_read_tr16_b64<VOFF + BLK>(vaddr[dt]);
+            lo[dt] = lds_read_tr16_b64<0>(vaddr[dt] + voff);
+            hi[dt] = lds_read_tr16_b64<BLK>(vaddr[dt] + voff);
         });
         if (valid < TK) {
 #pragma unroll
@@ -303,17 +304,13 @@ void sparse_batch_kernel(const KernelArgs a, int n_units, int row_groups)
             const u32x4_t both = {lo[dt][0], lo[dt][1], hi[dt][0], hi[dt][1]};
             o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, both), pf, o[dt], 0, 0, 0);
             if constexpr (dt + kPre < DT) {
-                lo[dt + kPre] = lds_read_tr16_b64<VOFF>(vaddr[dt + kPre]);
-                hi[dt + kPre] = lds_read_tr16_b64<VOFF + BLK>(vaddr[dt + kPre]);
+                lo[dt + kPre] = lds_read_tr16_b64<0>(vaddr[dt + kPre] + voff);
+                hi[dt + kPre] = lds_read_tr16_b64<BLK>(vaddr[dt + kPre] + voff);
             }
         });
     };
-    for (int t0 = 0; t0 < ntiles; t0 += NBUF) {
-        static_for<NBUF>([&](auto J) {
-            constexpr int j = decltype(J)::value;
-            if (t0 + j < ntiles) step(t0 + j, J);         // uniform
-        });
-    }
+#pragma clang loop unroll(disable)
+    for (int t = 0; t < ntiles; ++t) step(t);
 
     if (!wave_active) return;
     float l_tot = l_run + __shfl_xor(l_run, 16);
