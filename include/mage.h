@@ -22,8 +22,9 @@
  *     `out`, `lse_out`, `alpha_out` are fp32; indices are int32.
  *   - T is not an argument: the caller invokes mage_sparse_attn once per denoising step
  *     2..T with the index set that mage_select produced at step 1 (Alg. 1, Phase 2).
- *   - Supported: d in {64, 128}; Hq % Hkv == 0; 1 <= k <= L <= 2^30; B*G <= 256 for
- *     mage_select and mage_step1 with MAGE_BF16; mage_sparse_attn_batched with MAGE_BF16 only.
+ *   - Supported: d in {64, 128}; Hq % Hkv == 0; 1 <= k <= L <= 2^30; B*G <= 2^20, B*B*G < 2^32 and
+ *     Hkv*d < 2^29 (the kernels' 32-bit row arithmetic); B*G <= 256 for mage_select and mage_step1
+ *     with MAGE_BF16; mage_sparse_attn_batched with MAGE_BF16 only.
  */
 #ifndef MAGE_H
 #define MAGE_H
@@ -41,7 +42,7 @@ typedef enum {
     MAGE_OK = 0,
     MAGE_ERR_NULL = -1,        /* a required pointer is NULL */
     MAGE_ERR_SHAPE = -2,       /* B, Hq, Hkv, d, L or k <= 0; Hq % Hkv != 0; k > L */
-    MAGE_ERR_UNSUPPORTED = -3, /* d not in {64,128}; unknown dtype; L > 2^30; B*G too large */
+    MAGE_ERR_UNSUPPORTED = -3, /* d not in {64,128}; unknown dtype; L > 2^30; B, G or Hkv beyond the stated ranges */
     MAGE_ERR_WORKSPACE = -4,   /* workspace NULL or smaller than mage_workspace_bytes() */
     MAGE_ERR_HIP = -5,         /* a kernel launch reported an error */
     MAGE_ERR_ALIGN = -6,       /* a data pointer is not 16-byte aligned */

@@ -72,7 +72,10 @@ int check_shape(const mage_shape *s, bool need_k)
     if (s->d != 64 && s->d != 128) return MAGE_ERR_UNSUPPORTED;
     if (s->dtype != MAGE_F32 && s->dtype != MAGE_BF16) return MAGE_ERR_UNSUPPORTED;
     if (s->L > kMaxL) return MAGE_ERR_UNSUPPORTED;
-    if ((int64_t)(s->Hq / s->Hkv) * s->B > (1 << 20)) return MAGE_ERR_UNSUPPORTED;
+    const int64_t rows = (int64_t)(s->Hq / s->Hkv) * s->B;      // query rows that share a KV head
+    if (rows > (1 << 20)) return MAGE_ERR_UNSUPPORTED;
+    // what the kernels' 32-bit arithmetic assumes: row / B by a multiply-high, row strides in bytes
+    if (rows * s->B >= ((int64_t)1 << 32) || (int64_t)s->Hkv * s->d * 4 >= ((int64_t)1 << 31)) return MAGE_ERR_UNSUPPORTED;
     return MAGE_OK;
 }
 
@@ -292,7 +295,7 @@ const char *mage_status_string(int status)
     case MAGE_OK: return "ok";
     case MAGE_ERR_NULL: return "a required pointer is NULL";
     case MAGE_ERR_SHAPE: return "invalid shape (non-positive size, Hq % Hkv != 0, or k > L)";
-    case MAGE_ERR_UNSUPPORTED: return "unsupported configuration (d not in {64,128}, unknown dtype, L > 2^30, or B*G too large)";
+    case MAGE_ERR_UNSUPPORTED: return "unsupported configuration (d not in {64,128}, unknown dtype, L > 2^30, or B, G or Hkv beyond the kernels' 32-bit ranges)";
     case MAGE_ERR_WORKSPACE: return "workspace missing or smaller than mage_workspace_bytes()";
     case MAGE_ERR_HIP: return "HIP reported a launch error";
     case MAGE_ERR_ALIGN: return "a data pointer is not 16-byte aligned";

@@ -48,6 +48,9 @@ def test_workspace_bytes():
     (dict(Hq=30), -2),              # Hq % Hkv != 0
     (dict(k=5000, L=4096), -2),     # k > L
     (dict(d=96), -3), (dict(dtype=7), -3), (dict(L=(1 << 30) + 1), -3),
+    (dict(B=1 << 18, Hq=64), -3),                       # B*G > 2^20
+    (dict(B=70000, Hq=8), -3),                          # B*G fits, B*B*G >= 2^32
+    (dict(Hq=1 << 23, Hkv=1 << 23, d=64), -3),          # Hkv*d >= 2^29
 ])
 def test_argument_validation_happens_before_any_launch(kw, code):
     base = dict(B=32, Hq=32, Hkv=8, d=128, L=4096, k=512, dtype=1)
