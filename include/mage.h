@@ -185,7 +185,8 @@ int mage_sparse_attn_compact(const mage_shape *shape, const void *q, const void 
  * every array gains a leading sequence axis -- q, out [n_seq,B,Hq,d]; k_cache, v_cache
  * [n_seq,L,Hkv,d]; idx [n_seq,Hkv,k]; k_blk, v_blk [n_seq,B,Hkv,d]; lse_out [n_seq,B,Hq].
  * The launch then carries enough independent work to be bound by HBM bandwidth rather than by
- * the latency of one small gather.  MAGE_BF16 only (MAGE_ERR_UNSUPPORTED otherwise).
+ * the latency of one small gather.  1 <= n_seq <= 65535 (MAGE_ERR_SHAPE otherwise); MAGE_BF16 only and
+ * (n_seq*Hkv + 8)*Hkv < 2^32 (MAGE_ERR_UNSUPPORTED otherwise).
  */
 int mage_sparse_attn_batched(const mage_shape *shape, int n_seq, const void *q, const void *k_cache,
                              const void *v_cache, const int32_t *idx, const void *k_blk, const void *v_blk,

@@ -506,6 +506,8 @@ int mage_sparse_attn_batched(const mage_shape *shape, int n_seq, const void *q, 
     if (rc != MAGE_OK) return rc;
     if (n_seq <= 0 || n_seq > 65535) return MAGE_ERR_SHAPE;
     if (shape->dtype != MAGE_BF16) return MAGE_ERR_UNSUPPORTED;
+    // (sequence, head) = unit / Hkv by a multiply-high in the kernel
+    if (((int64_t)n_seq * shape->Hkv + 8) * shape->Hkv >= ((int64_t)1 << 32)) return MAGE_ERR_UNSUPPORTED;
     return run_sparse_bf16(shape, false, n_seq, q, k_cache, v_cache, idx, k_blk, v_blk, out, lse_out, hip_stream);
 }
 

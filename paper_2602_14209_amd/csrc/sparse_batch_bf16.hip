@@ -46,13 +46,31 @@ constexpr int SB_TK = 32;                    // keys per tile (two 16-key MFMA b
 constexpr int SB_NBUF = 4;                   // ring slots
 constexpr int SB_IDX_TILES = 64;             // tiles whose index entries LDS holds at a time (2048 entries)
 
+// What the kernel needs of a call, packed: the kernel arguments arrive through scalar loads that the very
+// first instructions wait for, so they are few and adjacent, and what the host can work out is worked out
+// there (the divisions by Hkv and B become a multiply-high).
+struct BatchArgs {
+    const void *q, *kc, *vc, *kblk, *vblk;
+    const int32_t *idx;
+    float *out, *lse_out;
+    long long seq_q, seq_kv, seq_idx, seq_blk, seq_out, seq_lse;   // element strides between sequences
+    int B, Hq, Hkv, G, R;
+    int nk, n_blk;               // selected cache rows, the block's own rows (0 = none)
+    int n_units;                 // n_seq * Hkv
+    unsigned inv_Hkv;            // ceil(2^32 / Hkv) for Hkv >= 2: unit / Hkv == mulhi(unit, inv_Hkv) while unit * Hkv < 2^32
+    unsigned inv_B;              // the same for B (row * B < 2^32)
+    float scale_log2;
+};
+
+constexpr int SB_GRID_Y = 32768;            // workgroup id: x = place inside a block of ids, (z, y) = block (y < SB_GRID_Y)
+
 // XOR swizzle of the 16-byte chunk index of tile row r (taken modulo 16): the 16 rows of a K fragment
 // read and the 8 rows of one phase of a transposing V read land on distinct LDS banks.
 __device__ __forceinline__ int sb_swz(int r) { return ((r & 7) << 1) | ((r >> 3) & 1); }
 
 template <int D>
 __global__ __launch_bounds__(SB_WAVES * 64) __attribute__((amdgpu_waves_per_eu(4, 4)))
-void sparse_batch_kernel(const KernelArgs a, int n_units, int row_groups)
+void sparse_batch_kernel(const BatchArgs a)
 {
     constexpr int NW = SB_WAVES, TK = SB_TK, NBUF = SB_NBUF;
     constexpr int KS = D / 32;                           // MFMA k-steps of the score product
@@ -68,21 +86,22 @@ void sparse_batch_kernel(const KernelArgs a, int n_units, int row_groups)
     __shared__ __attribute__((aligned(1024))) unsigned char smem[NBUF * BUF_BYTES];
     __shared__ int32_t idx_lds[SB_IDX_TILES * TK];
 
-    // Workgroup id -> (unit, row group): blocks of 8 * row_groups consecutive ids hold 8 units; the
-    // row groups of a unit are 8 ids apart, i.e. on the same XCD (ids are dealt round-robin to the 8
-    // XCDs) and close in time, so the second reader of a selected row finds it in that XCD's L2.
-    const int blk = wg_x() / (8 * row_groups), within = wg_x() % (8 * row_groups);
+    // Workgroup id -> (unit, row group): a block of 8 * row_groups consecutive ids (the x dimension) holds 8
+    // units; the row groups of a unit are 8 ids apart, i.e. on the same XCD (ids are dealt round-robin to
+    // the 8 XCDs) and close in time, so the second reader of a selected row finds it in that XCD's L2.
+    const int blk = wg_z() * SB_GRID_Y + wg_y(), within = wg_x();
     const int unit = blk * 8 + (within & 7), rg = within >> 3;
-    if (unit >= n_units) return;                         // uniform: ids past the last unit of a ragged block
-    const long long z = unit / a.Hkv;
-    const int h = unit % a.Hkv;
+    if (unit >= a.n_units) return;                       // uniform: ids past the last unit of a ragged block
+    const int zi = a.Hkv == 1 ? unit : (int)(((unsigned long long)(unsigned)unit * a.inv_Hkv) >> 32);
+    const int h = unit - zi * a.Hkv;
+    const long long z = zi;
     const int lane = tid_x() & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid_x() >> 6);   // scalar: what depends on it alone stays in scalar registers
     const int l16 = lane & 15, lg4 = lane >> 4;
     const int row0 = rg * SB_ROWS + wave * 16, row = row0 + l16;
     const bool wave_active = row0 < a.R;
 
-    const int nk = (int)a.nc;                             // selected cache rows
+    const int nk = a.nk;                                  // selected cache rows
     const int n_keys = nk + a.n_blk;
     const int ntiles = __builtin_amdgcn_readfirstlane((n_keys + TK - 1) / TK);
     const long long stride = (long long)a.Hkv * D;
@@ -95,17 +114,23 @@ void sparse_batch_kernel(const KernelArgs a, int n_units, int row_groups)
     // index entries of the selected rows at key positions [t0*TK, (t0 + SB_IDX_TILES)*TK) into LDS: at
     // most four per thread, all requested before the first is stored
     int idx_t0 = 0;
-    auto load_idx = [&](int t0) {
-        constexpr int PER = SB_IDX_TILES * TK / (NW * 64);
+    constexpr int PER = SB_IDX_TILES * TK / (NW * 64);
+    auto fetch_idx = [&](int t0, int (&e)[PER]) {
         const int first = t0 * TK;
-        int e[PER];
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
             const int p = first + i * NW * 64 + (int)tid_x();
             e[i] = p < nk ? idx[p] : 0;
         }
+    };
+    auto store_idx = [&](const int (&e)[PER]) {
 #pragma unroll
         for (int i = 0; i < PER; ++i) idx_lds[i * NW * 64 + tid_x()] = e[i];
+    };
+    auto load_idx = [&](int t0) {
+        int e[PER];
+        fetch_idx(t0, e);
+        store_idx(e);
     };
     const unsigned idx_addr = lds_addr(idx_lds);
     // This wavefront's share of a tile: load unit u = n*NW + wave of the 2*MAT_UNITS units (K matrix,
@@ -125,12 +150,11 @@ void sparse_batch_kernel(const KernelArgs a, int n_units, int row_groups)
     }
     const unsigned lds_wave = __builtin_amdgcn_readfirstlane(lds_addr(smem) + wave * 1024);
     const unsigned stride_bytes = (unsigned)stride * 2u;
-    auto all_cache = [&](int t) { return (t + 1) * TK <= nk; };   // tile t lies wholly in the selected cache rows
     // The index entries of a tile's rows are read from LDS one tile ahead of the request (request_entries:
     // no wait), so that a tile's requests go out right after the barrier that frees its buffer.
     float ent[UPW];
     auto request_entries = [&](int t) {
-        if (all_cache(t) && t >= idx_t0 && t < idx_t0 + SB_IDX_TILES) {      // uniform; the common case: no clamping
+        if ((t + 1) * TK <= nk && t >= idx_t0 && t < idx_t0 + SB_IDX_TILES) {   // uniform; the common case: a tile of selected rows, no clamping
             const unsigned base = idx_addr + (unsigned)((t - idx_t0) * TK) * 4;
 #pragma unroll
             for (int n = 0; n < UPW; ++n) ent[n] = lds_read_f32<0>(base + (unsigned)unit_row[n] * 4);
@@ -159,24 +183,25 @@ void sparse_batch_kernel(const KernelArgs a, int n_units, int row_groups)
         });
     };
 
-    load_idx(0);
+    // the index entries are requested first: everything else on the way to the first tile waits for them
+    int e0[PER];
+    fetch_idx(0, e0);
     // query fragment (B operand): row l16 of this wavefront's 16 rows, channels 32*ks + 8*lg4 .. +7
     bf16x8_t qf[KS];
     {
         const int rq = row < a.R ? row : a.R - 1;         // rows past R re-read the last row and are never stored
-        const int gl = rq / a.B, qi = rq - gl * a.B;
+        const int gl = a.B == 1 ? rq : (int)(((unsigned long long)(unsigned)rq * a.inv_B) >> 32), qi = rq - gl * a.B;
         const u16 *src = static_cast<const u16 *>(a.q) + z * a.seq_q + ((long long)qi * a.Hq + (long long)h * a.G + gl) * D + 8 * lg4;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) qf[ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(src + ks * 32));
     }
+    store_idx(e0);
     __syncthreads();
-    static_for<NBUF - 1>([&](auto J) {
-        constexpr int j = decltype(J)::value;
-        if (j < ntiles) {
-            request_entries(j);
-            issue(j);
-        }
-    });
+#pragma clang loop unroll(disable)
+    for (int j = 0; j < NBUF - 1 && j < ntiles; ++j) {
+        request_entries(j);
+        issue(j);
+    }
     request_entries(NBUF - 1);
 
     // Fragment read addresses.  The swizzle, the MFMA k-step (K) and the O^T tile (V) all act on address
@@ -220,7 +245,7 @@ void sparse_batch_kernel(const KernelArgs a, int n_units, int row_groups)
         __syncthreads();
         const int tn = t + NBUF - 1;                      // goes into the slot tile t-1 has just left
         if (tn < ntiles) {
-            if ((tn + 1) * TK > (idx_t0 + SB_IDX_TILES) * TK && tn * TK < nk) {   // uniform; rare (k > 2048)
+            if (tn + 1 > idx_t0 + SB_IDX_TILES && tn * TK < nk) {                 // uniform; rare (k > 2048)
                 idx_t0 = tn;
                 load_idx(tn);
                 __syncthreads();
@@ -317,7 +342,7 @@ void sparse_batch_kernel(const KernelArgs a, int n_units, int row_groups)
     l_tot += __shfl_xor(l_tot, 32);
     if (row >= a.R) return;
     const float inv = 1.f / l_tot;
-    const int gl = row / a.B, qi = row - gl * a.B;
+    const int gl = a.B == 1 ? row : (int)(((unsigned long long)(unsigned)row * a.inv_B) >> 32), qi = row - gl * a.B;
     const long long orow = (long long)qi * a.Hq + (long long)h * a.G + gl;
     float *dst = a.out + z * a.seq_out + orow * D;
     // O^T register (dt, v) holds channel 16*dt + 4*lg4 + v of this lane's query row
@@ -327,13 +352,45 @@ void sparse_batch_kernel(const KernelArgs a, int n_units, int row_groups)
 }
 
 // n_seq independent sequences, one workgroup per (sequence, KV head, 128-row group).
-hipError_t bf16_sparse_batched(const KernelArgs &a, int d, int row_groups, int n_seq, hipStream_t stream)
+hipError_t bf16_sparse_batched(const KernelArgs &k, int d, int row_groups, int n_seq, hipStream_t stream)
 {
-    const int n_units = n_seq * a.Hkv;
-    const int n_wg = (n_units + 7) / 8 * 8 * row_groups;
-    dim3 grid(n_wg), block(SB_WAVES * 64);
-    if (d == 128) hipLaunchKernelGGL((sparse_batch_kernel<128>), grid, block, 0, stream, a, n_units, row_groups);
-    else if (d == 64) hipLaunchKernelGGL((sparse_batch_kernel<64>), grid, block, 0, stream, a, n_units, row_groups);
+    const long long n_units = (long long)n_seq * k.Hkv;
+    const long long n_blocks = (n_units + 7) / 8;
+    // the kernel's 32-bit arithmetic: unit / Hkv and row / B by a multiply-high, ids within the grid's limits
+    if (n_seq <= 0 || row_groups <= 0 || k.nc <= 0 || k.nc > 0x7fffffff - k.n_blk || (n_units + 8) * k.Hkv >= (1ll << 32) ||
+        (long long)k.R * k.B >= (1ll << 32) || n_blocks > (long long)SB_GRID_Y * 65535 || 8ll * row_groups > 0x7fffffff)
+        return hipErrorInvalidValue;
+    BatchArgs a{};
+    a.q = k.q;
+    a.kc = k.kc;
+    a.vc = k.vc;
+    a.kblk = k.kblk;
+    a.vblk = k.vblk;
+    a.idx = k.idx;
+    a.out = k.out;
+    a.lse_out = k.lse_out;
+    a.seq_q = k.seq_q;
+    a.seq_kv = k.seq_kv;
+    a.seq_idx = k.seq_idx;
+    a.seq_blk = k.seq_blk;
+    a.seq_out = k.seq_out;
+    a.seq_lse = k.seq_lse;
+    a.B = k.B;
+    a.Hq = k.Hq;
+    a.Hkv = k.Hkv;
+    a.G = k.G;
+    a.R = k.R;
+    a.nk = (int)k.nc;
+    a.n_blk = k.n_blk;
+    a.n_units = (int)n_units;
+    a.inv_Hkv = k.Hkv >= 2 ? (unsigned)(((1ull << 32) + k.Hkv - 1) / k.Hkv) : 0u;
+    a.inv_B = k.B >= 2 ? (unsigned)(((1ull << 32) + k.B - 1) / k.B) : 0u;
+    a.scale_log2 = k.scale_log2;
+    const unsigned gy = (unsigned)(n_blocks < SB_GRID_Y ? n_blocks : SB_GRID_Y);
+    const unsigned gz = (unsigned)((n_blocks + SB_GRID_Y - 1) / SB_GRID_Y);
+    dim3 grid(8 * row_groups, gy, gz), block(SB_WAVES * 64);
+    if (d == 128) hipLaunchKernelGGL((sparse_batch_kernel<128>), grid, block, 0, stream, a);
+    else if (d == 64) hipLaunchKernelGGL((sparse_batch_kernel<64>), grid, block, 0, stream, a);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

@@ -429,6 +429,8 @@ def test_compacted_rows(oracle_mod, case):
     ("b8", 40, 8, 8, 128, 600, 16, 100, True),       # 320 units: more workgroups than CUs (the two-per-CU ring)
     ("b9", 70, 8, 4, 64, 2500, 8, 2100, False),       # ... at d = 64, and more index entries than LDS holds at a time
     ("b10", 2, 4, 2, 128, 5000, 32, 4200, True),     # the deep ring with two refills of the index entries
+    ("b11", 2, 4, 2, 128, 900, 64, 100, True),       # B = 64: the block's own rows fill the last two tiles
+    ("b12", 3, 8, 2, 64, 700, 32, 20, True),         # d = 64, one ragged tile of selected rows that the block's rows complete
 ])
 def test_batched_sparse_step(oracle_mod, case):
     """n_seq independent sequences in one launch equal the oracle's sparse step of every sequence."""
@@ -458,6 +460,32 @@ def test_batched_sparse_step(oracle_mod, case):
     mb.check(mb.mage_sparse_attn_batched(shape, n_seq, q, kc, vc, torch.from_numpy(idx).cuda(), kb, vb, out2, None), "batched")
     torch.cuda.synchronize()
     assert torch.equal(out.view(torch.int32), out2.view(torch.int32))
+
+
+def test_batched_sparse_step_with_more_units_than_one_grid_plane(oracle_mod):
+    """264000 (sequence, head) units: the blocks of eight units spill from the grid's y dimension into z.
+    Every output is written, and sequences on both sides of the boundary equal the oracle."""
+    import torch
+    import paper_2602_14209_amd.binding as mb
+    from gpu_util import check_out, to_device
+    from paper_2602_14209_amd.workloads import bf16_to_f32, round_to_bf16
+    n_seq, Hq, Hkv, d, L, B, k = 33000, 8, 8, 64, 8, 1, 3
+    rng = np.random.default_rng(77)
+    bf16_values = lambda shape: bf16_to_f32(round_to_bf16(rng.standard_normal(shape, dtype=np.float32)))
+    q, kc, vc = bf16_values((n_seq, B, Hq, d)), bf16_values((n_seq, L, Hkv, d)), bf16_values((n_seq, L, Hkv, d))
+    kb, vb = bf16_values((n_seq, B, Hkv, d)), bf16_values((n_seq, B, Hkv, d))
+    idx = np.sort(rng.permuted(np.tile(np.arange(L, dtype=np.int32), (n_seq, Hkv, 1)), axis=2)[:, :, :k], axis=2)
+    out = torch.full((n_seq, B, Hq, d), float("nan"), dtype=torch.float32, device="cuda")
+    lse = torch.full((n_seq, B, Hq), float("nan"), dtype=torch.float32, device="cuda")
+    shape = mb.make_shape(B, Hq, Hkv, d, L, k, "bf16")
+    print(f"[parity] batched sparse step, {n_seq * Hkv} units", flush=True)
+    mb.check(mb.mage_sparse_attn_batched(shape, n_seq, to_device(q, "bf16"), to_device(kc, "bf16"), to_device(vc, "bf16"),
+                                         torch.from_numpy(idx).cuda(), to_device(kb, "bf16"), to_device(vb, "bf16"), out, lse), "batched")
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all()) and bool(torch.isfinite(lse).all())
+    for s in (0, 12345, 32767, 32768, 32769, n_seq - 1):
+        o_ref, l_ref = oracle_mod.sparse_attn(q[s], kc[s], vc[s], idx[s], kb[s], vb[s])
+        check_out(out[s].cpu().numpy(), o_ref, lse[s].cpu().numpy(), l_ref, "bf16")
 
 
 @pytest.mark.parametrize("seed", list(range(12)))

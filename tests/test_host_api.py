@@ -91,6 +91,9 @@ def test_null_alignment_and_workspace_errors():
     assert L.mage_sparse_attn_batched(ctypes.byref(s), 2, fake, fake, fake, None, fake, fake, fake, None, None) == -1
     sf32 = mb.make_shape(32, 32, 8, 128, 4096, 512, "f32")
     assert L.mage_sparse_attn_batched(ctypes.byref(sf32), 2, fake, fake, fake, fake, fake, fake, fake, None, None) == -3
+    many_heads = mb.make_shape(32, 512, 512, 128, 4096, 512, "bf16")      # (n_seq*Hkv + 8)*Hkv >= 2^32
+    assert L.mage_sparse_attn_batched(ctypes.byref(many_heads), 60000, fake, fake, fake, fake, fake, fake, fake, None, None) == -3
+    assert L.mage_sparse_attn_batched(ctypes.byref(s), 65536, fake, fake, fake, fake, fake, fake, fake, None, None) == -2
     assert L.mage_step1(ctypes.byref(s), fake, fake, fake, fake, fake, fake, None, None, None, fake, big, None) == -1
     assert L.mage_step1(ctypes.byref(s), fake, fake, fake, fake, fake, fake, None, fake, None, fake, 16, None) == -4
     # the bf16 sparse step keeps its partials on chip and needs no workspace; the fp32 one does
