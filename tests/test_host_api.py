@@ -223,3 +223,12 @@ def test_binding_argument_counts_match_the_header():
         argtypes = getattr(lib, name).argtypes
         assert argtypes is not None or n == 0, name
         assert len(argtypes or []) == n, (name, n, len(argtypes or []))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "one GPU only" in r.stderr and r.stdout.strip() == ""
