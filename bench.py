@@ -61,8 +61,8 @@ def parse():
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build measures one GPU only (the path needs no exchange between GPUs; "
-              "see DESIGN.md for how it would shard). Run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build measures one GPU only (layers, sequences and KV heads are independent, so "
+              "several GPUs would each run this same path on their share). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
     import torch
 
