@@ -108,6 +108,8 @@ def _attention_only(oracle_mod, w, seed):
     ("w3", 40, 20, 64, 900, 56, 150),       # d = 64, unsplit
     ("w4", 8, 2, 128, 3000, 32, 1100),      # four per row tile and two passes over the key positions
     ("w5", 32, 16, 64, 700, 40, 700),       # d = 64, 80 workgroups: two per row tile, two passes, k = L
+    ("w6", 8, 2, 128, 4000, 32, 1500),      # three passes: the second finds its index entries already requested, the third asks for its own
+    ("w7", 4, 1, 128, 2000, 16, 660),       # 43 tiles: the second pass is almost as long as the first
 ])
 def test_sparse_channel_split_variants(oracle_mod, case):
     import torch
