@@ -139,6 +139,7 @@ void sparse_batch_kernel(const BatchArgs a)
     const u16 *unit_cache[UPW], *unit_blk[UPW];       // cache / block base pointer of each unit (scalar)
     int unit_row[UPW];                                // tile row this lane fetches in each unit
     unsigned unit_chunk[UPW];                         // its (swizzled) source chunk, in bytes
+    const unsigned char *unit_src[UPW];               // cache base + chunk: what a selected row's offset is added to
 #pragma unroll
     for (int n = 0; n < UPW; ++n) {
         const int u = n * NW + wave;
@@ -147,6 +148,7 @@ void sparse_batch_kernel(const BatchArgs a)
         unit_blk[n] = is_v ? vb : kb;
         unit_row[n] = (u % MAT_UNITS) * RPI + lane / CH;
         unit_chunk[n] = (unsigned)(((lane % CH) ^ (sb_swz(unit_row[n]) & (CH - 1))) * 16);
+        unit_src[n] = reinterpret_cast<const unsigned char *>(unit_cache[n]) + unit_chunk[n];
     }
     const unsigned lds_wave = __builtin_amdgcn_readfirstlane(lds_addr(smem) + wave * 1024);
     const unsigned stride_bytes = (unsigned)stride * 2u;
@@ -170,9 +172,20 @@ void sparse_batch_kernel(const BatchArgs a)
     };
     auto issue = [&](int t) {
         const unsigned dst = lds_wave + (unsigned)(t % NBUF) * BUF_BYTES;
+        // one wait for all entries, in one place: the registers an LDS read will write must not be named by any
+        // instruction before this (the compiler copies a register it is told an assembly statement modifies when the
+        // old value has a second reader, and such a copy would read too early)
+        static_for<UPW>([&](auto NI) { lds_wait<UPW - 1 - decltype(NI)::value>(ent[decltype(NI)::value]); });
+        if ((t + 1) * TK <= nk) {                        // uniform; nearly every tile: selected rows only, one multiply-add per request
+            static_for<UPW>([&](auto NI) {
+                constexpr int n = decltype(NI)::value;
+                const unsigned long long off = (unsigned long long)(unsigned)__builtin_bit_cast(int, ent[n]) * stride_bytes;
+                __builtin_amdgcn_global_load_lds(MAGE_GLOBAL_PTR(unit_src[n] + off), MAGE_LDS_ADDR(dst + n * NW * 1024), 16, 0, 0);
+            });
+            return;
+        }
         static_for<UPW>([&](auto NI) {
             constexpr int n = decltype(NI)::value;
-            lds_wait<UPW - 1 - n>(ent[n]);
             int p = t * TK + unit_row[n];
             p = p < n_keys ? p : n_keys - 1;
             const bool cache = p < nk;

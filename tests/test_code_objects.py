@@ -13,7 +13,11 @@ compiler or flag change could silently break:
   hundreds of instructions at the top of every kernel (csrc/ids.hpp has the register reads);
 * a scalar register written by a vector instruction (v_readfirstlane / v_readlane) is not used as the
   base of a vector-memory instruction before five wait states have passed -- the compiler inserts the
-  wait states for its own instructions, but cannot for a load written as inline assembly.
+  wait states for its own instructions, but cannot for a load written as inline assembly;
+* no instruction names a vector register that an LDS read or a vector-memory load still in flight is
+  going to write before the s_waitcnt that covers it: around loads written as inline assembly the
+  compiler may still place a register copy (it did once: a copy of an index entry ahead of the wait
+  gave wrong rows in one parity case), and nothing in the hardware holds such an instruction back.
 """
 import os
 import re
@@ -78,6 +82,59 @@ def _sgpr_hazards(ins):
             states += int(nop.group(1)) + 1 if nop else 1
             if states >= 5:
                 break
+    return bad
+
+
+def _vregs(tok):
+    m = re.fullmatch(r"v\[(\d+):(\d+)\]", tok)
+    if m:
+        return set(range(int(m.group(1)), int(m.group(2)) + 1))
+    m = re.fullmatch(r"v(\d+)", tok)
+    return {int(m.group(1))} if m else set()
+
+
+def _early_uses(ins):
+    """Instructions that name a vector register which an LDS read or a vector-memory load still in flight
+    will write, ahead of the s_waitcnt that covers that load.  The hardware does not interlock these: the
+    instruction would see the old contents.  (The kernels issue such loads from inline assembly and place
+    the waits by hand; what the compiler does around them -- a register copy, a hoisted use -- is not
+    visible in the source.)  Linear scan: branches fall through, the in-flight lists are dropped at
+    unconditional branches; returns are in order per counter, so a younger load of the same counter
+    may reuse a destination."""
+    lgkm, vm, bad = [], [], []               # operations in flight, oldest first: their destination VGPRs (may be none)
+    for s in ins:
+        op = s.split()[0]
+        ops = [x.strip() for x in s.split(None, 1)[1].split(",")] if " " in s else []
+        regs = [_vregs(o.split()[0]) if o else set() for o in ops]
+        is_lgkm = op.startswith("ds_") or op.startswith("s_load") or op.startswith("s_buffer_load")
+        is_vm = bool(re.match(r"(global|buffer|flat|scratch)_", op))
+        dest = set()
+        if op.startswith("ds_") and re.match(r"ds_(read|load|bpermute|permute|swizzle)|ds_.*_rtn", op):
+            dest = regs[0]
+        if is_vm and "load" in op and "lds" not in op:
+            dest = regs[0]
+        for queue, mine in ((lgkm, is_lgkm), (vm, is_vm)):
+            for i, r in enumerate(regs):
+                if mine and i == 0 and dest:      # a younger load into the same register: lands later, in order
+                    continue
+                if any(d & r for d in queue):
+                    bad.append(s)
+        if op == "s_waitcnt":
+            m = re.search(r"lgkmcnt\((\d+)\)", s)
+            if m:
+                del lgkm[:len(lgkm) - int(m.group(1))]
+            m = re.search(r"vmcnt\((\d+)\)", s)
+            if m:
+                del vm[:len(vm) - int(m.group(1))]
+        elif is_lgkm:
+            lgkm.append(dest)
+        elif is_vm:
+            vm.append(dest)
+            if op.startswith("flat_"):
+                lgkm.append(set())
+        elif op in ("s_endpgm", "s_branch", "s_setpc_b64"):
+            lgkm.clear()
+            vm.clear()
     return bad
 
 
@@ -176,3 +233,21 @@ def test_hazard_scan_notices_a_planted_hazard():
     assert _sgpr_hazards(ins)
     ok = ins[:3] + ["s_nop 4"] + ins[3:]
     assert not _sgpr_hazards(ok)
+
+
+def test_no_register_is_named_before_the_wait_that_covers_its_load(objects):
+    for _, kernels in objects.values():
+        for sym, ins in kernels.items():
+            bad = _early_uses(ins)
+            assert not bad, (_demangle(sym), bad[:3])
+
+
+def test_early_use_scan_notices_a_planted_copy():
+    ins = ["ds_read_b32 v27, v23", "ds_read_b32 v26, v23", "v_mov_b32_e32 v18, v27", "s_waitcnt lgkmcnt(1)",
+           "v_mad_u64_u32 v[18:19], s[4:5], v18, s22, v[70:71]"]
+    assert _early_uses(ins) == ["v_mov_b32_e32 v18, v27"]
+    ok = [ins[0], ins[1], ins[3], "v_mov_b32_e32 v18, v27", "s_waitcnt lgkmcnt(0)", "v_mov_b32_e32 v19, v26"]
+    assert not _early_uses(ok)
+    late = ["global_load_dword v5, v[2:3], off", "global_load_dword v6, v[2:3], off", "s_waitcnt vmcnt(1)", "v_add_u32_e32 v7, v5, v6"]
+    assert _early_uses(late) == ["v_add_u32_e32 v7, v5, v6"]
+
