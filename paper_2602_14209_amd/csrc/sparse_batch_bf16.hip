@@ -68,6 +68,15 @@ constexpr int SB_GRID_Y = 32768;            // workgroup id: x = place inside a 
 // read and the 8 rows of one phase of a transposing V read land on distinct LDS banks.
 __device__ __forceinline__ int sb_swz(int r) { return ((r & 7) << 1) | ((r >> 3) & 1); }
 
+// Tile t has landed once at most N younger row requests of this wavefront are in flight; every LDS read issued so far
+// has returned.  a, b: the index-entry registers (the same one twice where a wavefront has a single entry).
+template <int N>
+__device__ __forceinline__ void sb_tile_wait(float &a, float &b)
+{
+    if (&a == &b) asm volatile("s_waitcnt vmcnt(%1) lgkmcnt(0)" : "+v"(a) : "n"(N) : "memory");
+    else asm volatile("s_waitcnt vmcnt(%2) lgkmcnt(0)" : "+v"(a), "+v"(b) : "n"(N) : "memory");
+}
+
 template <int D>
 __global__ __launch_bounds__(SB_WAVES * 64) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void sparse_batch_kernel(const BatchArgs a)
@@ -170,12 +179,15 @@ void sparse_batch_kernel(const BatchArgs a)
             ent[n] = lds_read_f32<0>(idx_addr + (unsigned)p * 4);
         }
     };
+    // wait for the entries just requested: one wait for all of them, in one place -- the registers an LDS read will
+    // write must not be named by any instruction before it (the compiler copies a register it is told an assembly
+    // statement modifies when the old value has a second reader, and such a copy would read too early)
+    auto await_entries = [&] {
+        static_for<UPW>([&](auto NI) { lds_wait<UPW - 1 - decltype(NI)::value>(ent[decltype(NI)::value]); });
+    };
+    // request tile t's rows; its entries have landed (await_entries, or the wait at the top of a loop iteration)
     auto issue = [&](int t) {
         const unsigned dst = lds_wave + (unsigned)(t % NBUF) * BUF_BYTES;
-        // one wait for all entries, in one place: the registers an LDS read will write must not be named by any
-        // instruction before this (the compiler copies a register it is told an assembly statement modifies when the
-        // old value has a second reader, and such a copy would read too early)
-        static_for<UPW>([&](auto NI) { lds_wait<UPW - 1 - decltype(NI)::value>(ent[decltype(NI)::value]); });
         if ((t + 1) * TK <= nk) {                        // uniform; nearly every tile: selected rows only, one multiply-add per request
             static_for<UPW>([&](auto NI) {
                 constexpr int n = decltype(NI)::value;
@@ -213,6 +225,7 @@ void sparse_batch_kernel(const BatchArgs a)
 #pragma clang loop unroll(disable)
     for (int j = 0; j < NBUF - 1 && j < ntiles; ++j) {
         request_entries(j);
+        await_entries();
         issue(j);
     }
     request_entries(NBUF - 1);
@@ -253,35 +266,46 @@ void sparse_batch_kernel(const BatchArgs a)
         constexpr int BLK = 16 * ROW_BYTES;
         const unsigned koff = (unsigned)(t % NBUF) * BUF_BYTES, voff = koff + MAT_BYTES;
         // tile t has landed; NBUF-2 younger tiles may still be in flight; everyone is done with tile t-1
-        if (t + NBUF - 2 < ntiles) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((NBUF - 2) * UPW) : "memory");
-        else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        // (the wait names the entry registers: what reads them below depends on it and cannot be moved above it)
+        if (t + NBUF - 2 < ntiles) sb_tile_wait<(NBUF - 2) * UPW>(ent[0], ent[UPW - 1]);
+        else sb_tile_wait<0>(ent[0], ent[UPW - 1]);
         __syncthreads();
+        // ---- scores: sc[b][v] = S^T(key 16*b + 4*lg4 + v of the tile, query row l16) ----
+        // The two key blocks accumulate alternately (two independent chains of MFMAs); the fragments are
+        // read in batches of KB k-steps (registers: four wavefronts share a SIMD).  The first batch is
+        // requested before the next tile's rows are, so that those requests (all wavefronts issue theirs at
+        // the same moment, right after the barrier) are made while the fragments travel.
+        constexpr int KB = KS < 2 ? KS : 2;
+        u32x4_t kf[KB][2];
+        auto read_k = [&](auto BT) {
+            constexpr int k0 = decltype(BT)::value * KB;
+            static_for<KB>([&](auto S) {
+                constexpr int i = decltype(S)::value;
+                kf[i][0] = lds_read_b128<0>(kaddr[k0 + i] + koff);
+                kf[i][1] = lds_read_b128<BLK>(kaddr[k0 + i] + koff);
+            });
+        };
+        if (wave_active) read_k(std::integral_constant<int, 0>{});
         const int tn = t + NBUF - 1;                      // goes into the slot tile t-1 has just left
         if (tn < ntiles) {
             if (tn + 1 > idx_t0 + SB_IDX_TILES && tn * TK < nk) {                 // uniform; rare (k > 2048)
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                // the fragment reads above read LDS, too
                 idx_t0 = tn;
                 load_idx(tn);
                 __syncthreads();
                 request_entries(tn);
+                await_entries();
             }
             issue(tn);
             request_entries(tn + 1);                      // lands while this tile is computed; waited for at the next barrier
         }
         if (!wave_active) return;
         const int valid = n_keys - t * TK;                // >= 1
-        // ---- scores: sc[b][v] = S^T(key 16*b + 4*lg4 + v of the tile, query row l16) ----
-        // The two key blocks accumulate alternately (two independent chains of MFMAs); the fragments are
-        // read in batches of KB k-steps (registers: four wavefronts share a SIMD).
-        constexpr int KB = KS < 2 ? KS : 2;
         f32x4_t sc[2] = {f32x4_t{0.f, 0.f, 0.f, 0.f}, f32x4_t{0.f, 0.f, 0.f, 0.f}};
         static_for<KS / KB>([&](auto BT) {
             constexpr int k0 = decltype(BT)::value * KB;
-            u32x4_t kf[KB][2];
-            static_for<KB>([&](auto S) {
-                constexpr int i = decltype(S)::value;
-                kf[i][0] = lds_read_b128<0>(kaddr[k0 + i] + koff);
-                kf[i][1] = lds_read_b128<BLK>(kaddr[k0 + i] + koff);
-            });
+            // (the waits of the first batch count the entry reads behind it as if they were fragments: they only wait longer)
+            if constexpr (k0 > 0) read_k(BT);
             static_for<KB>([&](auto S) {
                 constexpr int i = decltype(S)::value;
                 static_for<2>([&](auto BI) {
